@@ -1,0 +1,253 @@
+"""ctypes access to the C++ oracle (numpy arrays in, numpy arrays out).
+
+Test infrastructure: see the header of gosh_oracle.cpp.  The library is built by
+``oracle/build.py``; it is loaded lazily and built on first use if missing.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        L = C.CDLL(path)
+        u32p, i32p, i64p, f32p = (C.POINTER(C.c_uint32), C.POINTER(C.c_int32),
+                                  C.POINTER(C.c_int64), C.POINTER(C.c_float))
+        L.orc_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.orc_philox4x32_10.restype = None
+        L.orc_draw.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.orc_draw.restype = C.c_uint64
+        L.orc_bounded.argtypes = [C.c_uint64, C.c_uint64]
+        L.orc_bounded.restype = C.c_uint64
+        L.orc_sample_epoch.argtypes = [C.c_int64, i64p, i32p, C.c_int32, C.c_uint64,
+                                       C.c_uint32, C.c_uint32, i32p]
+        L.orc_sample_epoch.restype = None
+        L.orc_sample_source.argtypes = [C.c_int64, i64p, i32p, C.c_int32, C.c_uint64,
+                                        C.c_uint32, C.c_uint32, C.c_int64, i32p]
+        L.orc_sample_source.restype = None
+        L.orc_update.argtypes = [f32p, f32p, C.c_int32, C.c_int32, C.c_float]
+        L.orc_update.restype = None
+        L.orc_lr.argtypes = [C.c_float, C.c_int64, C.c_int64]
+        L.orc_lr.restype = C.c_float
+        L.orc_train_epoch.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
+                                      C.c_float, C.c_uint64, C.c_uint32, C.c_uint32]
+        L.orc_train_epoch.restype = None
+        L.orc_train_level.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
+                                      C.c_float, C.c_int64, C.c_uint64, C.c_uint32]
+        L.orc_train_level.restype = None
+        L.orc_init_embedding.argtypes = [f32p, C.c_int64, C.c_int32, C.c_uint64, C.c_uint32]
+        L.orc_init_embedding.restype = None
+        L.orc_project.argtypes = [f32p, i32p, C.c_int64, C.c_int32, f32p]
+        L.orc_project.restype = None
+        L.orc_epoch_split.argtypes = [C.c_int64, C.c_double, C.c_int32, i64p]
+        L.orc_epoch_split.restype = C.c_int
+        L.orc_coarsen_map.argtypes = [C.c_int64, i64p, i32p, i32p]
+        L.orc_coarsen_map.restype = C.c_int64
+        L.orc_coarsen_graph.argtypes = [C.c_int64, i64p, i32p, i64p, i32p, C.c_int64,
+                                        i64p, i32p, i64p]
+        L.orc_coarsen_graph.restype = C.c_int64
+        L.orc_pair_order.argtypes = [C.c_int32, i32p, i32p]
+        L.orc_pair_order.restype = C.c_int64
+        L.orc_train_pair.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
+                                     C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                     C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, i32p]
+        L.orc_train_pair.restype = None
+        L.orc_rotations.argtypes = [C.c_int64, C.c_int32, C.c_int32]
+        L.orc_rotations.restype = C.c_int64
+        L.orc_train_parts.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
+                                      C.c_int64, C.c_float, C.c_uint64, C.c_uint32, C.c_int32,
+                                      C.c_int32]
+        L.orc_train_parts.restype = None
+        _lib = L
+    return _lib
+
+
+def _p(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype)) if a is not None else None
+
+
+def _csr(xadj, adj):
+    xadj = np.ascontiguousarray(np.asarray(xadj), dtype=np.int64)
+    adj = np.ascontiguousarray(np.asarray(adj), dtype=np.int32)
+    return xadj, adj
+
+
+def philox(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(c, C.c_uint32), _p(k, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def draw(seed, src, j, epoch, level):
+    return int(lib().orc_draw(seed, src, j, epoch, level))
+
+
+def bounded(r, bound):
+    return int(lib().orc_bounded(r, bound))
+
+
+def sample_epoch(xadj, adj, k, seed, epoch, level):
+    xadj, adj = _csr(xadj, adj)
+    n = xadj.size - 1
+    out = np.empty((n, k + 1), dtype=np.int32)
+    lib().orc_sample_epoch(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), k, seed, epoch, level,
+                           _p(out, C.c_int32))
+    return out
+
+
+def sample_source(xadj, adj, k, seed, epoch, level, src):
+    xadj, adj = _csr(xadj, adj)
+    out = np.empty(k + 1, dtype=np.int32)
+    lib().orc_sample_source(xadj.size - 1, _p(xadj, C.c_int64), _p(adj, C.c_int32), k, seed,
+                            epoch, level, src, _p(out, C.c_int32))
+    return out
+
+
+def update(m_v, m_sample, b, lr):
+    """Apply Alg. 1 in place to two fp32 rows (numpy arrays)."""
+    assert m_v.dtype == np.float32 and m_sample.dtype == np.float32
+    lib().orc_update(_p(m_v, C.c_float), _p(m_sample, C.c_float), m_v.size, b, lr)
+
+
+def lr(lr0, j, e_i):
+    return float(lib().orc_lr(lr0, j, e_i))
+
+
+def train_epoch(xadj, adj, M, k, lr_epoch, seed, epoch, level):
+    """One sequential epoch, in place on the fp32 matrix M (n x d, C-contiguous)."""
+    xadj, adj = _csr(xadj, adj)
+    assert M.dtype == np.float32 and M.flags.c_contiguous
+    n, d = M.shape
+    assert n == xadj.size - 1
+    lib().orc_train_epoch(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
+                          lr_epoch, seed, epoch, level)
+
+
+def train_level(xadj, adj, M, k, lr0, e_i, seed, level):
+    xadj, adj = _csr(xadj, adj)
+    assert M.dtype == np.float32 and M.flags.c_contiguous
+    n, d = M.shape
+    lib().orc_train_level(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
+                          lr0, e_i, seed, level)
+
+
+def init_embedding(n, d, seed, level):
+    M = np.empty((n, d), dtype=np.float32)
+    lib().orc_init_embedding(_p(M, C.c_float), n, d, seed, level)
+    return M
+
+
+def project(M_coarse, map_):
+    map_ = np.ascontiguousarray(map_, dtype=np.int32)
+    assert M_coarse.dtype == np.float32 and M_coarse.flags.c_contiguous
+    out = np.empty((map_.size, M_coarse.shape[1]), dtype=np.float32)
+    lib().orc_project(_p(M_coarse, C.c_float), _p(map_, C.c_int32), map_.size,
+                      M_coarse.shape[1], _p(out, C.c_float))
+    return out
+
+
+def epoch_split(e, p, D):
+    out = np.zeros(D, dtype=np.int64)
+    rc = lib().orc_epoch_split(e, p, D, _p(out, C.c_int64))
+    if rc != 0:
+        raise ValueError("epoch budget cannot cover every level")
+    return out
+
+
+def coarsen_map(xadj, adj):
+    xadj, adj = _csr(xadj, adj)
+    n = xadj.size - 1
+    m = np.empty(n, dtype=np.int32)
+    nc = lib().orc_coarsen_map(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(m, C.c_int32))
+    return m, int(nc)
+
+
+def coarsen_graph(xadj, adj, map_, n_coarse, mult=None):
+    xadj, adj = _csr(xadj, adj)
+    n = xadj.size - 1
+    map_ = np.ascontiguousarray(map_, dtype=np.int32)
+    if mult is not None:
+        mult = np.ascontiguousarray(mult, dtype=np.int64)
+    nnz = lib().orc_coarsen_graph(n, _p(xadj, C.c_int64), _p(adj, C.c_int32),
+                                  _p(mult, C.c_int64), _p(map_, C.c_int32), n_coarse,
+                                  None, None, None)
+    xo = np.zeros(n_coarse + 1, dtype=np.int64)
+    ao = np.zeros(nnz, dtype=np.int32)
+    mo = np.zeros(nnz, dtype=np.int64)
+    lib().orc_coarsen_graph(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(mult, C.c_int64),
+                            _p(map_, C.c_int32), n_coarse, _p(xo, C.c_int64),
+                            _p(ao, C.c_int32), _p(mo, C.c_int64))
+    return xo, ao, mo
+
+
+def coarsen(xadj, adj, threshold=100, min_shrink=0.8, max_levels=64):
+    """Alg. 4 outer loop.  READING (stop rule): build G_{i+1} while |V_i| > threshold;
+    after building it, stop if |V_{i+1}| > min_shrink * |V_i| (the level barely
+    shrank) or |V_{i+1}| == |V_i| (no progress at all, e.g. only isolated vertices
+    are left); that level is still kept as the last one.  max_levels caps the
+    number of graphs.
+    Returns (graphs, maps, mults): graphs[i] = (xadj, adj) of G_i, maps[i]: V_i -> V_{i+1}."""
+    xadj, adj = _csr(xadj, adj)
+    graphs, maps, mults = [(xadj, adj)], [], [np.ones(adj.size, dtype=np.int64)]
+    while graphs[-1][0].size - 1 > threshold and len(graphs) < max_levels:
+        x, a = graphs[-1]
+        n = x.size - 1
+        m, nc = coarsen_map(x, a)
+        xo, ao, mo = coarsen_graph(x, a, m, nc, mults[-1])
+        graphs.append((xo, ao))
+        maps.append(m)
+        mults.append(mo)
+        if nc > min_shrink * n or nc == n:
+            break
+    return graphs, maps, mults
+
+
+def pair_order(K):
+    npairs = K * (K + 1) // 2
+    a = np.zeros(npairs, dtype=np.int32)
+    b = np.zeros(npairs, dtype=np.int32)
+    cnt = lib().orc_pair_order(K, _p(a, C.c_int32), _p(b, C.c_int32))
+    assert cnt == npairs
+    return list(zip(a.tolist(), b.tolist()))
+
+
+def rotations(e_i, B, K):
+    return int(lib().orc_rotations(e_i, B, K))
+
+
+def train_pair(xadj, adj, M, k, B, K, pa, pb, lr_, seed, rotation, level, pair_index,
+               want_stream=False):
+    xadj, adj = _csr(xadj, adj)
+    n, d = M.shape
+    stream = None
+    if want_stream:
+        ps = (n + K - 1) // K
+        cnt = 0
+        for part in ([pa] if pa == pb else [pa, pb]):
+            lo = min(n, part * ps)
+            cnt += min(n, lo + ps) - lo
+        stream = np.full(cnt * B * (k + 1), -2, dtype=np.int32)
+    lib().orc_train_pair(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k, B,
+                         K, pa, pb, lr_, seed, rotation, level, pair_index,
+                         _p(stream, C.c_int32))
+    return stream
+
+
+def train_parts(xadj, adj, M, k, e_i, lr0, seed, level, K, B):
+    xadj, adj = _csr(xadj, adj)
+    n, d = M.shape
+    lib().orc_train_parts(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
+                          e_i, lr0, seed, level, K, B)

@@ -1,0 +1,124 @@
+"""Pins for the oracle's random draws and index mapping (no GPU)."""
+import os
+import random
+import subprocess
+
+import numpy as np
+import pytest
+import scipy.stats
+
+from oracle import gosh_oracle as O
+from tests.util import csr_from_pairs
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.fixture(scope="module")
+def aten_philox(tmp_path_factory):
+    """Independent Philox4x32-10: ATen's header-only engine compiled into a tiny CLI."""
+    import torch
+
+    inc = os.path.join(os.path.dirname(torch.__file__), "include")
+    exe = str(tmp_path_factory.mktemp("pin") / "pin_philox_aten")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-I" + inc,
+                    os.path.join(HERE, "pin_philox_aten.cpp"), "-o", exe], check=True)
+
+    def run(triples):
+        text = "".join(f"{s} {q} {o}\n" for s, q, o in triples)
+        out = subprocess.run([exe], input=text, capture_output=True, text=True, check=True)
+        rows = [list(map(int, line.split())) for line in out.stdout.strip().splitlines()]
+        assert len(rows) == len(triples)
+        return rows
+
+    return run
+
+
+def test_philox_matches_independent_engine(aten_philox):
+    rnd = random.Random(7)
+    edge = [0, 1, 2 ** 32 - 1, 2 ** 32, 2 ** 64 - 1]
+    triples = [(s, q, o) for s in edge for q in edge[:3] for o in edge[:4]]
+    triples += [(rnd.getrandbits(64), rnd.getrandbits(64), rnd.getrandbits(64))
+                for _ in range(300)]
+    ref = aten_philox(triples)
+    for (seed, subseq, offset), want in zip(triples, ref):
+        ctr = [offset & 0xFFFFFFFF, offset >> 32, subseq & 0xFFFFFFFF, subseq >> 32]
+        key = [seed & 0xFFFFFFFF, seed >> 32]
+        got = O.philox(ctr, key).tolist()
+        assert got == want, (seed, subseq, offset)
+
+
+def test_draw_keying(aten_philox):
+    """draw(seed, src, j, epoch, level) = words 0,1 of the block with counter
+    (src, j, epoch, level) and key (seed_lo, seed_hi)."""
+    rnd = random.Random(11)
+    cases = [(rnd.getrandbits(64), rnd.getrandbits(31), rnd.randrange(16),
+              rnd.getrandbits(31), rnd.randrange(64)) for _ in range(200)]
+    cases += [(1, 0, 0, 0, 0), (1, 1, 0, 0, 0), (1, 0, 1, 0, 0), (1, 0, 0, 1, 0), (1, 0, 0, 0, 1)]
+    triples = [(seed, epoch | (level << 32), src | (j << 32))
+               for seed, src, j, epoch, level in cases]
+    ref = aten_philox(triples)
+    seen = set()
+    for (seed, src, j, epoch, level), want in zip(cases, ref):
+        got = O.draw(seed, src, j, epoch, level)
+        assert got == want[0] | (want[1] << 32)
+        seen.add(got)
+    assert len(seen) == len(cases)  # every counter word matters
+
+
+def test_bounded_is_multiply_high():
+    rnd = random.Random(3)
+    cases = [(0, 1), (2 ** 64 - 1, 1), (2 ** 64 - 1, 2 ** 31 - 1), (2 ** 63, 2), (2 ** 63 - 1, 2),
+             (0, 2 ** 31 - 1), (2 ** 64 - 1, 2 ** 63)]
+    cases += [(rnd.getrandbits(64), rnd.randrange(1, 2 ** 40)) for _ in range(1000)]
+    for r, bound in cases:
+        got = O.bounded(r, bound)
+        assert got == (r * bound) >> 64
+        assert 0 <= got < bound
+
+
+def test_negatives_uniform_chi_square():
+    n, k = 48, 3
+    xadj, adj = csr_from_pairs(n, [(i, (i + 1) % n) for i in range(n)])
+    counts = np.zeros(n)
+    for epoch in range(200):
+        s = O.sample_epoch(xadj, adj, k, seed=5, epoch=epoch, level=0)
+        assert s[:, 1:].min() >= 0 and s[:, 1:].max() < n
+        counts += np.bincount(s[:, 1:].ravel(), minlength=n)
+    chi = scipy.stats.chisquare(counts)
+    assert chi.pvalue > 1e-3, chi
+    # the draws of different sample slots are not copies of each other
+    s0 = O.sample_epoch(xadj, adj, k, seed=5, epoch=0, level=0)
+    assert not np.array_equal(s0[:, 1], s0[:, 2])
+
+
+def test_positives_are_neighbours_and_uniform():
+    # vertex 0 has 12 neighbours, vertex 13 is isolated
+    n = 14
+    xadj, adj = csr_from_pairs(n, [(0, i) for i in range(1, 13)])
+    counts = np.zeros(n)
+    for epoch in range(3000):
+        s = O.sample_epoch(xadj, adj, 1, seed=9, epoch=epoch, level=2)
+        for v in range(n):
+            pos = s[v, 0]
+            if xadj[v + 1] == xadj[v]:
+                assert pos == -1
+            else:
+                assert pos in adj[xadj[v]:xadj[v + 1]]
+        counts[s[0, 0]] += 1
+    assert counts[0] == 0 and counts[13] == 0
+    chi = scipy.stats.chisquare(counts[1:13])
+    assert chi.pvalue > 1e-3, chi
+
+
+def test_stream_depends_on_seed_epoch_level():
+    n = 32
+    xadj, adj = csr_from_pairs(n, [(i, (i + 1) % n) for i in range(n)] +
+                               [(i, (i + 5) % n) for i in range(n)])
+    base = O.sample_epoch(xadj, adj, 3, seed=1, epoch=0, level=0)
+    assert np.array_equal(base, O.sample_epoch(xadj, adj, 3, seed=1, epoch=0, level=0))
+    for kw in (dict(seed=2, epoch=0, level=0), dict(seed=1, epoch=1, level=0),
+               dict(seed=1, epoch=0, level=1), dict(seed=1 + 2 ** 32, epoch=0, level=0)):
+        assert not np.array_equal(base, O.sample_epoch(xadj, adj, 3, **kw))
+    # per-source sampling agrees with the whole-epoch stream
+    for src in (0, 7, 31):
+        assert np.array_equal(base[src], O.sample_source(xadj, adj, 3, 1, 0, 0, src))

@@ -1,0 +1,50 @@
+"""Helpers shared by the tests (graph fixtures, small numpy utilities)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import graphgen
+
+
+def csr_from_pairs(n, pairs):
+    """Sorted symmetric CSR (int64 xadj, int32 adj) from undirected (u, v) pairs."""
+    nbrs = [set() for _ in range(n)]
+    for u, v in pairs:
+        if u == v:
+            continue
+        nbrs[u].add(v)
+        nbrs[v].add(u)
+    xadj = np.zeros(n + 1, dtype=np.int64)
+    adj = []
+    for v in range(n):
+        row = sorted(nbrs[v])
+        adj.extend(row)
+        xadj[v + 1] = len(adj)
+    return xadj, np.asarray(adj, dtype=np.int32)
+
+
+def csr_numpy(csr: graphgen.CSR):
+    return (csr.xadj.cpu().numpy().astype(np.int64), csr.adj.cpu().numpy().astype(np.int32))
+
+
+def dense_from_csr(xadj, adj):
+    n = xadj.size - 1
+    A = np.zeros((n, n), dtype=np.int64)
+    for v in range(n):
+        A[v, adj[xadj[v]:xadj[v + 1]]] = 1
+    return A
+
+
+def config1_graph(seed=1, holdout=0.1):
+    """Config 1: 1,024 vertices, 8,192 uniform-endpoint draws, 10 % of edges held out."""
+    edges = graphgen.er_gnm(1024, 8192, seed)
+    train, test = graphgen.holdout_split(edges, holdout, seed + 1000)
+    return 1024, train, test
+
+
+def rel_err(a, b):
+    """max |a - b| / max |b| -- the relative error the parity bar is stated in."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30))
