@@ -8,18 +8,18 @@ from tests.linkpred import aucroc, make_eval_sets
 
 
 def test_oracle_embedding_predicts_links_on_rmat():
-    n = 1 << 11
-    edges = graphgen.rmat(11, 1 << 15, seed=2)
+    n = 1 << 12
+    edges = graphgen.rmat(12, 1 << 16, seed=2)
     train, test = graphgen.holdout_split(edges, 0.1, 1002)
     csr = graphgen.to_csr(n, train)
     xadj, adj = csr.xadj.numpy().astype(np.int64), csr.adj.numpy()
     sets = make_eval_sets(n, train.numpy(), test.numpy(), seed=1)
     M = O.init_embedding(n, 32, 1, 0)
     held0, fit0 = aucroc(M, sets)
-    O.train_level(xadj, adj, M, 3, 0.045, 200, 1, 0)
+    O.train_level(xadj, adj, M, 3, 0.045, 300, 1, 0)
     held, fit = aucroc(M, sets)
     assert abs(held0 - 0.5) < 0.06  # the random initialisation knows nothing
-    assert held > 0.75 and fit > 0.85, (held, fit)
+    assert held > 0.75 and fit > 0.9, (held, fit)
 
 
 def test_uniform_random_graph_has_no_held_out_signal():
