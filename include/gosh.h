@@ -1,0 +1,115 @@
+/* libgosh -- MI355X (gfx950) implementation of the GOSH graph-embedding training
+ * path (Akyildiz, Aljundi, Kaya, "GOSH: Embedding Big Graphs on Small Hardware",
+ * ICPP'20).  Plain C ABI: raw pointers and sizes only.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers
+ *     are ordinary host memory.  The library never frees or keeps caller arrays.
+ *   - Graphs are CSR (Sec. 3.2.1 of the paper): adj holds the neighbour lists back to
+ *     back, xadj holds n+1 offsets into it, xadj[n] == nnz.  Rows must be sorted
+ *     ascending, without duplicates or self loops (gosh_csr_validate checks a host
+ *     copy; the device entry points trust the caller).
+ *   - The embedding matrix M is n x d, row-major fp32, 16-byte aligned, d a multiple
+ *     of 4 with 4 <= d <= 512.
+ *   - Every function returns GOSH_OK (0) or a negative gosh_status; the message of the
+ *     last failure on the calling thread is returned by gosh_last_error().  No
+ *     exception crosses this boundary.
+ *   - Device entry points are asynchronous: they enqueue work on the given HIP
+ *     stream (a hipStream_t passed as void*, NULL = the default stream) and return.
+ *     Faults inside a kernel surface at the caller's next synchronisation.
+ */
+#ifndef GOSH_H
+#define GOSH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GOSH_OK = 0,
+  GOSH_EINVAL = -1,  /* an argument violates a documented precondition */
+  GOSH_ENOMEM = -2,  /* host or device allocation failed */
+  GOSH_EHIP = -3,    /* a HIP runtime call failed */
+  GOSH_EBUDGET = -4  /* device budget too small for the requested part layout */
+} gosh_status;
+
+/* Borrowed view of a CSR graph.  All three arrays live on the same side (host or
+ * device) as the entry point documents. */
+typedef struct {
+  int64_t n;          /* |V| : 1 <= n < 2^31 - 1 */
+  int64_t nnz;        /* length of adj (= 2|E| for a symmetrised graph) */
+  const void *xadj;   /* n+1 offsets; int32_t* if xadj_is64 == 0, else int64_t* */
+  const int32_t *adj; /* neighbour ids */
+  int32_t xadj_is64;
+} gosh_csr;
+
+#define GOSH_MAX_DIM 512
+#define GOSH_MAX_NEG 15
+
+/* gosh_train_epoch flags */
+#define GOSH_FLAG_SEQUENTIAL 1u /* debug: one wavefront walks the sources in ascending
+                                   id, giving the sequential-order result */
+
+const char *gosh_last_error(void);
+
+/* ---- schedule helpers (host, pure) ------------------------------------------------ */
+
+/* Learning rate of epoch j (0-based) out of e_i at one level: lr0 * max(1 - j/e_i, 1e-4)
+ * (Sec. 3, last paragraph before Alg. 2; Alg. 3 first line of the epoch loop).
+ * Evaluated in double, rounded once.  Returns 0 if e_i <= 0. */
+float gosh_lr(float lr0, int64_t j, int64_t e_i);
+
+/* Epoch budget per level ("calculateEpochs", Sec. 3 paragraph on the smoothing ratio
+ * p): a share p of e evenly over the D levels, the rest geometrically with each level
+ * getting half of the next coarser one.  exact_i = p*e/D + (1-p)*e*2^i/(2^D-1); levels
+ * i >= 1 get max(1, floor(exact_i)), level 0 the remainder, so sum(e_i) == e.
+ * e_i: host array of D entries (written).  GOSH_EINVAL if D < 1, D > 62, p outside
+ * [0,1] or e cannot give every level one epoch. */
+int gosh_epoch_split(int64_t e, double p, int32_t D, int64_t *e_i);
+
+/* ---- device entry points ---------------------------------------------------------- */
+
+/* "Randomly initialize M" (Alg. 2, second line).  Fills the device matrix M (n x d)
+ * with values uniform in [-0.5/d, 0.5/d): entry (v, c) is word c%4 of
+ * Philox4x32-10(counter = (v, c/4, 0xFFFFFFFF, level), key = seed), mapped as
+ * ((w >> 8) * 2^-24 - 0.5) / d. */
+int gosh_init_embedding(float *M_dev, int64_t n, int32_t d, uint64_t seed, uint32_t level,
+                        void *hip_stream);
+
+/* The sampler of Alg. 3 on its own (parity/debug): for every source src writes
+ * out[src*(k_neg+1) + j], j = 0..k_neg.  j = 0 is the positive sample, a uniform member
+ * of the neighbour list of src (Sec. 3.1; -1 if the list is empty); j >= 1 are the
+ * negative samples, uniform over all n vertices.  Draw j of src is the low 64 bits of
+ * Philox4x32-10(counter = (src, j, epoch, level), key = seed), reduced to an index
+ * by multiply-high with the bound.  g_dev: CSR arrays on the device (the struct
+ * itself on the host).  out_dev: device int32[n*(k_neg+1)]. */
+int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint32_t epoch,
+                      uint32_t level, int32_t *out_dev, void *hip_stream);
+
+/* One epoch of Alg. 3 ("TrainInGPU"): every vertex is the source of one positive and
+ * k_neg negative updates of Alg. 1 ("UpdateEmbedding"), applied in that order:
+ *   g = lr_epoch * (b - sigmoid(M[src] . M[v]));  M[src] += g*M[v];  M[v] += g*M[src]
+ * (the second axpy uses the already updated source row; b = 1 for the positive, 0 for
+ * negatives).  No positive update for a vertex without neighbours; a negative equal
+ * to the source applies no update.  Sources run concurrently without locks (Sec. 3.1);
+ * the launch is the epoch barrier.  With GOSH_FLAG_SEQUENTIAL the sources are taken one
+ * by one in ascending id, which is deterministic.
+ * g_dev: CSR arrays on the device.  M_dev: device matrix, updated in place.
+ * lr_epoch: the already decayed learning rate (gosh_lr).  0 <= k_neg <= GOSH_MAX_NEG. */
+int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg,
+                     float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
+                     uint32_t flags, void *hip_stream);
+
+/* "ExpandEmbedding" (Alg. 2; Sec. 3: the row of a vertex of G_{i-1} is the row of its
+ * super vertex in G_i): M_fine[v,:] = M_coarse[map[v],:] for v < n_fine.  All pointers
+ * are device memory; map holds n_fine ids in [0, n_coarse) (trusted).  M_fine and
+ * M_coarse must not overlap. */
+int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev,
+                 int64_t n_fine, int32_t d, float *M_fine_dev, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GOSH_H */

@@ -1,0 +1,18 @@
+"""MI355X-native GOSH training path: HIP kernels behind a C ABI (libgosh.so) and a
+ctypes binding with the same entry-point names."""
+from .binding import (  # noqa: F401
+    GOSH_FLAG_SEQUENTIAL,
+    GOSH_MAX_DIM,
+    GOSH_MAX_NEG,
+    GoshError,
+    csr_view,
+    gosh_csr,
+    gosh_epoch_split,
+    gosh_init_embedding,
+    gosh_last_error,
+    gosh_lr,
+    gosh_project,
+    gosh_sample_epoch,
+    gosh_train_epoch,
+    lib,
+)

@@ -1,0 +1,137 @@
+"""Thin ctypes binding of libgosh: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors used purely as handles to device (or host) memory; every
+step of the training path runs inside the library's HIP kernels.  There is no CPU
+fallback: if the shared library is missing, loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgosh.so")
+
+GOSH_FLAG_SEQUENTIAL = 1
+GOSH_MAX_DIM = 512
+GOSH_MAX_NEG = 15
+
+
+class GoshError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libgosh error {code}: {message}")
+        self.code = code
+
+
+class gosh_csr(C.Structure):
+    _fields_ = [("n", C.c_int64), ("nnz", C.c_int64), ("xadj", C.c_void_p),
+                ("adj", C.c_void_p), ("xadj_is64", C.c_int32)]
+
+
+EXPORTS = {
+    "gosh_last_error": (C.c_char_p, []),
+    "gosh_lr": (C.c_float, [C.c_float, C.c_int64, C.c_int64]),
+    "gosh_epoch_split": (C.c_int, [C.c_int64, C.c_double, C.c_int32, C.POINTER(C.c_int64)]),
+    "gosh_init_embedding": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_uint32,
+                                      C.c_void_p]),
+    "gosh_sample_epoch": (C.c_int, [C.POINTER(gosh_csr), C.c_int32, C.c_uint64, C.c_uint32,
+                                    C.c_uint32, C.c_void_p, C.c_void_p]),
+    "gosh_train_epoch": (C.c_int, [C.POINTER(gosh_csr), C.c_void_p, C.c_int32, C.c_int32,
+                                   C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
+                                   C.c_void_p]),
+    "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
+                               C.c_void_p, C.c_void_p]),
+}
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libgosh.so (built by ``paper_2008_12336_amd.build``); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2008_12336_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise GoshError(rc, lib().gosh_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def csr_view(n: int, xadj: torch.Tensor, adj: torch.Tensor) -> gosh_csr:
+    """Describe CSR tensors (both on the same device, contiguous) to the library."""
+    if xadj.dtype not in (torch.int32, torch.int64) or adj.dtype != torch.int32:
+        raise TypeError("xadj must be int32/int64 and adj int32")
+    if xadj.numel() != n + 1 or not xadj.is_contiguous() or not adj.is_contiguous():
+        raise ValueError("xadj must hold n+1 contiguous offsets, adj must be contiguous")
+    return gosh_csr(n, adj.numel(), xadj.data_ptr(), adj.data_ptr() if adj.numel() else None,
+                    1 if xadj.dtype == torch.int64 else 0)
+
+
+def _matrix(M: torch.Tensor, name: str):
+    if M.dtype != torch.float32 or M.dim() != 2 or not M.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous 2-D float32 tensor")
+    return M.data_ptr(), M.shape[0], M.shape[1]
+
+
+def gosh_last_error() -> str:
+    return lib().gosh_last_error().decode()
+
+
+def gosh_lr(lr0: float, j: int, e_i: int) -> float:
+    return float(lib().gosh_lr(lr0, j, e_i))
+
+
+def gosh_epoch_split(e: int, p: float, D: int):
+    out = (C.c_int64 * max(D, 1))()
+    _check(lib().gosh_epoch_split(e, p, D, out))
+    return [int(x) for x in out[:D]]
+
+
+def gosh_init_embedding(M: torch.Tensor, seed: int, level: int = 0, stream=None) -> None:
+    ptr, n, d = _matrix(M, "M")
+    _check(lib().gosh_init_embedding(ptr, n, d, seed, level, _stream(stream)))
+
+
+def gosh_sample_epoch(g: gosh_csr, k_neg: int, seed: int, epoch: int, level: int,
+                      out: torch.Tensor, stream=None) -> None:
+    if out.dtype != torch.int32 or not out.is_contiguous() or out.numel() != g.n * (k_neg + 1):
+        raise TypeError("out must be a contiguous int32 tensor of n*(k_neg+1) entries")
+    _check(lib().gosh_sample_epoch(C.byref(g), k_neg, seed, epoch, level, out.data_ptr(),
+                                   _stream(stream)))
+
+
+def gosh_train_epoch(g: gosh_csr, M: torch.Tensor, k_neg: int, lr_epoch: float, seed: int,
+                     epoch: int, level: int = 0, flags: int = 0, stream=None) -> None:
+    ptr, n, d = _matrix(M, "M")
+    if n != g.n:
+        raise ValueError("M must have one row per vertex")
+    _check(lib().gosh_train_epoch(C.byref(g), ptr, d, k_neg, lr_epoch, seed, epoch, level, flags,
+                                  _stream(stream)))
+
+
+def gosh_project(M_coarse: torch.Tensor, map_: torch.Tensor, M_fine: torch.Tensor,
+                 stream=None) -> None:
+    cptr, nc, d = _matrix(M_coarse, "M_coarse")
+    fptr, nf, d2 = _matrix(M_fine, "M_fine")
+    if d != d2 or map_.dtype != torch.int32 or map_.numel() != nf or not map_.is_contiguous():
+        raise TypeError("map must be int32 with one entry per fine vertex; dims must agree")
+    _check(lib().gosh_project(cptr, nc, map_.data_ptr(), nf, d, fptr, _stream(stream)))

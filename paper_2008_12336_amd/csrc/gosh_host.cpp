@@ -1,0 +1,85 @@
+// Host-side pieces of libgosh that need no device code: error state, schedule helpers.
+#include <cmath>
+#include <cstdio>
+
+#include "gosh_common.h"
+
+namespace gosh {
+
+static thread_local char g_error[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int check_dim(int32_t d) {
+  if (d < 4 || d > GOSH_MAX_DIM || (d % 4) != 0)
+    return fail(GOSH_EINVAL, "d = %d: must be a multiple of 4 in [4, %d]", d, GOSH_MAX_DIM);
+  return GOSH_OK;
+}
+
+int check_matrix(const float *M, int32_t d, const char *what) {
+  if (int rc = check_dim(d)) return rc;
+  if (M == nullptr) return fail(GOSH_EINVAL, "%s is null", what);
+  if (reinterpret_cast<uintptr_t>(M) % 16 != 0)
+    return fail(GOSH_EINVAL, "%s must be 16-byte aligned", what);
+  return GOSH_OK;
+}
+
+int check_csr(const gosh_csr *g) {
+  if (g == nullptr) return fail(GOSH_EINVAL, "graph is null");
+  if (g->n < 1 || g->n >= 2147483647LL)
+    return fail(GOSH_EINVAL, "n = %lld: must be in [1, 2^31-1)", (long long)g->n);
+  if (g->nnz < 0) return fail(GOSH_EINVAL, "nnz = %lld is negative", (long long)g->nnz);
+  if (g->xadj == nullptr) return fail(GOSH_EINVAL, "xadj is null");
+  if (g->nnz > 0 && g->adj == nullptr) return fail(GOSH_EINVAL, "adj is null but nnz > 0");
+  if (!g->xadj_is64 && g->nnz > 2147483647LL)
+    return fail(GOSH_EINVAL, "nnz = %lld needs 64-bit offsets", (long long)g->nnz);
+  return GOSH_OK;
+}
+
+int check_launch(const char *kernel) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(GOSH_EHIP, "%s: %s", kernel, hipGetErrorString(e));
+  return GOSH_OK;
+}
+
+}  // namespace gosh
+
+extern "C" {
+
+const char *gosh_last_error(void) { return gosh::g_error; }
+
+float gosh_lr(float lr0, int64_t j, int64_t e_i) {
+  if (e_i <= 0) return 0.0f;
+  double frac = 1.0 - static_cast<double>(j) / static_cast<double>(e_i);
+  frac = std::fmax(frac, 1e-4);
+  return static_cast<float>(static_cast<double>(lr0) * frac);
+}
+
+int gosh_epoch_split(int64_t e, double p, int32_t D, int64_t *e_i) {
+  if (e_i == nullptr) return gosh::fail(GOSH_EINVAL, "e_i is null");
+  if (D < 1 || D > 62) return gosh::fail(GOSH_EINVAL, "D = %d: must be in [1, 62]", D);
+  if (!(p >= 0.0 && p <= 1.0)) return gosh::fail(GOSH_EINVAL, "p = %g outside [0, 1]", p);
+  if (e < D) return gosh::fail(GOSH_EINVAL, "e = %lld cannot cover %d levels", (long long)e, D);
+  const double uniform_share = p * static_cast<double>(e) / static_cast<double>(D);
+  const double geometric_pool = (1.0 - p) * static_cast<double>(e);
+  const double weight_sum = static_cast<double>((uint64_t{1} << D) - 1);
+  int64_t remaining = e;
+  for (int32_t level = 1; level < D; ++level) {
+    double weight = static_cast<double>(uint64_t{1} << level);
+    int64_t epochs = static_cast<int64_t>(std::floor(uniform_share + geometric_pool * weight / weight_sum));
+    e_i[level] = epochs < 1 ? 1 : epochs;
+    remaining -= e_i[level];
+  }
+  if (remaining < 1)
+    return gosh::fail(GOSH_EINVAL, "e = %lld leaves no epoch for level 0", (long long)e);
+  e_i[0] = remaining;
+  return GOSH_OK;
+}
+
+}  // extern "C"
