@@ -138,11 +138,13 @@ float orc_lr(float lr0, int64_t j, int64_t e_i) {
 // negative equal to the source itself is drawn but applies no update; negatives
 // that happen to be neighbours, or repeat, are applied like any other.
 // ---------------------------------------------------------------------------
-void orc_train_epoch(int64_t n, const int64_t *xadj, const int32_t *adj, float *M,
-                     int32_t d, int32_t k, float lr_epoch, uint64_t seed, uint32_t epoch,
-                     uint32_t level) {
+// Sources first .. first+count-1 of one epoch (a contiguous slice of the sequential
+// order; the whole epoch is the slice [0, n)).
+void orc_train_sources(int64_t n, const int64_t *xadj, const int32_t *adj, float *M,
+                       int32_t d, int32_t k, float lr_epoch, uint64_t seed, uint32_t epoch,
+                       uint32_t level, int64_t first, int64_t count) {
   std::vector<int32_t> smp((size_t)k + 1);
-  for (int64_t src = 0; src < n; ++src) {
+  for (int64_t src = first; src < first + count && src < n; ++src) {
     orc_sample_source(n, xadj, adj, k, seed, epoch, level, src, smp.data());
     for (int32_t j = 0; j <= k; ++j) {
       int64_t v = smp[j];
@@ -150,6 +152,12 @@ void orc_train_epoch(int64_t n, const int64_t *xadj, const int32_t *adj, float *
       orc_update(M + src * d, M + v * d, d, j == 0 ? 1 : 0, lr_epoch);
     }
   }
+}
+
+void orc_train_epoch(int64_t n, const int64_t *xadj, const int32_t *adj, float *M,
+                     int32_t d, int32_t k, float lr_epoch, uint64_t seed, uint32_t epoch,
+                     uint32_t level) {
+  orc_train_sources(n, xadj, adj, M, d, k, lr_epoch, seed, epoch, level, 0, n);
 }
 
 // e_i epochs at one level with the decaying learning rate (Alg. 3 outer loop).
@@ -164,16 +172,22 @@ void orc_train_level(int64_t n, const int64_t *xadj, const int32_t *adj, float *
 // uniform in [-0.5/d, 0.5/d).  Entry (v, c) uses word c%4 of
 // Philox(counter = (v, c/4, 0xFFFFFFFF, level)); word w maps to
 // ((w >> 8) * 2^-24 - 0.5) / d evaluated in fp64 and rounded to fp32.
-void orc_init_embedding(float *M, int64_t n, int32_t d, uint64_t seed, uint32_t level) {
+// Rows first .. first+count-1 of the initial matrix, written to out (count x d).
+void orc_init_rows(float *out, int64_t first, int64_t count, int32_t d, uint64_t seed,
+                   uint32_t level) {
   uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
-  for (int64_t v = 0; v < n; ++v)
+  for (int64_t r = 0; r < count; ++r)
     for (int32_t c = 0; c < d; ++c) {
-      uint32_t ctr[4] = {(uint32_t)v, (uint32_t)(c / 4), 0xFFFFFFFFu, level};
-      uint32_t out[4];
-      orc_philox4x32_10(ctr, key, out);
-      double u = (double)(out[c % 4] >> 8) * (1.0 / 16777216.0);
-      M[v * d + c] = (float)((u - 0.5) / (double)d);
+      uint32_t ctr[4] = {(uint32_t)(first + r), (uint32_t)(c / 4), 0xFFFFFFFFu, level};
+      uint32_t out4[4];
+      orc_philox4x32_10(ctr, key, out4);
+      double u = (double)(out4[c % 4] >> 8) * (1.0 / 16777216.0);
+      out[r * d + c] = (float)((u - 0.5) / (double)d);
     }
+}
+
+void orc_init_embedding(float *M, int64_t n, int32_t d, uint64_t seed, uint32_t level) {
+  orc_init_rows(M, 0, n, d, seed, level);
 }
 
 // ---------------------------------------------------------------------------

@@ -43,6 +43,13 @@ def lib():
         L.orc_train_epoch.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
                                       C.c_float, C.c_uint64, C.c_uint32, C.c_uint32]
         L.orc_train_epoch.restype = None
+        L.orc_train_sources.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
+                                        C.c_float, C.c_uint64, C.c_uint32, C.c_uint32,
+                                        C.c_int64, C.c_int64]
+        L.orc_train_sources.restype = None
+        L.orc_init_rows.argtypes = [f32p, C.c_int64, C.c_int64, C.c_int32, C.c_uint64,
+                                    C.c_uint32]
+        L.orc_init_rows.restype = None
         L.orc_train_level.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
                                       C.c_float, C.c_int64, C.c_uint64, C.c_uint32]
         L.orc_train_level.restype = None
@@ -134,6 +141,21 @@ def train_epoch(xadj, adj, M, k, lr_epoch, seed, epoch, level):
     assert n == xadj.size - 1
     lib().orc_train_epoch(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
                           lr_epoch, seed, epoch, level)
+
+
+def train_sources(xadj, adj, M, k, lr_epoch, seed, epoch, level, first, count):
+    """Sources first..first+count-1 of one sequential epoch, in place on M."""
+    xadj, adj = _csr(xadj, adj)
+    assert M.dtype == np.float32 and M.flags.c_contiguous
+    n, d = M.shape
+    lib().orc_train_sources(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
+                            lr_epoch, seed, epoch, level, first, count)
+
+
+def init_rows(first, count, d, seed, level):
+    out = np.empty((count, d), dtype=np.float32)
+    lib().orc_init_rows(_p(out, C.c_float), first, count, d, seed, level)
+    return out
 
 
 def train_level(xadj, adj, M, k, lr0, e_i, seed, level):
