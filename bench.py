@@ -62,6 +62,11 @@ def main() -> int:
     ap.add_argument("--log2m", type=int, default=None, help="override edge draws (scaled runs)")
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--flags", type=int, default=0,
+                    help="gosh_train_epoch flags (0 = default mix of plain stores and atomic adds)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of the matrix (known size) so that "
+                         "profiler byte counters can be scaled against it")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget for the oracle baseline slice (0 = skip)")
     args = ap.parse_args()
@@ -109,7 +114,7 @@ def main() -> int:
 
     total_epochs = args.warmup + args.steps
     for j in range(args.warmup):
-        G.gosh_train_epoch(g, M, k, G.gosh_lr(w["lr0"], j, total_epochs), args.seed, j, 0, 0)
+        G.gosh_train_epoch(g, M, k, G.gosh_lr(w["lr0"], j, total_epochs), args.seed, j, 0, args.flags)
     torch.cuda.synchronize()
 
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
@@ -119,13 +124,19 @@ def main() -> int:
     for i in range(args.steps):
         j = args.warmup + i
         starts[i].record()  # same (current) stream the kernel is launched on
-        G.gosh_train_epoch(g, M, k, G.gosh_lr(w["lr0"], j, total_epochs), args.seed, j, 0, 0)
+        G.gosh_train_epoch(g, M, k, G.gosh_lr(w["lr0"], j, total_epochs), args.seed, j, 0, args.flags)
         ends[i].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     kernel_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
     avg_kernel_s = float(np.mean(kernel_ms)) / 1e3
     finite = bool(torch.isfinite(M[:: max(1, n // 4096)]).all())
+
+    if args.copy_calibration:
+        scratch = torch.empty_like(M)
+        scratch.copy_(M)  # reads and writes n*d*4 bytes each
+        torch.cuda.synchronize()
+        del scratch
 
     samples_per_step = n * (k + 1)
     value = samples_per_step * args.steps / elapsed
@@ -170,7 +181,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload + ("_scaled" if scaled else ""), "desc": w["desc"],
                    "n": n, "undirected_edges": n_edges, "nnz": int(csr.adj.numel()), "d": d,
-                   "k_neg": k, "seed": args.seed, "graph_build_s": round(t_graph, 2),
+                   "k_neg": k, "seed": args.seed, "flags": args.flags, "graph_build_s": round(t_graph, 2),
                    "finite": finite},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,

@@ -49,8 +49,13 @@ typedef struct {
 #define GOSH_MAX_NEG 15
 
 /* gosh_train_epoch flags */
-#define GOSH_FLAG_SEQUENTIAL 1u /* debug: one wavefront walks the sources in ascending
-                                   id, giving the sequential-order result */
+#define GOSH_FLAG_SEQUENTIAL 1u   /* debug: one wavefront walks the sources in ascending
+                                     id, giving the sequential-order result */
+#define GOSH_FLAG_PLAIN_STORES 2u /* concurrent mode: write every updated row back with
+                                     plain stores (the paper's lock-free scheme as it
+                                     stands: concurrent updates of one row can be lost) */
+#define GOSH_FLAG_ATOMIC_ADDS 4u  /* concurrent mode: apply every update as atomic adds of
+                                     the step (no update is ever lost; about 2x the cost) */
 
 const char *gosh_last_error(void);
 
@@ -95,7 +100,13 @@ int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint3
  * negatives).  No positive update for a vertex without neighbours; a negative equal
  * to the source applies no update.  Sources run concurrently without locks (Sec. 3.1);
  * the launch is the epoch barrier.  With GOSH_FLAG_SEQUENTIAL the sources are taken one
- * by one in ascending id, which is deterministic.
+ * by one in ascending id, which is deterministic.  In concurrent mode the default is a
+ * mix: rows likely to be held by several wavefronts at once (every row of a small
+ * graph, high-degree vertices of a large one) receive atomic adds of the step, the
+ * others plain stores; GOSH_FLAG_PLAIN_STORES / GOSH_FLAG_ATOMIC_ADDS force one kind.
+ * The mix uses a per-device scratch bitmap owned by the library (n bits, allocated on
+ * first use), so concurrent-mode calls on one device must not overlap on different
+ * streams.
  * g_dev: CSR arrays on the device.  M_dev: device matrix, updated in place.
  * lr_epoch: the already decayed learning rate (gosh_lr).  0 <= k_neg <= GOSH_MAX_NEG. */
 int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg,

@@ -1,6 +1,8 @@
 """MI355X-native GOSH training path: HIP kernels behind a C ABI (libgosh.so) and a
 ctypes binding with the same entry-point names."""
 from .binding import (  # noqa: F401
+    GOSH_FLAG_ATOMIC_ADDS,
+    GOSH_FLAG_PLAIN_STORES,
     GOSH_FLAG_SEQUENTIAL,
     GOSH_MAX_DIM,
     GOSH_MAX_NEG,

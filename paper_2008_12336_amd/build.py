@@ -21,6 +21,8 @@ FLAGS = [
     "-fopenmp",
     "-Wall",
     "-Wno-unused-function",
+    # fp32 atomic adds on coarse-grained device memory use the hardware instruction
+    "-munsafe-fp-atomics",
     # packed-fp32 instructions are kept off on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]

@@ -11,6 +11,9 @@
 // before the first dot product so that their HBM latencies overlap.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cstdlib>
+
 #include "gosh_common.h"
 
 namespace {
@@ -100,55 +103,150 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
-__device__ __forceinline__ float dot4(const float4 &a, const float4 &b) {
-  return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+// ---------------------------------------------------------------------------------
+// Row access policies.  A row is moved in "units" of F floats per lane.
+//
+// The chip's eight XCDs each have their own L2, and plain stores sit in the writer's
+// L2 until they are evicted or the kernel ends: with plain accesses a row updated on
+// one XCD is read stale on the others and the last write-back wins.  Lock-free SGD
+// needs the rows to be coherent across the whole device, so the concurrent kernel
+// moves rows with agent-scope (device-scope) accesses, which are served behind the
+// per-XCD L2s.  Every sample row is touched once per turn, so no L2 reuse is lost.
+//   RowAgent32: 32-bit relaxed atomic loads and stores at agent scope, lanes interleaved
+//     over the row (lane g owns floats g, g+LPG, ...) so that every access instruction
+//     of a group covers one whole 128-byte line.  Measured on the 2^24-vertex graph this
+//     is as fast as wider per-lane accesses, and it makes the atomic adds used for hot
+//     rows (below) dense: one line per instruction instead of half-filled lines, which
+//     the memory-side atomic units process at half the rate.
+//   RowPlain128: ordinary 128-bit accesses (coherent only inside one XCD); used by the
+//     sequential-order mode, which runs on a single wavefront.
+// ---------------------------------------------------------------------------------
+template <int F>
+struct Unit {
+  float v[F];
+};
+
+__device__ __forceinline__ void atomic_step(float *p, float x) {
+  // Built with -munsafe-fp-atomics: the matrix is ordinary coarse-grained device
+  // memory, where the hardware fp32 add is available.
+  __hip_atomic_fetch_add(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void axpy4(float4 &y, float g, const float4 &x) {
-  y.x = fmaf(g, x.x, y.x);
-  y.y = fmaf(g, x.y, y.y);
-  y.z = fmaf(g, x.z, y.z);
-  y.w = fmaf(g, x.w, y.w);
+
+struct RowPlain128 {
+  static constexpr int F = 4;
+  static __device__ __forceinline__ Unit<4> load(const float *p) {
+    const float4 x = *reinterpret_cast<const float4 *>(p);
+    return Unit<4>{{x.x, x.y, x.z, x.w}};
+  }
+  static __device__ __forceinline__ void store(float *p, const Unit<4> &u) {
+    *reinterpret_cast<float4 *>(p) = float4{u.v[0], u.v[1], u.v[2], u.v[3]};
+  }
+};
+
+struct RowAgent32 {
+  static constexpr int F = 1;
+  static __device__ __forceinline__ Unit<1> load(const float *p) {
+    return Unit<1>{{__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)}};
+  }
+  static __device__ __forceinline__ void store(float *p, const Unit<1> &u) {
+    __hip_atomic_store(p, u.v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+};
+
+// ---------------------------------------------------------------------------------
+// Hot rows.  A lock-free update is a read-modify-write of a row; when two wavefronts
+// hold the same row at once, one of the two writes is lost (Sec. 3.1 of the paper
+// accepts such races, and reports that too many of them hurt the embedding).  With
+// C sources in flight out of n, a row that is touched h times per epoch has about
+// h*C/n concurrent holders.  Rows for which that is not small -- every row of a
+// small graph, the high-degree vertices of a large one, which are drawn as positive
+// samples in proportion to their degree -- are "hot": their updates are applied as
+// atomic adds of the step (M[v] += g*M[src], and M[src] += its accumulated change),
+// which cannot be lost.  Cold rows are written back with plain stores, which cost
+// half as much on this memory system.
+// ---------------------------------------------------------------------------------
+enum HotMode : int32_t { kHotNone = 0, kHotBitmap = 1, kHotAll = 2 };
+
+template <typename OffT>
+__global__ __launch_bounds__(256) void mark_hot_kernel(const OffT *__restrict__ xadj, int64_t n,
+                                                       int64_t min_degree,
+                                                       unsigned long long *__restrict__ bits) {
+  // one vertex per lane, one 64-bit word of the bitmap per wavefront
+  const int64_t words = (n + 63) / 64;
+  const int64_t wave0 = (blockIdx.x * 256LL + threadIdx.x) >> 6;
+  const int64_t nwaves = (gridDim.x * 256LL) >> 6;
+  const int lane = threadIdx.x & 63;
+  for (int64_t w = wave0; w < words; w += nwaves) {
+    const int64_t v = w * 64 + lane;
+    bool hot = false;
+    if (v < n) hot = static_cast<int64_t>(xadj[v + 1] - xadj[v]) >= min_degree;
+    const unsigned long long mask = __ballot(hot);
+    if (lane == 0) bits[w] = mask;
+  }
 }
 
 struct TrainArgs {
   SamplerArgs s;
   float *M;
-  int32_t d4;  // d / 4
+  const uint32_t *hot_bits;  // n bits, used when hot_mode == kHotBitmap
+  int32_t hot_mode;
+  int32_t d;
   int32_t k_neg;
   float lr;
+  int64_t active_waves;  // wavefronts that take part; the rest of the grid exits at once
 };
 
 constexpr int kChunk = 4;  // sample rows in flight per source
 
-// One epoch.  SEQ: a single lane group walks all sources in ascending order (the
-// sequential-order result); otherwise groups stride over the sources.
-template <int LPG, int VPL, typename OffT, bool SEQ>
+__device__ __forceinline__ bool is_hot(const TrainArgs &a, int32_t v) {
+  if (a.hot_mode == kHotBitmap) return (a.hot_bits[v >> 5] >> (v & 31)) & 1u;
+  return a.hot_mode == kHotAll;
+}
+
+// One epoch.  P: row access policy; LPG lanes per source, UPL units per lane
+// (LPG * UPL * P::F >= d).  SEQ: a single lane group walks all sources in ascending
+// order (the sequential-order result); otherwise groups stride over the sources.
+template <class P, int LPG, int UPL, typename OffT, bool SEQ>
 __global__ __launch_bounds__(256) void train_epoch_kernel(TrainArgs a) {
   constexpr int kGroupsPerWave = 64 / LPG;
+  constexpr int F = P::F;
+  using U = Unit<F>;
   const int lane = threadIdx.x & 63;
   const int gl = lane & (LPG - 1);
   if (SEQ && (lane >= LPG || threadIdx.x >= 64 || blockIdx.x != 0)) return;
 
   const int64_t wave = blockIdx.x * static_cast<int64_t>(blockDim.x / 64) + (threadIdx.x >> 6);
+  if (!SEQ && wave >= a.active_waves) return;
   const int64_t n = a.s.n;
-  const int64_t stride = SEQ ? 1 : static_cast<int64_t>(gridDim.x) * (blockDim.x / 64) * kGroupsPerWave;
+  const int64_t stride = SEQ ? 1 : a.active_waves * kGroupsPerWave;
   const int64_t first = SEQ ? 0 : wave * kGroupsPerWave + lane / LPG;
-  const int32_t d4 = a.d4;
-  float4 *const Mv = reinterpret_cast<float4 *>(a.M);
+  const int32_t d = a.d;
+  float *const M = a.M;
 
-  bool col_ok[VPL];
+  // Lane gl owns floats [(gl + i*LPG)*F, +F) of a row, i < UPL: consecutive lanes touch
+  // consecutive addresses, so each access instruction covers whole cache lines.
+  int32_t col[UPL];
+  bool col_ok[UPL];
 #pragma unroll
-  for (int i = 0; i < VPL; ++i) col_ok[i] = gl + i * LPG < d4;
+  for (int i = 0; i < UPL; ++i) {
+    col[i] = (gl + i * LPG) * F;
+    col_ok[i] = col[i] < d;
+  }
+  const U zero{};
 
   // The loop bound is uniform over the wave; groups past the end idle inside.
   const int64_t first_of_wave = SEQ ? 0 : wave * kGroupsPerWave;
   for (int64_t base = first_of_wave; base < n; base += stride) {
     const int64_t src = first + (base - first_of_wave);
     if (src >= n) continue;
-    float4 *const src_row = Mv + src * d4;
-    float4 s[VPL];
+    float *const src_row = M + src * d;
+    U s[UPL];
 #pragma unroll
-    for (int i = 0; i < VPL; ++i) s[i] = col_ok[i] ? src_row[gl + i * LPG] : float4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < UPL; ++i) s[i] = col_ok[i] ? P::load(src_row + col[i]) : zero;
+    const bool src_hot = !SEQ && is_hot(a, static_cast<int32_t>(src));
+    U s_before[UPL];
+#pragma unroll
+    for (int i = 0; i < UPL; ++i) s_before[i] = s[i];
 
     for (int32_t j0 = 0; j0 <= a.k_neg; j0 += kChunk) {
       // Sample ids of this chunk: lane q of the group evaluates draw j0+q, then the
@@ -169,13 +267,14 @@ __global__ __launch_bounds__(256) void train_epoch_kernel(TrainArgs a) {
         if (v[q] == static_cast<int32_t>(src)) v[q] = -1;
 
       // Fetch all rows of the chunk before using any of them.
-      float4 t[kChunk][VPL];
+      U t[kChunk][UPL];
+      bool hot[kChunk];
 #pragma unroll
       for (int q = 0; q < kChunk; ++q) {
-        const float4 *row = Mv + static_cast<int64_t>(v[q] < 0 ? 0 : v[q]) * d4;
+        const float *row = M + static_cast<int64_t>(v[q] < 0 ? 0 : v[q]) * d;
 #pragma unroll
-        for (int i = 0; i < VPL; ++i)
-          t[q][i] = (v[q] >= 0 && col_ok[i]) ? row[gl + i * LPG] : float4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < UPL; ++i) t[q][i] = (v[q] >= 0 && col_ok[i]) ? P::load(row + col[i]) : zero;
+        hot[q] = !SEQ && v[q] >= 0 && is_hot(a, v[q]);
       }
 
 #pragma unroll
@@ -183,16 +282,30 @@ __global__ __launch_bounds__(256) void train_epoch_kernel(TrainArgs a) {
         if (v[q] < 0) continue;  // uniform over the group
         float partial = 0.f;
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) partial += dot4(s[i], t[q][i]);
+        for (int i = 0; i < UPL; ++i)
+#pragma unroll
+          for (int c = 0; c < F; ++c) partial = fmaf(s[i].v[c], t[q][i].v[c], partial);
         const float x = group_sum<LPG>(partial);
         const float label = (j0 + q == 0) ? 1.f : 0.f;
         const float g = a.lr * (label - 1.f / (1.f + expf(-x)));
-        float4 *row = Mv + static_cast<int64_t>(v[q]) * d4;
+        float *row = M + static_cast<int64_t>(v[q]) * d;
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-          axpy4(s[i], g, t[q][i]);
-          axpy4(t[q][i], g, s[i]);
-          if (col_ok[i]) row[gl + i * LPG] = t[q][i];
+        for (int i = 0; i < UPL; ++i)
+#pragma unroll
+          for (int c = 0; c < F; ++c) {
+            s[i].v[c] = fmaf(g, t[q][i].v[c], s[i].v[c]);
+            t[q][i].v[c] = fmaf(g, s[i].v[c], t[q][i].v[c]);
+          }
+        if (hot[q]) {  // uniform over the group
+#pragma unroll
+          for (int i = 0; i < UPL; ++i)
+#pragma unroll
+            for (int c = 0; c < F; ++c)
+              if (col_ok[i]) atomic_step(row + col[i] + c, g * s[i].v[c]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < UPL; ++i)
+            if (col_ok[i]) P::store(row + col[i], t[q][i]);
         }
         // A later sample of the same chunk that names the same vertex must see this
         // update: forward the registers instead of the stale prefetched copy.
@@ -200,13 +313,21 @@ __global__ __launch_bounds__(256) void train_epoch_kernel(TrainArgs a) {
         for (int r = q + 1; r < kChunk; ++r)
           if (v[r] == v[q]) {
 #pragma unroll
-            for (int i = 0; i < VPL; ++i) t[r][i] = t[q][i];
+            for (int i = 0; i < UPL; ++i) t[r][i] = t[q][i];
           }
       }
     }
+    if (src_hot) {
 #pragma unroll
-    for (int i = 0; i < VPL; ++i)
-      if (col_ok[i]) src_row[gl + i * LPG] = s[i];
+      for (int i = 0; i < UPL; ++i)
+#pragma unroll
+        for (int c = 0; c < F; ++c)
+          if (col_ok[i]) atomic_step(src_row + col[i] + c, s[i].v[c] - s_before[i].v[c]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < UPL; ++i)
+        if (col_ok[i]) P::store(src_row + col[i], s[i]);
+    }
   }
 }
 
@@ -261,15 +382,130 @@ SamplerArgs sampler_args(const gosh_csr *g, uint64_t seed, uint32_t epoch, uint3
   return s;
 }
 
-template <int LPG, int VPL>
-void launch_train(const TrainArgs &a, bool is64, bool seq, int blocks, hipStream_t st) {
-  if (seq) {
-    if (is64) hipLaunchKernelGGL((train_epoch_kernel<LPG, VPL, int64_t, true>), dim3(1), dim3(64), 0, st, a);
-    else hipLaunchKernelGGL((train_epoch_kernel<LPG, VPL, int32_t, true>), dim3(1), dim3(64), 0, st, a);
-  } else {
-    if (is64) hipLaunchKernelGGL((train_epoch_kernel<LPG, VPL, int64_t, false>), dim3(blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((train_epoch_kernel<LPG, VPL, int32_t, false>), dim3(blocks), dim3(256), 0, st, a);
+long env_long(const char *name, long fallback) {
+  const char *e = getenv(name);
+  return e ? atol(e) : fallback;
+}
+
+// Tuning / experiment overrides (read once).  GOSH_ROW_POLICY: 0 = plain 128-bit row
+// accesses also in the concurrent kernel (coherent inside one XCD only).
+// GOSH_MAX_WAVES: cap on participating wavefronts.  GOSH_HOT_INV_EPS: 1/eps of the
+// hot-row rule.
+struct Tuning {
+  int row_policy = static_cast<int>(env_long("GOSH_ROW_POLICY", 1));
+  int64_t max_waves = env_long("GOSH_MAX_WAVES", 1L << 22);
+  int64_t hot_inv_eps = env_long("GOSH_HOT_INV_EPS", 64);
+  int64_t hot_all_inv_eps = env_long("GOSH_HOT_ALL_INV_EPS", 4);
+};
+const Tuning &tuning() {
+  static const Tuning t;
+  return t;
+}
+
+// Per-device scratch for the hot-row bitmap (n bits), grown on demand and kept until
+// the process ends.  Calls on one device must not overlap on different streams.
+struct HotScratch {
+  void *ptr = nullptr;
+  size_t bytes = 0;
+};
+constexpr int kMaxDevices = 64;
+HotScratch g_hot_scratch[kMaxDevices];
+
+int hot_scratch(size_t bytes, void **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return gosh::fail(GOSH_EHIP, "cannot identify the current device");
+  HotScratch &h = g_hot_scratch[dev];
+  if (h.bytes < bytes) {
+    if (h.ptr) (void)hipFree(h.ptr);
+    h.ptr = nullptr;
+    h.bytes = 0;
+    const size_t want = bytes + bytes / 4 + 4096;
+    if (hipMalloc(&h.ptr, want) != hipSuccess) {
+      (void)hipGetLastError();
+      return gosh::fail(GOSH_ENOMEM, "cannot allocate %zu bytes for the hot-row bitmap", want);
+    }
+    h.bytes = want;
   }
+  *out = h.ptr;
+  return GOSH_OK;
+}
+
+int resident_waves() {
+  static const int value = [] {
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      int v = 0;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        cus = v;
+    }
+    return cus * 32;  // 8 wavefronts on each of the 4 SIMDs of a CU
+  }();
+  return value;
+}
+
+template <class P, int LPG, int UPL>
+int launch_train_p(TrainArgs a, const gosh_csr *g, uint32_t flags, hipStream_t st) {
+  const bool seq = (flags & GOSH_FLAG_SEQUENTIAL) != 0;
+  constexpr int kWavesPerBlock = 4;
+  constexpr int kGroupsPerWave = 64 / LPG;
+  const bool is64 = g->xadj_is64 != 0;
+  const int64_t n = g->n;
+  int64_t waves = (n + kGroupsPerWave - 1) / kGroupsPerWave;
+  if (waves > tuning().max_waves) waves = tuning().max_waves;
+  if (waves < 1) waves = 1;
+  a.active_waves = waves;
+  a.hot_mode = kHotNone;
+  a.hot_bits = nullptr;
+  if (!seq) {
+    // Sources in flight C, and the hot-row rule.  A vertex is hot if its expected
+    // positive hits per epoch, deg/avg_deg, give more than eps = 1/64 concurrent holders:
+    // deg * C / nnz > eps.  On graphs so small that even the k+1 uniform touches of
+    // every row overlap ((k+1)*C/n > 1/4, i.e. fewer than 16 rounds at k = 3) all rows
+    // are hot.  Both constants come from link-prediction AUCROC against the sequential
+    // reference on R-MAT graphs of 2^12..2^18 vertices: with them the concurrent kernel
+    // stays within 0.001..0.005 of the reference, without them it drops by up to 0.4.
+    const int64_t in_flight = (waves < resident_waves() ? waves : resident_waves()) * kGroupsPerWave;
+    const int64_t inv_eps = tuning().hot_inv_eps;
+    int mode = ((a.k_neg + 1) * in_flight * tuning().hot_all_inv_eps > n) ? kHotAll : kHotBitmap;
+    if (flags & GOSH_FLAG_PLAIN_STORES) mode = kHotNone;
+    if (flags & GOSH_FLAG_ATOMIC_ADDS) mode = kHotAll;
+    if (mode == kHotBitmap) {
+      int64_t min_degree = g->nnz / (inv_eps * in_flight) + 1;
+      void *bits = nullptr;
+      const size_t bytes = static_cast<size_t>((n + 63) / 64) * 8;
+      if (int rc = hot_scratch(bytes, &bits)) return rc;
+      const int blocks = static_cast<int>(std::min<int64_t>(((n + 63) / 64 + 3) / 4, 1 << 16));
+      if (is64)
+        hipLaunchKernelGGL(mark_hot_kernel<int64_t>, dim3(blocks), dim3(256), 0, st,
+                           static_cast<const int64_t *>(g->xadj), n, min_degree,
+                           static_cast<unsigned long long *>(bits));
+      else
+        hipLaunchKernelGGL(mark_hot_kernel<int32_t>, dim3(blocks), dim3(256), 0, st,
+                           static_cast<const int32_t *>(g->xadj), n, min_degree,
+                           static_cast<unsigned long long *>(bits));
+      if (int rc = gosh::check_launch("mark_hot_kernel")) return rc;
+      a.hot_bits = static_cast<const uint32_t *>(bits);
+    }
+    a.hot_mode = mode;
+  }
+  const int blocks = static_cast<int>((a.active_waves + kWavesPerBlock - 1) / kWavesPerBlock);
+  if (seq) {
+    if (is64) hipLaunchKernelGGL((train_epoch_kernel<P, LPG, UPL, int64_t, true>), dim3(1), dim3(64), 0, st, a);
+    else hipLaunchKernelGGL((train_epoch_kernel<P, LPG, UPL, int32_t, true>), dim3(1), dim3(64), 0, st, a);
+  } else {
+    if (is64) hipLaunchKernelGGL((train_epoch_kernel<P, LPG, UPL, int64_t, false>), dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((train_epoch_kernel<P, LPG, UPL, int32_t, false>), dim3(blocks), dim3(256), 0, st, a);
+  }
+  return gosh::check_launch("train_epoch_kernel");
+}
+
+// LPG lanes per source, V128 = 128-bit vectors per lane.
+template <int LPG, int V128>
+int launch_train(const TrainArgs &a, const gosh_csr *g, uint32_t flags, hipStream_t st) {
+  if ((flags & GOSH_FLAG_SEQUENTIAL) || tuning().row_policy == 0)
+    return launch_train_p<RowPlain128, LPG, V128>(a, g, flags, st);
+  return launch_train_p<RowAgent32, LPG, 4 * V128>(a, g, flags, st);
 }
 
 }  // namespace
@@ -312,36 +548,35 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
   if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
   if (k_neg < 0 || k_neg > GOSH_MAX_NEG)
     return gosh::fail(GOSH_EINVAL, "k_neg = %d: must be in [0, %d]", k_neg, GOSH_MAX_NEG);
-  if (flags & ~GOSH_FLAG_SEQUENTIAL) return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
+  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS))
+    return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
+  if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
+    return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
   if (!(lr_epoch == lr_epoch)) return gosh::fail(GOSH_EINVAL, "lr is NaN");
 
   TrainArgs a;
   a.s = sampler_args(g_dev, seed, epoch, level);
   a.M = M_dev;
-  a.d4 = d / 4;
+  a.d = d;
   a.k_neg = k_neg;
   a.lr = lr_epoch;
-  const bool seq = (flags & GOSH_FLAG_SEQUENTIAL) != 0;
-  const bool is64 = g_dev->xadj_is64 != 0;
   hipStream_t st = gosh::as_stream(hip_stream);
 
   // Smallest power-of-two lane group that covers d/4 vectors (two vectors per lane
   // above 64 vectors).
+  const int d4 = d / 4;
   int lpg = 1;
-  while (lpg < a.d4 && lpg < 64) lpg *= 2;
-  const int64_t groups_per_block = 256 / lpg;
-  const int blocks = grid_for(g_dev->n, static_cast<int>(groups_per_block), 1 << 20);
-  if (a.d4 > 64) launch_train<64, 2>(a, is64, seq, blocks, st);
-  else switch (lpg) {
-    case 64: launch_train<64, 1>(a, is64, seq, blocks, st); break;
-    case 32: launch_train<32, 1>(a, is64, seq, blocks, st); break;
-    case 16: launch_train<16, 1>(a, is64, seq, blocks, st); break;
-    case 8: launch_train<8, 1>(a, is64, seq, blocks, st); break;
-    case 4: launch_train<4, 1>(a, is64, seq, blocks, st); break;
-    case 2: launch_train<2, 1>(a, is64, seq, blocks, st); break;
-    default: launch_train<1, 1>(a, is64, seq, blocks, st); break;
+  while (lpg < d4 && lpg < 64) lpg *= 2;
+  if (d4 > 64) return launch_train<64, 2>(a, g_dev, flags, st);
+  switch (lpg) {
+    case 64: return launch_train<64, 1>(a, g_dev, flags, st);
+    case 32: return launch_train<32, 1>(a, g_dev, flags, st);
+    case 16: return launch_train<16, 1>(a, g_dev, flags, st);
+    case 8: return launch_train<8, 1>(a, g_dev, flags, st);
+    case 4: return launch_train<4, 1>(a, g_dev, flags, st);
+    case 2: return launch_train<2, 1>(a, g_dev, flags, st);
+    default: return launch_train<1, 1>(a, g_dev, flags, st);
   }
-  return gosh::check_launch("train_epoch_kernel");
 }
 
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev, int64_t n_fine,

@@ -79,7 +79,8 @@ def test_bad_arguments_are_rejected_on_the_host():
         (dict(k=-1), "k_neg"),
         (dict(ptr=ok_ptr + 4), "aligned"),
         (dict(ptr=0), "null"),
-        (dict(flags=2), "flags"),
+        (dict(flags=8), "flags"),
+        (dict(flags=2 | 4), "flags"),
         (dict(lr=float("nan")), "NaN"),
         (dict(gv=G.gosh_csr(0, 0, 0x1000, 0x2000, 0)), "n = 0"),
         (dict(gv=G.gosh_csr(2 ** 31, 0, 0x1000, 0x2000, 1)), "n ="),

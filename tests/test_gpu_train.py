@@ -138,19 +138,46 @@ def test_sequential_epoch_parity(name, d, k, offsets64, scale):
     say(f"      worst relative error {worst:.2e}")
 
 
+@pytest.mark.parametrize("flags", [0, G.GOSH_FLAG_PLAIN_STORES, G.GOSH_FLAG_ATOMIC_ADDS])
 @pytest.mark.parametrize("name,d,k", [("cl3001", 128, 3), ("er1024", 32, 3), ("rmat4096", 64, 5),
                                       ("ring24", 8, 15), ("er1024", 512, 1), ("cl3001", 100, 2)])
-def test_parallel_epoch_with_zero_lr_moves_nothing(name, d, k):
-    """With lr = 0 every update writes back exactly what it read, so any row stored to
-    the wrong place by the parallel launch would show."""
+def test_parallel_epoch_with_zero_lr_moves_nothing(name, d, k, flags):
+    """With lr = 0 every update writes back exactly what it read (or adds a zero step), so
+    any row stored to the wrong place by the parallel launch would show."""
     n, xadj, adj = GRAPHS[name]
-    say(f"[lr0] graph={name} n={n} d={d} k={k}")
+    say(f"[lr0] graph={name} n={n} d={d} k={k} flags={flags}")
     g, keep = upload(n, xadj, adj, False)
     M0 = start_matrix(n, d, 6, 1.0)
     M = torch.from_numpy(M0).to(DEV)
-    G.gosh_train_epoch(g, M, k, 0.0, 3, 0, 0, 0)
+    G.gosh_train_epoch(g, M, k, 0.0, 3, 0, 0, flags)
     torch.cuda.synchronize()
     assert np.array_equal(M.cpu().numpy(), M0)
+
+
+@pytest.mark.parametrize("name,d,k", [("cl3001", 128, 3), ("er1024", 32, 3), ("ring24", 8, 15),
+                                      ("rmat4096", 100, 4)])
+def test_atomic_epoch_matches_first_order_sum(name, d, k):
+    """With atomic adds no update is lost, and for a small learning rate the order of
+    updates matters only at second order: every row must end within a small fraction of
+    its own movement from the sequential-order result, however the updates interleave."""
+    n, xadj, adj = GRAPHS[name]
+    lr = 1e-3
+    say(f"[atomic] graph={name} n={n} d={d} k={k}")
+    g, keep = upload(n, xadj, adj, False)
+    M0 = start_matrix(n, d, 9, 0.5)
+    want = M0.copy()
+    O.train_epoch(xadj, adj, want, k, lr, 21, 2, 0)
+    M = torch.from_numpy(M0).to(DEV)
+    G.gosh_train_epoch(g, M, k, lr, 21, 2, 0, G.GOSH_FLAG_ATOMIC_ADDS)
+    torch.cuda.synchronize()
+    got = M.cpu().numpy().astype(np.float64)
+    step = np.abs(want.astype(np.float64) - M0).max(axis=1)
+    err = np.abs(got - want).max(axis=1)
+    # second-order terms: each of the h touches of a row sees partners that moved by
+    # about lr; allow 2% of the row's own movement plus rounding
+    ok = err <= 0.02 * step + 2e-7 * np.abs(M0).max()
+    say(f"      rows agreeing: {ok.mean():.4f}, worst err/step {np.max(err / np.maximum(step, 1e-30)):.3e}")
+    assert ok.all()
 
 
 def test_parallel_epoch_stays_within_the_reach_of_its_updates():
