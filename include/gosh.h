@@ -74,6 +74,46 @@ float gosh_lr(float lr0, int64_t j, int64_t e_i);
  * [0,1] or e cannot give every level one epoch. */
 int gosh_epoch_split(int64_t e, double p, int32_t D, int64_t *e_i);
 
+/* ---- coarsening (host) -------------------------------------------------------------- */
+
+/* Checks a host CSR graph against the conventions above (offsets start at 0, end at
+ * nnz and never decrease; neighbour ids in range; rows strictly ascending; no self
+ * loops).  GOSH_OK or GOSH_EINVAL with the first violation in gosh_last_error(). */
+int gosh_csr_validate(const gosh_csr *g_host);
+
+/* The set of coarsened graphs and the maps between them ("MultiEdgeCollapse", Alg. 4,
+ * Sec. 3.2).  Opaque; owned by the library, released with gosh_hierarchy_free. */
+typedef struct gosh_hierarchy gosh_hierarchy;
+
+/* Alg. 4, sequential semantics.  Per level: vertices are visited by degree, largest
+ * first (ties: smaller id first); an unmarked vertex v opens cluster number
+ * (clusters so far) and takes every unmarked neighbour u, in neighbour-list order,
+ * for which deg(v) <= delta or deg(u) <= delta, delta = nnz/n (tested as deg*n <= nnz).
+ * G_{i+1} has the entry (a, b), a != b, iff some entry (x, y) of G_i has map[x] = a,
+ * map[y] = b; rows ascending, parallel entries merged.
+ * Levels are built while |V_i| > threshold (the paper's default is 100); building stops
+ * after a level with |V_{i+1}| > min_shrink*|V_i| or |V_{i+1}| == |V_i| (that level is
+ * kept), or when max_levels graphs exist.  min_shrink in (0, 1]; 1.0 keeps only the
+ * no-progress guard.  n_threads <= 0 uses every available core (the result does not
+ * depend on the thread count).
+ * g0_host: host CSR, borrowed for the lifetime of the hierarchy (level 0 is a view of
+ * it, not a copy).  *out receives the hierarchy; on failure it is NULL. */
+int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
+                 int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
+
+/* D, the number of graphs G_0..G_{D-1} (0 for NULL). */
+int gosh_hierarchy_levels(const gosh_hierarchy *h);
+/* Borrowed host view of G_i (coarse levels have 64-bit offsets). */
+int gosh_hierarchy_graph(const gosh_hierarchy *h, int32_t i, gosh_csr *view);
+/* map_i: one entry per vertex of G_i, its super vertex in G_{i+1}; 0 <= i < D-1. */
+int gosh_hierarchy_map(const gosh_hierarchy *h, int32_t i, const int32_t **map, int64_t *len);
+/* Per entry of G_i's adj, how many entries of G_0 were merged into it (NULL and 0 for
+ * level 0, where every entry counts once).  Not used by training; it makes edge-weight
+ * conservation checkable: sum(mult_{i+1}) + (weight of entries inside clusters) =
+ * sum(mult_i). */
+int gosh_hierarchy_mult(const gosh_hierarchy *h, int32_t i, const int64_t **mult, int64_t *len);
+void gosh_hierarchy_free(gosh_hierarchy *h);
+
 /* ---- device entry points ---------------------------------------------------------- */
 
 /* "Randomly initialize M" (Alg. 2, second line).  Fills the device matrix M (n x d)

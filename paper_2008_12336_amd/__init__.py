@@ -7,8 +7,11 @@ from .binding import (  # noqa: F401
     GOSH_MAX_DIM,
     GOSH_MAX_NEG,
     GoshError,
+    Hierarchy,
     csr_view,
+    gosh_coarsen,
     gosh_csr,
+    gosh_csr_validate,
     gosh_epoch_split,
     gosh_init_embedding,
     gosh_last_error,

@@ -36,6 +36,16 @@ EXPORTS = {
     "gosh_last_error": (C.c_char_p, []),
     "gosh_lr": (C.c_float, [C.c_float, C.c_int64, C.c_int64]),
     "gosh_epoch_split": (C.c_int, [C.c_int64, C.c_double, C.c_int32, C.POINTER(C.c_int64)]),
+    "gosh_csr_validate": (C.c_int, [C.POINTER(gosh_csr)]),
+    "gosh_coarsen": (C.c_int, [C.POINTER(gosh_csr), C.c_int64, C.c_double, C.c_int32, C.c_int32,
+                               C.POINTER(C.c_void_p)]),
+    "gosh_hierarchy_levels": (C.c_int, [C.c_void_p]),
+    "gosh_hierarchy_graph": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(gosh_csr)]),
+    "gosh_hierarchy_map": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
+                                     C.POINTER(C.c_int64)]),
+    "gosh_hierarchy_mult": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int64)),
+                                      C.POINTER(C.c_int64)]),
+    "gosh_hierarchy_free": (None, [C.c_void_p]),
     "gosh_init_embedding": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_uint32,
                                       C.c_void_p]),
     "gosh_sample_epoch": (C.c_int, [C.POINTER(gosh_csr), C.c_int32, C.c_uint64, C.c_uint32,
@@ -137,3 +147,101 @@ def gosh_project(M_coarse: torch.Tensor, map_: torch.Tensor, M_fine: torch.Tenso
     if d != d2 or map_.dtype != torch.int32 or map_.numel() != nf or not map_.is_contiguous():
         raise TypeError("map must be int32 with one entry per fine vertex; dims must agree")
     _check(lib().gosh_project(cptr, nc, map_.data_ptr(), nf, d, fptr, _stream(stream)))
+
+
+def gosh_csr_validate(g: gosh_csr) -> None:
+    """Raise GoshError unless the HOST graph follows the CSR conventions."""
+    _check(lib().gosh_csr_validate(C.byref(g)))
+
+
+class Hierarchy:
+    """Handle of a library-owned coarsening hierarchy.  Arrays are exposed as numpy
+    views of the library's host memory (level 0 is the caller's own graph)."""
+
+    def __init__(self, handle, keep_alive):
+        self._h = handle
+        self._keep = keep_alive  # the level-0 tensors must outlive the hierarchy
+
+    def __del__(self):
+        self.free()
+
+    def free(self) -> None:
+        if getattr(self, "_h", None):
+            lib().gosh_hierarchy_free(self._h)
+            self._h = None
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def levels(self) -> int:
+        return int(lib().gosh_hierarchy_levels(self._h))
+
+    def graph_view(self, i: int) -> gosh_csr:
+        v = gosh_csr()
+        _check(lib().gosh_hierarchy_graph(self._h, i, C.byref(v)))
+        return v
+
+    def graph(self, i: int):
+        """(n, xadj, adj) of G_i as numpy arrays (views, do not write)."""
+        import numpy as np
+
+        v = self.graph_view(i)
+        off_t = C.c_int64 if v.xadj_is64 else C.c_int32
+        xadj = np.ctypeslib.as_array(C.cast(v.xadj, C.POINTER(off_t)), shape=(v.n + 1,))
+        if v.nnz:
+            adj = np.ctypeslib.as_array(C.cast(v.adj, C.POINTER(C.c_int32)), shape=(v.nnz,))
+        else:
+            adj = np.zeros(0, dtype=np.int32)
+        return int(v.n), xadj, adj
+
+    def map(self, i: int):
+        import numpy as np
+
+        ptr = C.POINTER(C.c_int32)()
+        n = C.c_int64()
+        _check(lib().gosh_hierarchy_map(self._h, i, C.byref(ptr), C.byref(n)))
+        return np.ctypeslib.as_array(ptr, shape=(n.value,))
+
+    def mult(self, i: int):
+        import numpy as np
+
+        ptr = C.POINTER(C.c_int64)()
+        n = C.c_int64()
+        _check(lib().gosh_hierarchy_mult(self._h, i, C.byref(ptr), C.byref(n)))
+        if n.value == 0:
+            return None
+        return np.ctypeslib.as_array(ptr, shape=(n.value,))
+
+
+def gosh_coarsen(n: int, xadj: torch.Tensor, adj: torch.Tensor, threshold: int = 100,
+                 min_shrink: float = 1.0, max_levels: int = 64, n_threads: int = 0) -> Hierarchy:
+    """Coarsen a HOST graph (CPU tensors).  The tensors are kept alive by the result."""
+    if xadj.is_cuda or adj.is_cuda:
+        raise TypeError("gosh_coarsen takes host (CPU) tensors")
+    g = csr_view(n, xadj, adj)
+    out = C.c_void_p()
+    _check(lib().gosh_coarsen(C.byref(g), threshold, min_shrink, max_levels, n_threads,
+                              C.byref(out)))
+    return Hierarchy(out, (xadj, adj))
+
+
+def gosh_hierarchy_levels(h: Hierarchy) -> int:
+    return h.levels
+
+
+def gosh_hierarchy_graph(h: Hierarchy, i: int):
+    return h.graph(i)
+
+
+def gosh_hierarchy_map(h: Hierarchy, i: int):
+    return h.map(i)
+
+
+def gosh_hierarchy_mult(h: Hierarchy, i: int):
+    return h.mult(i)
+
+
+def gosh_hierarchy_free(h: Hierarchy) -> None:
+    h.free()

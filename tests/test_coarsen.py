@@ -1,0 +1,112 @@
+"""gosh_coarsen (host C++) against the oracle's Alg. 4: maps and graphs bit-exact."""
+import numpy as np
+import pytest
+import torch
+from hypothesis import given, settings, strategies as st
+
+import graphgen
+import paper_2008_12336_amd as G
+from oracle import gosh_oracle as O
+from tests.util import csr_from_pairs
+
+
+def product_hierarchy(n, xadj, adj, offsets64, **kw):
+    xt = torch.from_numpy(np.asarray(xadj, dtype=np.int64 if offsets64 else np.int32))
+    at = torch.from_numpy(np.asarray(adj, dtype=np.int32))
+    return G.gosh_coarsen(n, xt, at, **kw)
+
+
+def assert_same_hierarchy(h, graphs, maps, mults):
+    assert h.levels == len(graphs)
+    for i, (xo, ao) in enumerate(graphs):
+        n, x, a = h.graph(i)
+        assert n == xo.size - 1
+        assert np.array_equal(np.asarray(x, dtype=np.int64), xo)
+        assert np.array_equal(a, ao)
+        m = h.mult(i)
+        if i == 0:
+            assert m is None
+        else:
+            assert np.array_equal(np.zeros(0, dtype=np.int64) if m is None else m, mults[i])
+    for i, mo in enumerate(maps):
+        assert np.array_equal(h.map(i), mo)
+
+
+CASES = {
+    "er1024": lambda: (1024, graphgen.er_gnm(1024, 8192, 1)),
+    "rmat4096": lambda: (4096, graphgen.rmat(12, 1 << 15, 2)),
+    "cl5000": lambda: (5000, graphgen.chung_lu(5000, 40000, 3)),
+    "rmat65536": lambda: (1 << 16, graphgen.rmat(16, 1 << 19, 5)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+@pytest.mark.parametrize("offsets64", [False, True])
+@pytest.mark.parametrize("threads", [1, 5])
+def test_hierarchy_matches_oracle(name, offsets64, threads):
+    n, edges = CASES[name]()
+    c = graphgen.to_csr(n, edges)
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    for kw in (dict(threshold=100, min_shrink=1.0), dict(threshold=50, min_shrink=0.8),
+               dict(threshold=10, min_shrink=1.0, max_levels=3)):
+        graphs, maps, mults = O.coarsen(xadj, adj, **kw)
+        h = product_hierarchy(n, xadj, adj, offsets64, n_threads=threads, **kw)
+        assert_same_hierarchy(h, graphs, maps, mults)
+        assert h.levels >= 2
+        h.free()
+
+
+graphs_st = st.integers(min_value=2, max_value=60).flatmap(
+    lambda n: st.tuples(st.just(n), st.lists(
+        st.tuples(st.integers(0, n - 1), st.integers(0, n - 1)), min_size=0, max_size=5 * n)))
+
+
+@settings(max_examples=100, deadline=None)
+@given(graphs_st)
+def test_random_tiny_graphs_match_oracle(g):
+    n, pairs = g
+    xadj, adj = csr_from_pairs(n, pairs)
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=1, min_shrink=1.0)
+    h = product_hierarchy(n, xadj, adj, False, threshold=1, min_shrink=1.0, n_threads=3)
+    assert_same_hierarchy(h, graphs, maps, mults)
+
+
+def test_edge_cases():
+    # at or below the threshold: nothing to build
+    xadj, adj = csr_from_pairs(5, [(0, 1), (1, 2)])
+    h = product_hierarchy(5, xadj, adj, False, threshold=5)
+    assert h.levels == 1
+    n, x, a = h.graph(0)
+    assert n == 5 and np.array_equal(a, adj)
+    with pytest.raises(G.GoshError):
+        h.map(0)
+    # edgeless graph: no progress, one extra level, identity map
+    xe = np.zeros(301, dtype=np.int64)
+    h = product_hierarchy(300, xe, np.zeros(0, dtype=np.int32), True, threshold=100, min_shrink=0.8)
+    assert h.levels == 2 and h.map(0).tolist() == list(range(300))
+    assert h.graph(1)[0] == 300 and h.graph(1)[2].size == 0
+    # bad arguments
+    for kw in (dict(threshold=0), dict(min_shrink=0.0), dict(min_shrink=1.5), dict(max_levels=0)):
+        with pytest.raises(G.GoshError):
+            product_hierarchy(5, xadj, adj, False, **kw)
+
+
+def test_csr_validate():
+    xadj, adj = csr_from_pairs(6, [(0, 1), (1, 2), (2, 5)])
+    xt, at = torch.from_numpy(xadj), torch.from_numpy(adj)
+    G.gosh_csr_validate(G.csr_view(6, xt, at))
+    bad = at.clone(); bad[0] = 9
+    with pytest.raises(G.GoshError, match="out of range"):
+        G.gosh_csr_validate(G.csr_view(6, xt, bad))
+    bad = at.clone(); bad[0] = 0  # vertex 0 lists itself
+    with pytest.raises(G.GoshError, match="self loop"):
+        G.gosh_csr_validate(G.csr_view(6, xt, bad))
+    bad = at.clone(); bad[1], bad[2] = at[2].item(), at[1].item()  # row of vertex 1 descending
+    with pytest.raises(G.GoshError, match="ascending"):
+        G.gosh_csr_validate(G.csr_view(6, xt, bad))
+    badx = xt.clone(); badx[-1] = xt[-1] + 1
+    with pytest.raises(G.GoshError, match="nnz"):
+        G.gosh_csr_validate(G.csr_view(6, badx, at))
+    badx = xt.clone(); badx[2] = 0
+    with pytest.raises(G.GoshError):
+        G.gosh_csr_validate(G.csr_view(6, badx, at))
