@@ -160,6 +160,33 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev,
                  int64_t n_fine, int32_t d, float *M_fine_dev, void *hip_stream);
 
+/* ---- multilevel driver ---------------------------------------------------------------- */
+
+typedef struct {
+  int32_t level;     /* i */
+  int64_t n, nnz;    /* size of G_i */
+  int64_t epochs;    /* e_i */
+  double upload_ms;  /* host -> device copy of G_i (wall clock) */
+  double train_ms;   /* the e_i epoch launches (HIP events on the stream) */
+  double project_ms; /* map upload + projection to level i-1 (wall clock; 0 at level 0) */
+} gosh_level_stats;
+
+/* Alg. 2 ("GOSH") for levels that fit the device: with D = levels of h and
+ * e_i = gosh_epoch_split(epochs, p, D), for i = D-1 down to 0: copy G_i to the device,
+ * (i = D-1: initialise M_{D-1} with gosh_init_embedding(seed, level D-1)), run e_i epochs
+ * of gosh_train_epoch with lr = gosh_lr(lr0, j, e_i), epoch j and level i in the random
+ * counter, then (i > 0) project to level i-1 with map_{i-1}.  The paper prints the loop
+ * as "D-1 to 1"; the text trains until M_0 is obtained, which is what is done here.
+ * h: hierarchy (host).  M0_dev: device matrix n_0 x d, receives the embedding of G_0.
+ * flags: as for gosh_train_epoch.  device_budget_bytes: if non-zero, a level whose
+ * graph plus matrix exceed it is refused with GOSH_EBUDGET (use gosh_train_parts for
+ * such a level).  stats: NULL or host array of D entries, filled per level.
+ * Blocking: returns after the last level finished; intermediate device buffers are
+ * allocated and freed inside the call. */
+int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p,
+               float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
+               float *M0_dev, gosh_level_stats *stats, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -237,6 +237,21 @@ def coarsen(xadj, adj, threshold=100, min_shrink=0.8, max_levels=64):
     return graphs, maps, mults
 
 
+def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, max_levels=64):
+    """Alg. 2: coarsen, initialise M_{D-1}, then for i = D-1..0 train e_i epochs on G_i and
+    (i > 0) project to G_{i-1}.  READING: the printed loop bound "D-1 to 1" would never
+    train G_0; the text trains until M_0 is obtained.  Returns (M_0, graphs, maps, e_i)."""
+    graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink, max_levels)
+    D = len(graphs)
+    e_i = epoch_split(epochs, p, D)
+    M = init_embedding(graphs[-1][0].size - 1, d, seed, D - 1)
+    for i in range(D - 1, -1, -1):
+        train_level(graphs[i][0], graphs[i][1], M, k, lr0, int(e_i[i]), seed, i)
+        if i > 0:
+            M = project(M, maps[i - 1])
+    return M, graphs, maps, e_i
+
+
 def pair_order(K):
     npairs = K * (K + 1) // 2
     a = np.zeros(npairs, dtype=np.int32)

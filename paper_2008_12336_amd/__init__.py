@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     gosh_coarsen,
     gosh_csr,
     gosh_csr_validate,
+    gosh_embed,
     gosh_epoch_split,
     gosh_init_embedding,
     gosh_last_error,

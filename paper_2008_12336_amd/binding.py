@@ -32,6 +32,11 @@ class gosh_csr(C.Structure):
                 ("adj", C.c_void_p), ("xadj_is64", C.c_int32)]
 
 
+class gosh_level_stats(C.Structure):
+    _fields_ = [("level", C.c_int32), ("n", C.c_int64), ("nnz", C.c_int64), ("epochs", C.c_int64),
+                ("upload_ms", C.c_double), ("train_ms", C.c_double), ("project_ms", C.c_double)]
+
+
 EXPORTS = {
     "gosh_last_error": (C.c_char_p, []),
     "gosh_lr": (C.c_float, [C.c_float, C.c_int64, C.c_int64]),
@@ -53,6 +58,9 @@ EXPORTS = {
     "gosh_train_epoch": (C.c_int, [C.POINTER(gosh_csr), C.c_void_p, C.c_int32, C.c_int32,
                                    C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.c_void_p]),
+    "gosh_embed": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_float,
+                             C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p,
+                             C.POINTER(gosh_level_stats), C.c_void_p]),
     "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                C.c_void_p, C.c_void_p]),
 }
@@ -245,3 +253,17 @@ def gosh_hierarchy_mult(h: Hierarchy, i: int):
 
 def gosh_hierarchy_free(h: Hierarchy) -> None:
     h.free()
+
+
+def gosh_embed(h: Hierarchy, M0: torch.Tensor, k_neg: int, epochs: int, p: float, lr0: float,
+               seed: int, flags: int = 0, device_budget_bytes: int = 0, stream=None):
+    """Multilevel training into the device matrix M0 (n_0 x d); returns per-level stats."""
+    ptr, n0, d = _matrix(M0, "M0")
+    if n0 != h.graph_view(0).n:
+        raise ValueError("M0 must have one row per vertex of G_0")
+    D = h.levels
+    stats = (gosh_level_stats * D)()
+    _check(lib().gosh_embed(h.handle, d, k_neg, epochs, p, lr0, seed, flags, device_budget_bytes,
+                            ptr, stats, _stream(stream)))
+    return [dict(level=s.level, n=s.n, nnz=s.nnz, epochs=s.epochs, upload_ms=s.upload_ms,
+                 train_ms=s.train_ms, project_ms=s.project_ms) for s in stats]
