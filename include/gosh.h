@@ -187,6 +187,64 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
                float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
                float *M0_dev, gosh_level_stats *stats, void *hip_stream);
 
+/* ---- graphs larger than a device budget (Sec. 3.3, Alg. 5 "LargeGraphGPU") -------------- */
+
+typedef struct {
+  int32_t K;             /* number of parts (contiguous ranges of ceil(n/K) vertices) */
+  int64_t rotations;     /* ceil(epochs / (B*K)), at least 1 */
+  int64_t pair_visits;   /* rotations * K(K+1)/2 pair kernels */
+  int64_t updates;       /* updates of Alg. 1 attempted (sources * B * (k_neg+1) per visit) */
+  uint64_t device_bytes; /* part slots + sample pools + hot-row bitmap */
+  uint64_t bytes_h2d;    /* parts and pools copied to the device */
+  uint64_t bytes_d2h;    /* parts copied back */
+  double kernel_ms;      /* sum of the pair kernels' durations (HIP events) */
+  double wall_ms;        /* whole call, host wall clock */
+} gosh_parts_stats;
+
+/* Visiting order of the part pairs in one rotation (Sec. 3.3.1): (0,0), (1,0), (1,1),
+ * (2,0), ... -- K(K+1)/2 pairs written to a[] and b[] (host arrays), a[j] >= b[j]. */
+int gosh_pair_order(int32_t K, int32_t *a, int32_t *b);
+
+/* The part layout gosh_train_parts would use: the smallest K for which min(P_gpu, K) part
+ * slots of ceil(n/K) rows, S_gpu sample pools of 2*ceil(n/K)*B ids and the hot-row bitmap
+ * fit device_budget_bytes; rotations = ceil(epochs/(B*K)) (Alg. 5, first line).  Any of
+ * the output pointers may be NULL.  GOSH_EBUDGET if no K up to min(n, 4096) fits. */
+int gosh_parts_plan(int64_t n, int32_t d, int64_t epochs, uint64_t device_budget_bytes,
+                    int32_t P_gpu, int32_t S_gpu, int32_t B, int32_t *K_out,
+                    int64_t *rotations_out, uint64_t *device_bytes_out);
+
+/* Parity/debug: the sample ids of one visit of the pair (pa, pb), pb <= pa, in the order
+ * the sequential reference applies them: for every vertex of part pa, B rounds of
+ * (positive, k_neg negatives), then -- if pa != pb -- the same for every vertex of part pb.
+ * Positive of a vertex: uniform member of its neighbours inside the partner part, -1 if
+ * none; negatives: uniform over the partner part.  Draw t of a source uses
+ * Philox4x32-10(counter = (src, side*B*(k_neg+1) + t, rotation,
+ * (level & 255) | (pair_index+1) << 8), key = seed).  Positives are drawn on the host,
+ * negatives on the device, exactly as in training.  g_host: host CSR; out_host: host
+ * int32[(size(pa) + size(pb))*B*(k_neg+1)] (only size(pa) sources if pa == pb). */
+int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_t pb, int32_t B,
+                           int32_t k_neg, uint64_t seed, uint32_t rotation, uint32_t level,
+                           uint32_t pair_index, int32_t *out_host);
+
+/* Alg. 5 for one level: the matrix stays on the host, K parts rotate through P_gpu device
+ * slots, every pair of parts is trained against each other once per rotation (in the
+ * order of gosh_pair_order) for `rotations` rotations, with lr = gosh_lr(lr0, r, rotations)
+ * in rotation r.  In a visit of (a, b) every vertex of a runs B rounds of one positive
+ * update (a neighbour inside b, drawn on the host into a pool that is shipped to the
+ * device) and k_neg negative updates (drawn on the device, uniform over b), and vice versa;
+ * a vertex without a neighbour in the partner part gets no positive update there.
+ * g_host: host CSR.  M_host: host matrix n x d, updated in place; pinned memory makes the
+ * transfers asynchronous.  device_budget_bytes: cap for slots + pools + bitmap (0 only
+ * together with force_K > 0).  P_gpu >= 2 (paper: 3), S_gpu >= 1 (paper: 4), B >= 1
+ * (paper: 5).  force_K > 0 overrides the part count.  flags as for gosh_train_epoch
+ * (GOSH_FLAG_SEQUENTIAL: every pair kernel runs on one wavefront, sources in order).
+ * The library owns its streams, device buffers and sampler thread for the duration of
+ * the call, which blocks until the matrix is back on the host.  stats_out may be NULL. */
+int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k_neg,
+                     int64_t epochs, float lr0, uint64_t seed, uint32_t level,
+                     uint64_t device_budget_bytes, int32_t P_gpu, int32_t S_gpu, int32_t B,
+                     int32_t force_K, uint32_t flags, gosh_parts_stats *stats_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,6 +37,12 @@ class gosh_level_stats(C.Structure):
                 ("upload_ms", C.c_double), ("train_ms", C.c_double), ("project_ms", C.c_double)]
 
 
+class gosh_parts_stats(C.Structure):
+    _fields_ = [("K", C.c_int32), ("rotations", C.c_int64), ("pair_visits", C.c_int64),
+                ("updates", C.c_int64), ("device_bytes", C.c_uint64), ("bytes_h2d", C.c_uint64),
+                ("bytes_d2h", C.c_uint64), ("kernel_ms", C.c_double), ("wall_ms", C.c_double)]
+
+
 EXPORTS = {
     "gosh_last_error": (C.c_char_p, []),
     "gosh_lr": (C.c_float, [C.c_float, C.c_int64, C.c_int64]),
@@ -61,6 +67,17 @@ EXPORTS = {
     "gosh_embed": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_float,
                              C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p,
                              C.POINTER(gosh_level_stats), C.c_void_p]),
+    "gosh_pair_order": (C.c_int, [C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "gosh_parts_plan": (C.c_int, [C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_int32, C.c_int32,
+                                  C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                                  C.POINTER(C.c_uint64)]),
+    "gosh_parts_sample_pair": (C.c_int, [C.POINTER(gosh_csr), C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_int32, C.c_int32, C.c_uint64, C.c_uint32, C.c_uint32,
+                                         C.c_uint32, C.c_void_p]),
+    "gosh_train_parts": (C.c_int, [C.POINTER(gosh_csr), C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+                                   C.c_float, C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
+                                   C.c_int32, C.c_int32, C.c_int32, C.c_uint32,
+                                   C.POINTER(gosh_parts_stats)]),
     "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                C.c_void_p, C.c_void_p]),
 }
@@ -267,3 +284,58 @@ def gosh_embed(h: Hierarchy, M0: torch.Tensor, k_neg: int, epochs: int, p: float
                             ptr, stats, _stream(stream)))
     return [dict(level=s.level, n=s.n, nnz=s.nnz, epochs=s.epochs, upload_ms=s.upload_ms,
                  train_ms=s.train_ms, project_ms=s.project_ms) for s in stats]
+
+
+def gosh_pair_order(K: int):
+    """[(a_0, b_0), (a_1, b_1), ...]: the order in which part pairs are visited."""
+    npairs = K * (K + 1) // 2 if K > 0 else 1
+    a = (C.c_int32 * npairs)()
+    b = (C.c_int32 * npairs)()
+    _check(lib().gosh_pair_order(K, a, b))
+    return list(zip(list(a), list(b)))
+
+
+def gosh_parts_plan(n: int, d: int, epochs: int, device_budget_bytes: int, P_gpu: int = 3,
+                    S_gpu: int = 4, B: int = 5):
+    K = C.c_int32()
+    rot = C.c_int64()
+    nbytes = C.c_uint64()
+    _check(lib().gosh_parts_plan(n, d, epochs, device_budget_bytes, P_gpu, S_gpu, B, C.byref(K),
+                                 C.byref(rot), C.byref(nbytes)))
+    return dict(K=K.value, rotations=rot.value, device_bytes=nbytes.value)
+
+
+def _host_csr(n, xadj, adj):
+    if xadj.is_cuda or adj.is_cuda:
+        raise TypeError("this entry point takes host (CPU) graph tensors")
+    return csr_view(n, xadj, adj)
+
+
+def gosh_parts_sample_pair(n: int, xadj: torch.Tensor, adj: torch.Tensor, K: int, pa: int, pb: int,
+                           B: int, k_neg: int, seed: int, rotation: int, level: int,
+                           pair_index: int) -> torch.Tensor:
+    g = _host_csr(n, xadj, adj)
+    ps = -(-n // K)
+    size = lambda p: max(0, min(n, (p + 1) * ps) - min(n, p * ps))
+    sources = size(pa) + (size(pb) if pa != pb else 0)
+    out = torch.full((sources * B * (k_neg + 1),), -2, dtype=torch.int32)
+    _check(lib().gosh_parts_sample_pair(C.byref(g), K, pa, pb, B, k_neg, seed, rotation, level,
+                                        pair_index, out.data_ptr()))
+    return out
+
+
+def gosh_train_parts(n: int, xadj: torch.Tensor, adj: torch.Tensor, M_host: torch.Tensor,
+                     k_neg: int, epochs: int, lr0: float, seed: int, level: int = 0,
+                     device_budget_bytes: int = 0, P_gpu: int = 3, S_gpu: int = 4, B: int = 5,
+                     force_K: int = 0, flags: int = 0):
+    """Train a HOST matrix (ideally pinned) in place with the part-pair rotation."""
+    g = _host_csr(n, xadj, adj)
+    if M_host.is_cuda:
+        raise TypeError("M_host must be a host tensor (the rotation moves its parts itself)")
+    ptr, rows, d = _matrix(M_host, "M_host")
+    if rows != n:
+        raise ValueError("M_host must have one row per vertex")
+    st = gosh_parts_stats()
+    _check(lib().gosh_train_parts(C.byref(g), ptr, d, k_neg, epochs, lr0, seed, level,
+                                  device_budget_bytes, P_gpu, S_gpu, B, force_K, flags, C.byref(st)))
+    return {name: getattr(st, name) for name, _ in gosh_parts_stats._fields_}

@@ -24,4 +24,26 @@ inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 // Turns a failed launch into GOSH_EHIP.
 int check_launch(const char *kernel);
 
+// Tuning / experiment overrides, read once from the environment.
+//   GOSH_ROW_POLICY=0      plain 128-bit row accesses also in the concurrent kernels
+//                          (coherent inside one XCD only)
+//   GOSH_MAX_WAVES         cap on the wavefronts that share the sources of a launch
+//   GOSH_HOT_INV_EPS       1/eps of the hot-row degree rule (default 64)
+//   GOSH_HOT_ALL_INV_EPS   1/eps of the "every row is hot" rule (default 4)
+struct Tuning {
+  int row_policy;
+  int64_t max_waves;
+  int64_t hot_inv_eps;
+  int64_t hot_all_inv_eps;
+};
+const Tuning &tuning();
+
+// Wavefronts the device keeps resident (8 on each of the 4 SIMDs of every CU).
+int resident_waves();
+
+// Per-device scratch for the hot-row bitmap (one bit per vertex), grown on demand and
+// kept until the process ends.  Calls on one device must not overlap on different
+// streams.
+int hot_scratch(size_t bytes, void **out);
+
 }  // namespace gosh

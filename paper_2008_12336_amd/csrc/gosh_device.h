@@ -1,0 +1,346 @@
+// Device-side building blocks of libgosh shared by the epoch kernel (Alg. 3) and the
+// part-pair kernel (Alg. 5): the counter-based generator, the cross-lane reduction,
+// the row access policies and the generic lock-free SGD kernel.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace gosh {
+
+// ---------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  Returns the first two output words as one
+// 64-bit draw; w2/w3 optionally receive the other two.  Usable on host and device.
+// ---------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ uint32_t mul_hi32(uint32_t a, uint32_t b) {
+  return static_cast<uint32_t>((static_cast<uint64_t>(a) * b) >> 32);
+}
+
+__host__ __device__ __forceinline__ uint64_t philox_draw(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                         uint32_t c3, uint32_t k0, uint32_t k1,
+                                                         uint32_t *w2 = nullptr,
+                                                         uint32_t *w3 = nullptr) {
+  constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
+  constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hiA = mul_hi32(kMulA, c0), loA = kMulA * c0;
+    const uint32_t hiB = mul_hi32(kMulB, c2), loB = kMulB * c2;
+    c0 = hiB ^ c1 ^ k0;
+    c1 = loB;
+    c2 = hiA ^ c3 ^ k1;
+    c3 = loA;
+    k0 += kWeylA;
+    k1 += kWeylB;
+  }
+  if (w2) *w2 = c2;
+  if (w3) *w3 = c3;
+  return static_cast<uint64_t>(c0) | (static_cast<uint64_t>(c1) << 32);
+}
+
+// floor(r * bound / 2^64) for bound < 2^32.
+__host__ __device__ __forceinline__ uint32_t scale_draw(uint64_t r, uint32_t bound) {
+  const uint32_t lo = static_cast<uint32_t>(r), hi = static_cast<uint32_t>(r >> 32);
+  const uint64_t t = static_cast<uint64_t>(hi) * bound + mul_hi32(lo, bound);
+  return static_cast<uint32_t>(t >> 32);
+}
+
+// ---------------------------------------------------------------------------------
+// Sum over the LPG lanes of a group; every lane of the group gets the total.
+// Steps inside a 16-lane row use DPP (no LDS traffic); 32 and 64 lanes finish with
+// swizzle / bpermute.
+// ---------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+
+template <int LPG>
+__device__ __forceinline__ float group_sum(float x) {
+  if (LPG >= 2) x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
+  if (LPG >= 4) x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
+  if (LPG >= 8) x += dpp_move<0x141>(x);   // row_half_mirror (quads already uniform)
+  if (LPG >= 16) x += dpp_move<0x140>(x);  // row_mirror (halves already uniform)
+  if (LPG >= 32) x += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), 0x401F));  // lane ^ 16
+  if (LPG >= 64) x += __shfl_xor(x, 32, 64);
+  return x;
+}
+
+// ---------------------------------------------------------------------------------
+// Row access policies.  A row is moved in "units" of F floats per lane.
+//
+// The chip's eight XCDs each have their own L2, and plain stores sit in the writer's
+// L2 until they are evicted or the kernel ends: with plain accesses a row updated on
+// one XCD is read stale on the others and the last write-back wins.  Lock-free SGD
+// needs the rows to be coherent across the whole device, so the concurrent kernels
+// move rows with agent-scope (device-scope) accesses, which are served behind the
+// per-XCD L2s.  Every sample row is touched once per turn, so no L2 reuse is lost.
+//   RowAgent32: 32-bit relaxed atomic loads and stores at agent scope, lanes interleaved
+//     over the row (lane g owns floats g, g+LPG, ...) so that every access instruction
+//     of a group covers one whole 128-byte line.  Measured on a 2^24-vertex graph this
+//     is as fast as wider per-lane accesses, and it makes the atomic adds used for hot
+//     rows (below) dense: one line per instruction instead of half-filled lines, which
+//     the memory-side atomic units process at half the rate.
+//   RowPlain128: ordinary 128-bit accesses (coherent only inside one XCD); used by the
+//     sequential-order mode, which runs on a single wavefront.
+// ---------------------------------------------------------------------------------
+template <int F>
+struct Unit {
+  float v[F];
+};
+
+__device__ __forceinline__ void atomic_step(float *p, float x) {
+  // Built with -munsafe-fp-atomics: the matrix is ordinary coarse-grained device
+  // memory, where the hardware fp32 add is available.
+  __hip_atomic_fetch_add(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct RowPlain128 {
+  static constexpr int F = 4;
+  static __device__ __forceinline__ Unit<4> load(const float *p) {
+    const float4 x = *reinterpret_cast<const float4 *>(p);
+    return Unit<4>{{x.x, x.y, x.z, x.w}};
+  }
+  static __device__ __forceinline__ void store(float *p, const Unit<4> &u) {
+    *reinterpret_cast<float4 *>(p) = float4{u.v[0], u.v[1], u.v[2], u.v[3]};
+  }
+};
+
+struct RowAgent32 {
+  static constexpr int F = 1;
+  static __device__ __forceinline__ Unit<1> load(const float *p) {
+    return Unit<1>{{__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)}};
+  }
+  static __device__ __forceinline__ void store(float *p, const Unit<1> &u) {
+    __hip_atomic_store(p, u.v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+};
+
+// ---------------------------------------------------------------------------------
+// Hot rows.  A lock-free update is a read-modify-write of a row; when two wavefronts
+// hold the same row at once, one of the two writes is lost (Sec. 3.1 of the paper
+// accepts such races, and reports that too many of them hurt the embedding).  With
+// C sources in flight out of n, a row that is touched h times per epoch has about
+// h*C/n concurrent holders.  Rows for which that is not small -- every row of a
+// small graph, the high-degree vertices of a large one, which are drawn as positive
+// samples in proportion to their degree -- are "hot": their updates are applied as
+// atomic adds of the step (M[v] += g*M[src], and M[src] += its accumulated change),
+// which cannot be lost.  Cold rows are written back with plain stores, which cost
+// half as much on this memory system.
+// ---------------------------------------------------------------------------------
+enum HotMode : int32_t { kHotNone = 0, kHotBitmap = 1, kHotAll = 2 };
+
+struct HotSet {
+  const uint32_t *bits;  // one bit per vertex, used when mode == kHotBitmap
+  int32_t mode;
+  __device__ __forceinline__ bool contains(int32_t v) const {
+    if (mode == kHotBitmap) return (bits[v >> 5] >> (v & 31)) & 1u;
+    return mode == kHotAll;
+  }
+};
+
+struct SgdArgs {
+  HotSet hot;
+  int32_t d;
+  int32_t k_neg;    // sample t of a source is a positive iff t % (k_neg + 1) == 0
+  int32_t samples;  // samples per source: k_neg + 1 per round
+  float lr;
+  int64_t active_waves;  // wavefronts that take part; the rest of the grid exits at once
+};
+
+constexpr int kChunk = 4;  // sample rows in flight per source
+
+// The lock-free SGD kernel.  Every source applies `samples` updates of Alg. 1 in order:
+//   g = lr * (b - sigmoid(M[src] . M[v]));  M[src] += g*M[v];  M[v] += g*M[src]
+// with the source row held in registers for its whole turn.
+//   W (work description, passed by value) provides
+//     int64_t count()                         number of sources
+//     int32_t source_id(int64_t i)            vertex id of source i (random counter, self test)
+//     float  *source_row(int64_t i)
+//     int32_t sample(int64_t i, int32_t id, int32_t t)   vertex id of sample t, or -1 = none
+//     float  *sample_row(int64_t i, int32_t v)
+//   P: row access policy; LPG lanes per source, UPL units per lane (LPG*UPL*P::F >= d).
+//   SEQ: a single lane group walks all sources in ascending index (the sequential-order
+//   result); otherwise lane groups stride over the sources.
+template <class P, int LPG, int UPL, class W, bool SEQ>
+__global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
+  constexpr int kGroupsPerWave = 64 / LPG;
+  constexpr int F = P::F;
+  using U = Unit<F>;
+  const int lane = threadIdx.x & 63;
+  const int gl = lane & (LPG - 1);
+  if (SEQ && (lane >= LPG || threadIdx.x >= 64 || blockIdx.x != 0)) return;
+
+  const int64_t wave = blockIdx.x * static_cast<int64_t>(blockDim.x / 64) + (threadIdx.x >> 6);
+  if (!SEQ && wave >= a.active_waves) return;
+  const int64_t n = w.count();
+  const int64_t stride = SEQ ? 1 : a.active_waves * kGroupsPerWave;
+  const int64_t first = SEQ ? 0 : wave * kGroupsPerWave + lane / LPG;
+  const int32_t d = a.d;
+  const int32_t per_round = a.k_neg + 1;
+
+  // Lane gl owns floats [(gl + i*LPG)*F, +F) of a row, i < UPL: consecutive lanes touch
+  // consecutive addresses, so each access instruction covers whole cache lines.
+  int32_t col[UPL];
+  bool col_ok[UPL];
+#pragma unroll
+  for (int i = 0; i < UPL; ++i) {
+    col[i] = (gl + i * LPG) * F;
+    col_ok[i] = col[i] < d;
+  }
+  const U zero{};
+
+  // The loop bound is uniform over the wave; groups past the end idle inside.
+  const int64_t first_of_wave = SEQ ? 0 : wave * kGroupsPerWave;
+  for (int64_t base = first_of_wave; base < n; base += stride) {
+    const int64_t idx = first + (base - first_of_wave);
+    if (idx >= n) continue;
+    const int32_t src = w.source_id(idx);
+    float *const src_row = w.source_row(idx);
+    U s[UPL];
+#pragma unroll
+    for (int i = 0; i < UPL; ++i) s[i] = col_ok[i] ? P::load(src_row + col[i]) : zero;
+    const bool src_hot = !SEQ && a.hot.contains(src);
+    U s_before[UPL];
+#pragma unroll
+    for (int i = 0; i < UPL; ++i) s_before[i] = s[i];
+
+    for (int32_t t0 = 0; t0 < a.samples; t0 += kChunk) {
+      // Sample ids of this chunk: lane q of the group evaluates sample t0+q, then the
+      // ids are broadcast inside the group.
+      int32_t v[kChunk];
+#pragma unroll
+      for (int p = 0; p < kChunk; p += LPG) {
+        const int32_t t = t0 + p + gl;
+        int32_t mine = -1;
+        if (p + gl < kChunk && t < a.samples) mine = w.sample(idx, src, t);
+#pragma unroll
+        for (int q = 0; q < LPG && p + q < kChunk; ++q) v[p + q] = __shfl(mine, q, LPG);
+      }
+      // A sample that hits the source itself applies no update.
+#pragma unroll
+      for (int q = 0; q < kChunk; ++q)
+        if (v[q] == src) v[q] = -1;
+
+      // Fetch all rows of the chunk before using any of them.
+      U r[kChunk][UPL];
+      float *row[kChunk];
+      bool hot[kChunk];
+#pragma unroll
+      for (int q = 0; q < kChunk; ++q) {
+        row[q] = v[q] >= 0 ? w.sample_row(idx, v[q]) : src_row;
+#pragma unroll
+        for (int i = 0; i < UPL; ++i) r[q][i] = (v[q] >= 0 && col_ok[i]) ? P::load(row[q] + col[i]) : zero;
+        hot[q] = !SEQ && v[q] >= 0 && a.hot.contains(v[q]);
+      }
+
+#pragma unroll
+      for (int q = 0; q < kChunk; ++q) {
+        if (v[q] < 0) continue;  // uniform over the group
+        float partial = 0.f;
+#pragma unroll
+        for (int i = 0; i < UPL; ++i)
+#pragma unroll
+          for (int c = 0; c < F; ++c) partial = fmaf(s[i].v[c], r[q][i].v[c], partial);
+        const float x = group_sum<LPG>(partial);
+        const float label = ((t0 + q) % per_round == 0) ? 1.f : 0.f;
+        const float g = a.lr * (label - 1.f / (1.f + expf(-x)));
+#pragma unroll
+        for (int i = 0; i < UPL; ++i)
+#pragma unroll
+          for (int c = 0; c < F; ++c) {
+            s[i].v[c] = fmaf(g, r[q][i].v[c], s[i].v[c]);
+            r[q][i].v[c] = fmaf(g, s[i].v[c], r[q][i].v[c]);
+          }
+        if (hot[q]) {  // uniform over the group
+#pragma unroll
+          for (int i = 0; i < UPL; ++i)
+#pragma unroll
+            for (int c = 0; c < F; ++c)
+              if (col_ok[i]) atomic_step(row[q] + col[i] + c, g * s[i].v[c]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < UPL; ++i)
+            if (col_ok[i]) P::store(row[q] + col[i], r[q][i]);
+        }
+        // A later sample of the same chunk that names the same vertex must see this
+        // update: forward the registers instead of the stale prefetched copy.
+#pragma unroll
+        for (int z = q + 1; z < kChunk; ++z)
+          if (v[z] == v[q]) {
+#pragma unroll
+            for (int i = 0; i < UPL; ++i) r[z][i] = r[q][i];
+          }
+      }
+    }
+    if (src_hot) {
+#pragma unroll
+      for (int i = 0; i < UPL; ++i)
+#pragma unroll
+        for (int c = 0; c < F; ++c)
+          if (col_ok[i]) atomic_step(src_row + col[i] + c, s[i].v[c] - s_before[i].v[c]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < UPL; ++i)
+        if (col_ok[i]) P::store(src_row + col[i], s[i]);
+    }
+  }
+}
+
+// Launches sgd_kernel for a given dimension: picks the lane-group size (the smallest
+// power of two covering d/4 128-bit vectors, two vectors per lane above 64) and the
+// row policy (plain 128-bit in sequential mode, interleaved agent-scope 32-bit
+// otherwise).  `a.active_waves` is filled in here from `count`.
+template <class W>
+struct SgdLauncher {
+  template <class P, int LPG, int UPL>
+  static void run(const W &w, SgdArgs a, int64_t count, bool seq, int64_t max_waves, hipStream_t st) {
+    constexpr int kWavesPerBlock = 4;
+    constexpr int kGroupsPerWave = 64 / LPG;
+    int64_t waves = (count + kGroupsPerWave - 1) / kGroupsPerWave;
+    if (waves > max_waves) waves = max_waves;
+    if (waves < 1) waves = 1;
+    a.active_waves = waves;
+    if (seq) {
+      hipLaunchKernelGGL((sgd_kernel<P, LPG, UPL, W, true>), dim3(1), dim3(64), 0, st, w, a);
+    } else {
+      const int blocks = static_cast<int>((waves + kWavesPerBlock - 1) / kWavesPerBlock);
+      hipLaunchKernelGGL((sgd_kernel<P, LPG, UPL, W, false>), dim3(blocks), dim3(256), 0, st, w, a);
+    }
+  }
+
+  template <int LPG, int V128>
+  static void pick_policy(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
+                          int64_t max_waves, hipStream_t st) {
+    if (seq || plain_rows) run<RowPlain128, LPG, V128>(w, a, count, seq, max_waves, st);
+    else run<RowAgent32, LPG, 4 * V128>(w, a, count, seq, max_waves, st);
+  }
+
+  static void launch(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
+                     int64_t max_waves, hipStream_t st) {
+    const int d4 = a.d / 4;
+    int lpg = 1;
+    while (lpg < d4 && lpg < 64) lpg *= 2;
+    if (d4 > 64) return pick_policy<64, 2>(w, a, count, seq, plain_rows, max_waves, st);
+    switch (lpg) {
+      case 64: return pick_policy<64, 1>(w, a, count, seq, plain_rows, max_waves, st);
+      case 32: return pick_policy<32, 1>(w, a, count, seq, plain_rows, max_waves, st);
+      case 16: return pick_policy<16, 1>(w, a, count, seq, plain_rows, max_waves, st);
+      case 8: return pick_policy<8, 1>(w, a, count, seq, plain_rows, max_waves, st);
+      case 4: return pick_policy<4, 1>(w, a, count, seq, plain_rows, max_waves, st);
+      case 2: return pick_policy<2, 1>(w, a, count, seq, plain_rows, max_waves, st);
+      default: return pick_policy<1, 1>(w, a, count, seq, plain_rows, max_waves, st);
+    }
+  }
+
+  // Lane groups per wavefront for dimension d (to size the launch and the hot-row rule).
+  static int groups_per_wave(int32_t d) {
+    const int d4 = d / 4;
+    int lpg = 1;
+    while (lpg < d4 && lpg < 64) lpg *= 2;
+    return 64 / lpg;
+  }
+};
+
+}  // namespace gosh

@@ -1,6 +1,7 @@
 // Host-side pieces of libgosh that need no device code: error state, schedule helpers.
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 
 #include "gosh_common.h"
 
@@ -45,6 +46,60 @@ int check_csr(const gosh_csr *g) {
 int check_launch(const char *kernel) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(GOSH_EHIP, "%s: %s", kernel, hipGetErrorString(e));
+  return GOSH_OK;
+}
+
+static long env_long(const char *name, long fallback) {
+  const char *e = getenv(name);
+  return e ? atol(e) : fallback;
+}
+
+const Tuning &tuning() {
+  static const Tuning t{static_cast<int>(env_long("GOSH_ROW_POLICY", 1)),
+                        env_long("GOSH_MAX_WAVES", 1L << 22), env_long("GOSH_HOT_INV_EPS", 64),
+                        env_long("GOSH_HOT_ALL_INV_EPS", 4)};
+  return t;
+}
+
+int resident_waves() {
+  static const int value = [] {
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      int v = 0;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        cus = v;
+    }
+    return cus * 32;
+  }();
+  return value;
+}
+
+namespace {
+struct HotScratch {
+  void *ptr = nullptr;
+  size_t bytes = 0;
+};
+constexpr int kMaxDevices = 64;
+HotScratch g_hot_scratch[kMaxDevices];
+}  // namespace
+
+int hot_scratch(size_t bytes, void **out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(GOSH_EHIP, "cannot identify the current device");
+  HotScratch &h = g_hot_scratch[dev];
+  if (h.bytes < bytes) {
+    if (h.ptr) (void)hipFree(h.ptr);
+    h.ptr = nullptr;
+    h.bytes = 0;
+    const size_t want = bytes + bytes / 4 + 4096;
+    if (hipMalloc(&h.ptr, want) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(GOSH_ENOMEM, "cannot allocate %zu bytes for the hot-row bitmap", want);
+    }
+    h.bytes = want;
+  }
+  *out = h.ptr;
   return GOSH_OK;
 }
 

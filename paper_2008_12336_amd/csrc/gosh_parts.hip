@@ -1,0 +1,590 @@
+// Training of a graph whose embedding matrix does not fit a device budget
+// ("LargeGraphGPU", Alg. 5 and Sec. 3.3 of the paper): the matrix stays on the host,
+// split into K parts of consecutive vertices; pairs of parts are brought into a few
+// device slots, trained against each other by the pair kernel, and written back.
+//
+// Roles (the paper runs them as three host threads; here the device-side ordering is
+// carried by HIP streams and events, and one extra host thread draws the positives):
+//   * sampler thread: fills pools of positive samples on the host, a bounded number of
+//     pairs ahead (an OpenMP team fills one pool);
+//   * copy stream: part write-back / part upload / pool upload, overlapped with
+//   * compute stream: one pair kernel per visited pair, in the fixed inside-out order.
+#include <hip/hip_runtime.h>
+#include <omp.h>
+
+#include <algorithm>
+#include <chrono>
+#include <condition_variable>
+#include <mutex>
+#include <thread>
+#include <vector>
+
+#include "gosh_common.h"
+#include "gosh_device.h"
+
+namespace {
+
+using gosh::philox_draw;
+using gosh::scale_draw;
+
+// Fourth counter word of the parts mode: level in the low 8 bits, visited-pair index + 1
+// above it, so no draw of this mode coincides with one of the epoch kernel.
+__host__ __device__ inline uint32_t level_word(uint32_t level, uint32_t pair_index) {
+  return (level & 0xFFu) | ((pair_index + 1u) << 8);
+}
+
+// Work description of one visit of a pair of parts (a, b).  Sources are the vertices of
+// part a (side 0) followed, unless a == b, by those of part b (side 1).  A source runs B
+// rounds of 1 + k_neg samples: the positive of round r comes from its pool entry, the
+// negatives are uniform over the partner part.
+struct PairWork {
+  int32_t a_lo, a_n, b_lo, b_n;  // vertex id ranges of the two parts
+  float *a_rows, *b_rows;        // device slots holding their rows
+  const int32_t *pool_a;         // a_n * B positives for the sources of a
+  const int32_t *pool_b;         // b_n * B positives for the sources of b (unused if a == b)
+  int32_t B, per_round, d, diagonal;
+  uint32_t key0, key1, rotation, word3;
+
+  __host__ __device__ __forceinline__ int64_t count() const {
+    return diagonal ? a_n : static_cast<int64_t>(a_n) + b_n;
+  }
+  __device__ __forceinline__ int32_t source_id(int64_t i) const {
+    return i < a_n ? a_lo + static_cast<int32_t>(i) : b_lo + static_cast<int32_t>(i - a_n);
+  }
+  __device__ __forceinline__ float *source_row(int64_t i) const {
+    return i < a_n ? a_rows + i * d : b_rows + (i - a_n) * d;
+  }
+  __device__ __forceinline__ int32_t sample(int64_t i, int32_t src, int32_t t) const {
+    const int side = i >= a_n;
+    const int32_t round = t / per_round, j = t % per_round;
+    if (j == 0) {
+      const int64_t local = side ? i - a_n : i;
+      return (side ? pool_b : pool_a)[local * B + round];
+    }
+    const int32_t other_lo = side ? a_lo : b_lo, other_n = side ? a_n : b_n;
+    const uint64_t r = philox_draw(static_cast<uint32_t>(src),
+                                   static_cast<uint32_t>(side * B * per_round + t), rotation, word3,
+                                   key0, key1);
+    return other_lo + static_cast<int32_t>(scale_draw(r, static_cast<uint32_t>(other_n)));
+  }
+  __device__ __forceinline__ float *sample_row(int64_t i, int32_t v) const {
+    return i >= a_n ? a_rows + static_cast<int64_t>(v - a_lo) * d
+                    : b_rows + static_cast<int64_t>(v - b_lo) * d;
+  }
+};
+
+// Debug: the ids the pair kernel would use, source by source, sample by sample.
+__global__ __launch_bounds__(256) void pair_stream_kernel(PairWork w, int32_t samples,
+                                                          int32_t *__restrict__ out) {
+  const int64_t total = w.count() * samples;
+  for (int64_t x = blockIdx.x * 256LL + threadIdx.x; x < total; x += gridDim.x * 256LL) {
+    const int64_t i = x / samples;
+    out[x] = w.sample(i, w.source_id(i), static_cast<int32_t>(x % samples));
+  }
+}
+
+struct HostCsr {
+  const gosh_csr *g;
+  int64_t begin(int64_t v) const {
+    return g->xadj_is64 ? static_cast<const int64_t *>(g->xadj)[v] : static_cast<const int32_t *>(g->xadj)[v];
+  }
+};
+
+// Positives of the sources of part [lo, lo+cnt) against the partner range [olo, ohi): for
+// round r a uniform member of the source's neighbours inside the partner range, -1 if it
+// has none there (Sec. 3.3).  Neighbour lists are ascending, so the candidates are one
+// contiguous run found by two binary searches.
+void fill_pool(const HostCsr &csr, int32_t lo, int32_t cnt, int32_t olo, int32_t ohi, int side,
+               int32_t B, int32_t per_round, uint32_t key0, uint32_t key1, uint32_t rotation,
+               uint32_t word3, int threads, int32_t *pool) {
+  const int32_t *adj = csr.g->adj;
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1024)
+  for (int32_t local = 0; local < cnt; ++local) {
+    const int64_t src = static_cast<int64_t>(lo) + local;
+    const int32_t *row_begin = adj + csr.begin(src), *row_end = adj + csr.begin(src + 1);
+    const int32_t *first = std::lower_bound(row_begin, row_end, olo);
+    const int32_t *last = std::lower_bound(first, row_end, ohi);
+    const uint32_t candidates = static_cast<uint32_t>(last - first);
+    for (int32_t r = 0; r < B; ++r) {
+      int32_t pick = -1;
+      if (candidates > 0) {
+        const uint64_t draw = philox_draw(static_cast<uint32_t>(src),
+                                          static_cast<uint32_t>(side * B * per_round + r * per_round),
+                                          rotation, word3, key0, key1);
+        pick = first[scale_draw(draw, candidates)];
+      }
+      pool[static_cast<int64_t>(local) * B + r] = pick;
+    }
+  }
+}
+
+struct Layout {
+  int64_t n;
+  int32_t K;
+  int64_t part_rows;  // ceil(n / K)
+  int32_t lo(int32_t p) const { return static_cast<int32_t>(std::min<int64_t>(n, p * part_rows)); }
+  int32_t size(int32_t p) const { return static_cast<int32_t>(std::min<int64_t>(n, (p + 1) * part_rows) - lo(p)); }
+};
+
+// The order in which part pairs are visited in one rotation (Sec. 3.3.1, "inside-out"):
+// (0,0), (1,0), (1,1), (2,0), ...
+void pair_order(int32_t K, std::vector<int32_t> &a, std::vector<int32_t> &b) {
+  a.clear();
+  b.clear();
+  for (int32_t m = 0; m < K; ++m)
+    for (int32_t s = 0; s <= m; ++s) {
+      a.push_back(m);
+      b.push_back(s);
+    }
+}
+
+#define PARTS_HIP(call, what)                                                          \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      rc = gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_));               \
+      goto done;                                                                       \
+    }                                                                                  \
+  } while (0)
+
+uint64_t device_bytes_for(int64_t n, int32_t K, int32_t d, int32_t P, int32_t S, int32_t B) {
+  const int64_t ps = (n + K - 1) / K;
+  return static_cast<uint64_t>(P) * ps * d * 4 + static_cast<uint64_t>(S) * 2 * ps * B * 4 +
+         static_cast<uint64_t>((n + 63) / 64) * 8;
+}
+
+int check_parts_args(const gosh_csr *g, const float *M, int32_t d, int32_t k_neg, int32_t P,
+                     int32_t S, int32_t B, uint32_t flags) {
+  if (int rc = gosh::check_csr(g)) return rc;
+  if (int rc = gosh::check_matrix(M, d, "M")) return rc;
+  if (k_neg < 0 || k_neg > GOSH_MAX_NEG)
+    return gosh::fail(GOSH_EINVAL, "k_neg = %d: must be in [0, %d]", k_neg, GOSH_MAX_NEG);
+  if (P < 2 || P > 64) return gosh::fail(GOSH_EINVAL, "P_gpu = %d: must be in [2, 64]", P);
+  if (S < 1 || S > 64) return gosh::fail(GOSH_EINVAL, "S_gpu = %d: must be in [1, 64]", S);
+  if (B < 1 || B > 64) return gosh::fail(GOSH_EINVAL, "B = %d: must be in [1, 64]", B);
+  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS))
+    return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
+  if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
+    return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
+  return GOSH_OK;
+}
+
+constexpr int32_t kMaxParts = 4096;
+
+}  // namespace
+
+extern "C" {
+
+int gosh_pair_order(int32_t K, int32_t *a, int32_t *b) {
+  if (K < 1 || K > kMaxParts) return gosh::fail(GOSH_EINVAL, "K = %d: must be in [1, %d]", K, kMaxParts);
+  if (a == nullptr || b == nullptr) return gosh::fail(GOSH_EINVAL, "output array is null");
+  std::vector<int32_t> va, vb;
+  pair_order(K, va, vb);
+  std::copy(va.begin(), va.end(), a);
+  std::copy(vb.begin(), vb.end(), b);
+  return GOSH_OK;
+}
+
+int gosh_parts_plan(int64_t n, int32_t d, int64_t epochs, uint64_t device_budget_bytes, int32_t P_gpu,
+                    int32_t S_gpu, int32_t B, int32_t *K_out, int64_t *rotations_out,
+                    uint64_t *device_bytes_out) {
+  if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
+  if (int rc = gosh::check_dim(d)) return rc;
+  if (P_gpu < 2 || S_gpu < 1 || B < 1 || epochs < 1)
+    return gosh::fail(GOSH_EINVAL, "need P_gpu >= 2, S_gpu >= 1, B >= 1, epochs >= 1");
+  int32_t K = 1;
+  const int32_t K_max = static_cast<int32_t>(std::min<int64_t>(n, kMaxParts));
+  // With K parts only min(P_gpu, K) slots are needed.
+  while (K <= K_max &&
+         device_bytes_for(n, K, d, std::min(P_gpu, K), S_gpu, B) > device_budget_bytes)
+    ++K;
+  if (K > K_max)
+    return gosh::fail(GOSH_EBUDGET, "a budget of %llu bytes cannot hold %d parts of a %d-part split",
+                      (unsigned long long)device_budget_bytes, P_gpu, K_max);
+  if (K_out) *K_out = K;
+  if (rotations_out) {
+    const int64_t per = static_cast<int64_t>(B) * K;
+    *rotations_out = std::max<int64_t>(1, (epochs + per - 1) / per);
+  }
+  if (device_bytes_out) *device_bytes_out = device_bytes_for(n, K, d, std::min(P_gpu, K), S_gpu, B);
+  return GOSH_OK;
+}
+
+int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_t pb, int32_t B,
+                           int32_t k_neg, uint64_t seed, uint32_t rotation, uint32_t level,
+                           uint32_t pair_index, int32_t *out_host) {
+  if (int rc = gosh::check_csr(g_host)) return rc;
+  if (K < 1 || K > kMaxParts || pa < 0 || pb < 0 || pa >= K || pb >= K || pb > pa)
+    return gosh::fail(GOSH_EINVAL, "need 0 <= pb <= pa < K <= %d", kMaxParts);
+  if (B < 1 || B > 64 || k_neg < 0 || k_neg > GOSH_MAX_NEG || out_host == nullptr)
+    return gosh::fail(GOSH_EINVAL, "bad B, k_neg or output pointer");
+  const Layout L{g_host->n, K, (g_host->n + K - 1) / K};
+  const HostCsr csr{g_host};
+  const int32_t per_round = k_neg + 1, samples = B * per_round;
+  PairWork w{};
+  w.a_lo = L.lo(pa); w.a_n = L.size(pa); w.b_lo = L.lo(pb); w.b_n = L.size(pb);
+  w.B = B; w.per_round = per_round; w.d = 4; w.diagonal = pa == pb;
+  w.key0 = static_cast<uint32_t>(seed); w.key1 = static_cast<uint32_t>(seed >> 32);
+  w.rotation = rotation; w.word3 = level_word(level, pair_index);
+  std::vector<int32_t> pool_a(static_cast<size_t>(w.a_n) * B + 1), pool_b(static_cast<size_t>(w.b_n) * B + 1);
+  const int threads = omp_get_max_threads();
+  fill_pool(csr, w.a_lo, w.a_n, w.b_lo, w.b_lo + w.b_n, 0, B, per_round, w.key0, w.key1, rotation,
+            w.word3, threads, pool_a.data());
+  if (!w.diagonal)
+    fill_pool(csr, w.b_lo, w.b_n, w.a_lo, w.a_lo + w.a_n, 1, B, per_round, w.key0, w.key1, rotation,
+              w.word3, threads, pool_b.data());
+  const int64_t total = w.count() * samples;
+  int rc = GOSH_OK;
+  int32_t *d_pa = nullptr, *d_pb = nullptr, *d_out = nullptr;
+  PARTS_HIP(hipMalloc(&d_pa, pool_a.size() * 4), "hipMalloc");
+  PARTS_HIP(hipMalloc(&d_pb, pool_b.size() * 4), "hipMalloc");
+  PARTS_HIP(hipMalloc(&d_out, static_cast<size_t>(std::max<int64_t>(total, 1)) * 4), "hipMalloc");
+  PARTS_HIP(hipMemcpy(d_pa, pool_a.data(), pool_a.size() * 4, hipMemcpyHostToDevice), "copy pool");
+  PARTS_HIP(hipMemcpy(d_pb, pool_b.data(), pool_b.size() * 4, hipMemcpyHostToDevice), "copy pool");
+  w.pool_a = d_pa;
+  w.pool_b = d_pb;
+  if (total > 0) {
+    const int blocks = static_cast<int>(std::min<int64_t>((total + 255) / 256, 1 << 16));
+    hipLaunchKernelGGL(pair_stream_kernel, dim3(blocks), dim3(256), 0, nullptr, w, samples, d_out);
+    if ((rc = gosh::check_launch("pair_stream_kernel"))) goto done;
+    PARTS_HIP(hipMemcpy(out_host, d_out, static_cast<size_t>(total) * 4, hipMemcpyDeviceToHost), "copy stream");
+  }
+done:
+  if (d_pa) (void)hipFree(d_pa);
+  if (d_pb) (void)hipFree(d_pb);
+  if (d_out) (void)hipFree(d_out);
+  return rc;
+}
+
+int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k_neg, int64_t epochs,
+                     float lr0, uint64_t seed, uint32_t level, uint64_t device_budget_bytes,
+                     int32_t P_gpu, int32_t S_gpu, int32_t B, int32_t force_K, uint32_t flags,
+                     gosh_parts_stats *stats_out) {
+  if (int rc0 = check_parts_args(g_host, M_host, d, k_neg, P_gpu, S_gpu, B, flags)) return rc0;
+  if (epochs < 1) return gosh::fail(GOSH_EINVAL, "epochs = %lld: must be >= 1", (long long)epochs);
+  const int64_t n = g_host->n;
+  int32_t K = 0;
+  int64_t rotations = 0;
+  uint64_t planned_bytes = 0;
+  if (force_K > 0) {
+    if (force_K > kMaxParts || force_K > n) return gosh::fail(GOSH_EINVAL, "force_K = %d too large", force_K);
+    K = force_K;
+    rotations = std::max<int64_t>(1, (epochs + static_cast<int64_t>(B) * K - 1) / (static_cast<int64_t>(B) * K));
+    planned_bytes = device_bytes_for(n, K, d, std::min(P_gpu, K), S_gpu, B);
+    if (device_budget_bytes != 0 && planned_bytes > device_budget_bytes)
+      return gosh::fail(GOSH_EBUDGET, "K = %d needs %llu device bytes, budget is %llu", K,
+                        (unsigned long long)planned_bytes, (unsigned long long)device_budget_bytes);
+  } else if (int rc0 = gosh_parts_plan(n, d, epochs, device_budget_bytes, P_gpu, S_gpu, B, &K,
+                                       &rotations, &planned_bytes)) {
+    return rc0;
+  }
+  const Layout L{n, K, (n + K - 1) / K};
+  const int32_t P = std::min(P_gpu, K), S = S_gpu;
+  const int32_t per_round = k_neg + 1, samples = B * per_round;
+  const bool seq = (flags & GOSH_FLAG_SEQUENTIAL) != 0;
+  const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
+  std::vector<int32_t> pa, pb;
+  pair_order(K, pa, pb);
+  const int64_t npairs = static_cast<int64_t>(pa.size());
+  const int64_t visits = rotations * npairs;
+  const HostCsr csr{g_host};
+  const int host_threads = std::max(1, omp_get_max_threads());
+  const size_t pool_ints = static_cast<size_t>(2) * L.part_rows * B;  // side 0 then side 1
+
+  int rc = GOSH_OK;
+  auto wall0 = std::chrono::steady_clock::now();
+  gosh_parts_stats st{};
+  st.K = K;
+  st.rotations = rotations;
+  st.pair_visits = visits;
+  st.device_bytes = planned_bytes;
+
+  // ---- device and pinned-host resources ------------------------------------------------
+  std::vector<float *> slot(P, nullptr);
+  std::vector<int32_t *> dpool(S, nullptr);
+  const int NS = S + 1;  // host staging buffers for pools
+  std::vector<int32_t *> staging(NS, nullptr);
+  uint32_t *hot_bits_dev = nullptr;
+  hipStream_t compute = nullptr, copy = nullptr;
+  std::vector<hipEvent_t> slot_ready(P, nullptr), slot_used(P, nullptr), pool_ready(S, nullptr),
+      pool_used(S, nullptr), staging_done(NS, nullptr);
+  std::vector<hipEvent_t> k_begin, k_end;
+  std::vector<int32_t> slot_part(P, -1);
+
+  // ---- sampler thread state -------------------------------------------------------------
+  std::mutex mu;
+  std::condition_variable cv;
+  int64_t filled = 0;    // pools produced so far (visit indices [0, filled))
+  int64_t released = 0;  // staging buffers given back (visit indices [0, released))
+  bool stop = false;
+  std::thread sampler;
+
+  auto visit_pair = [&](int64_t vi, int32_t &a, int32_t &b, uint32_t &rot, uint32_t &q) {
+    rot = static_cast<uint32_t>(vi / npairs);
+    q = static_cast<uint32_t>(vi % npairs);
+    a = pa[q];
+    b = pb[q];
+  };
+
+  gosh::HotSet hot{nullptr, gosh::kHotNone};
+
+  PARTS_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
+  PARTS_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
+  for (int s = 0; s < P; ++s) {
+    PARTS_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * d * 4), "hipMalloc part slot");
+    PARTS_HIP(hipEventCreateWithFlags(&slot_ready[s], hipEventDisableTiming), "hipEventCreate");
+    PARTS_HIP(hipEventCreateWithFlags(&slot_used[s], hipEventDisableTiming), "hipEventCreate");
+  }
+  for (int s = 0; s < S; ++s) {
+    PARTS_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
+    PARTS_HIP(hipEventCreateWithFlags(&pool_ready[s], hipEventDisableTiming), "hipEventCreate");
+    PARTS_HIP(hipEventCreateWithFlags(&pool_used[s], hipEventDisableTiming), "hipEventCreate");
+  }
+  for (int s = 0; s < NS; ++s) {
+    PARTS_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
+              "hipHostMalloc staging");
+    PARTS_HIP(hipEventCreateWithFlags(&staging_done[s], hipEventDisableTiming), "hipEventCreate");
+  }
+  k_begin.assign(static_cast<size_t>(visits), nullptr);
+  k_end.assign(static_cast<size_t>(visits), nullptr);
+
+  // ---- hot rows: degree rule evaluated on the host, bitmap uploaded once -----------------
+  if (!seq) {
+    const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(d);
+    const int64_t pair_sources = 2 * L.part_rows;
+    const int64_t waves = std::min<int64_t>((pair_sources + gpw - 1) / gpw, gosh::tuning().max_waves);
+    const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;
+    // per visit a row takes about B*k_neg uniform hits plus its own turn
+    int mode = ((static_cast<int64_t>(B) * k_neg + 1) * in_flight * gosh::tuning().hot_all_inv_eps > pair_sources)
+                   ? gosh::kHotAll
+                   : gosh::kHotBitmap;
+    if (flags & GOSH_FLAG_PLAIN_STORES) mode = gosh::kHotNone;
+    if (flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
+    if (mode == gosh::kHotBitmap) {
+      const int64_t min_degree = g_host->nnz / (gosh::tuning().hot_inv_eps * in_flight * B) + 1;
+      std::vector<uint64_t> bits(static_cast<size_t>((n + 63) / 64), 0);
+#pragma omp parallel for num_threads(host_threads) schedule(static)
+      for (int64_t w64 = 0; w64 < static_cast<int64_t>(bits.size()); ++w64) {
+        uint64_t word = 0;
+        for (int bit = 0; bit < 64; ++bit) {
+          const int64_t v = w64 * 64 + bit;
+          if (v < n && csr.begin(v + 1) - csr.begin(v) >= min_degree) word |= uint64_t{1} << bit;
+        }
+        bits[static_cast<size_t>(w64)] = word;
+      }
+      PARTS_HIP(hipMalloc(&hot_bits_dev, bits.size() * 8), "hipMalloc hot bitmap");
+      PARTS_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
+      hot.bits = hot_bits_dev;
+    }
+    hot.mode = mode;
+  }
+
+  // ---- sampler thread: pools of positives, at most NS visits ahead of their release ------
+  sampler = std::thread([&] {
+    for (int64_t vi = 0; vi < visits; ++vi) {
+      {
+        std::unique_lock<std::mutex> lock(mu);
+        cv.wait(lock, [&] { return stop || vi - released < NS; });
+        if (stop) return;
+      }
+      int32_t a, b;
+      uint32_t rot, q;
+      visit_pair(vi, a, b, rot, q);
+      int32_t *buf = staging[vi % NS];
+      const uint32_t w3 = level_word(level, q);
+      fill_pool(csr, L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, B, per_round, key0, key1,
+                rot, w3, host_threads, buf);
+      if (a != b)
+        fill_pool(csr, L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, B, per_round, key0, key1,
+                  rot, w3, host_threads, buf + static_cast<size_t>(L.part_rows) * B);
+      {
+        std::lock_guard<std::mutex> lock(mu);
+        filled = vi + 1;
+      }
+      cv.notify_all();
+    }
+  });
+
+  {
+    // next visit (>= from) that uses part p, or a large number
+    auto next_use = [&](int32_t p, int64_t from) {
+      for (int64_t vi = from; vi < std::min(visits, from + 4 * npairs + 4); ++vi) {
+        const int64_t q = vi % npairs;
+        if (pa[q] == p || pb[q] == p) return vi;
+      }
+      return visits + npairs;
+    };
+    auto slot_of = [&](int32_t p) {
+      for (int s = 0; s < P; ++s)
+        if (slot_part[s] == p) return s;
+      return -1;
+    };
+    // Brings part p into a slot whose part is not in `keep` (SwitchSubMatrices): among the
+    // other slots an empty one is taken, else the part whose next use is farthest is
+    // written back and replaced.  Everything is queued on the copy stream behind the last
+    // kernel that used the slot.  Returns the slot, -1 if every slot is kept, -2 on error.
+    auto load_part = [&](int32_t p, const int32_t (&keep)[3], int64_t now) -> int {
+      int victim = -1;
+      int64_t farthest = -1;
+      for (int s = 0; s < P; ++s) {
+        const int32_t sp = slot_part[s];
+        if (sp == -1) { victim = s; break; }
+        if (sp == keep[0] || sp == keep[1] || sp == keep[2]) continue;
+        const int64_t nu = next_use(sp, now);
+        if (nu > farthest) { farthest = nu; victim = s; }
+      }
+      if (victim < 0) return -1;
+      if (hipStreamWaitEvent(copy, slot_used[victim], 0) != hipSuccess) return -2;
+      if (slot_part[victim] >= 0) {
+        const int32_t old = slot_part[victim];
+        const size_t bytes = static_cast<size_t>(L.size(old)) * d * 4;
+        if (hipMemcpyAsync(M_host + static_cast<int64_t>(L.lo(old)) * d, slot[victim], bytes,
+                           hipMemcpyDeviceToHost, copy) != hipSuccess) return -2;
+        st.bytes_d2h += bytes;
+      }
+      const size_t bytes = static_cast<size_t>(L.size(p)) * d * 4;
+      if (hipMemcpyAsync(slot[victim], M_host + static_cast<int64_t>(L.lo(p)) * d, bytes,
+                         hipMemcpyHostToDevice, copy) != hipSuccess) return -2;
+      st.bytes_h2d += bytes;
+      if (hipEventRecord(slot_ready[victim], copy) != hipSuccess) return -2;
+      slot_part[victim] = p;
+      return victim;
+    };
+    // Makes the parts of visit vi resident as far as slots allow, never evicting the
+    // parts of the visit whose kernel may still be running (run_a, run_b; -1 = none).
+    auto ensure_parts = [&](int64_t vi, int32_t run_a, int32_t run_b) -> int {
+      if (vi >= visits) return 0;
+      const int64_t q = vi % npairs;
+      const int32_t need[2] = {pa[q], pb[q]};
+      for (int t = 0; t < 2; ++t) {
+        if (t == 1 && need[1] == need[0]) break;
+        if (slot_of(need[t]) >= 0) continue;
+        // keep the running pair; keep the partner too unless it IS part of the running
+        // pair (already covered) -- with three slots at most two distinct parts are kept
+        // whenever a load is possible at all
+        const int32_t keep[3] = {run_a, run_b, need[1 - t]};
+        if (load_part(need[t], keep, vi) == -2) return -2;
+      }
+      return 0;
+    };
+
+    for (int64_t vi = 0; vi < visits && rc == GOSH_OK; ++vi) {
+      int32_t a, b;
+      uint32_t rot, q;
+      visit_pair(vi, a, b, rot, q);
+      // 1. the two parts of this visit (nothing is running that they could disturb: the
+      //    copy stream waits for the last kernel of any slot it overwrites)
+      if (ensure_parts(vi, -1, -1) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
+      const int sa = slot_of(a), sb = slot_of(b);
+      if (sa < 0 || sb < 0) { rc = gosh::fail(GOSH_EHIP, "internal: part not resident"); break; }
+      // 2. the pool of this visit: wait for the sampler, upload on the copy stream
+      {
+        std::unique_lock<std::mutex> lock(mu);
+        cv.wait(lock, [&] { return filled > vi; });
+      }
+      const int ps = static_cast<int>(vi % S), hs = static_cast<int>(vi % NS);
+      PARTS_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
+      {
+        const size_t side0 = static_cast<size_t>(L.size(a)) * B * 4;
+        PARTS_HIP(hipMemcpyAsync(dpool[ps], staging[hs], side0, hipMemcpyHostToDevice, copy), "pool upload");
+        st.bytes_h2d += side0;
+        if (a != b) {
+          const size_t side1 = static_cast<size_t>(L.size(b)) * B * 4;
+          PARTS_HIP(hipMemcpyAsync(dpool[ps] + static_cast<size_t>(L.part_rows) * B,
+                                   staging[hs] + static_cast<size_t>(L.part_rows) * B, side1,
+                                   hipMemcpyHostToDevice, copy), "pool upload");
+          st.bytes_h2d += side1;
+        }
+      }
+      PARTS_HIP(hipEventRecord(pool_ready[ps], copy), "hipEventRecord");
+      PARTS_HIP(hipEventRecord(staging_done[hs], copy), "hipEventRecord");
+      // 3. the pair kernel
+      PARTS_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
+      PARTS_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
+      PARTS_HIP(hipStreamWaitEvent(compute, pool_ready[ps], 0), "hipStreamWaitEvent");
+      {
+        PairWork w{};
+        w.a_lo = L.lo(a); w.a_n = L.size(a); w.b_lo = L.lo(b); w.b_n = L.size(b);
+        w.a_rows = slot[sa]; w.b_rows = slot[sb];
+        w.pool_a = dpool[ps];
+        w.pool_b = dpool[ps] + static_cast<size_t>(L.part_rows) * B;
+        w.B = B; w.per_round = per_round; w.d = d; w.diagonal = a == b;
+        w.key0 = key0; w.key1 = key1; w.rotation = rot; w.word3 = level_word(level, q);
+        gosh::SgdArgs args{};
+        args.hot = hot;
+        args.d = d;
+        args.k_neg = k_neg;
+        args.samples = samples;
+        args.lr = gosh_lr(lr0, rot, rotations);
+        PARTS_HIP(hipEventCreate(&k_begin[vi]), "hipEventCreate");
+        PARTS_HIP(hipEventCreate(&k_end[vi]), "hipEventCreate");
+        PARTS_HIP(hipEventRecord(k_begin[vi], compute), "hipEventRecord");
+        gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, gosh::tuning().row_policy == 0,
+                                            gosh::tuning().max_waves, compute);
+        if ((rc = gosh::check_launch("sgd_kernel (pair)"))) break;
+        PARTS_HIP(hipEventRecord(k_end[vi], compute), "hipEventRecord");
+        st.updates += w.count() * samples;
+      }
+      PARTS_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
+      PARTS_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
+      PARTS_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
+      // 4. while that kernel runs: bring in what the next visit needs, if a slot is spare
+      if (ensure_parts(vi + 1, a, b) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
+      // 5. hand the staging buffer back to the sampler once its upload is done
+      PARTS_HIP(hipEventSynchronize(staging_done[hs]), "hipEventSynchronize");
+      {
+        std::lock_guard<std::mutex> lock(mu);
+        released = vi + 1;
+      }
+      cv.notify_all();
+    }
+    if (rc == GOSH_OK) {
+      // write every resident part back
+      for (int s = 0; s < P; ++s) {
+        if (slot_part[s] < 0) continue;
+        const int32_t old = slot_part[s];
+        const size_t bytes = static_cast<size_t>(L.size(old)) * d * 4;
+        PARTS_HIP(hipStreamWaitEvent(copy, slot_used[s], 0), "hipStreamWaitEvent");
+        PARTS_HIP(hipMemcpyAsync(M_host + static_cast<int64_t>(L.lo(old)) * d, slot[s], bytes,
+                                 hipMemcpyDeviceToHost, copy), "part write-back");
+        st.bytes_d2h += bytes;
+      }
+      PARTS_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
+      PARTS_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
+      for (int64_t vi = 0; vi < visits; ++vi) {
+        float ms = 0.f;
+        if (k_begin[vi] && k_end[vi] && hipEventElapsedTime(&ms, k_begin[vi], k_end[vi]) == hipSuccess)
+          st.kernel_ms += ms;
+      }
+    }
+  }
+
+done:
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    stop = true;
+    released = visits + NS;  // unblock the sampler
+  }
+  cv.notify_all();
+  if (sampler.joinable()) sampler.join();
+  if (compute) (void)hipStreamSynchronize(compute);
+  if (copy) (void)hipStreamSynchronize(copy);
+  for (auto e : k_begin) if (e) (void)hipEventDestroy(e);
+  for (auto e : k_end) if (e) (void)hipEventDestroy(e);
+  for (auto e : slot_ready) if (e) (void)hipEventDestroy(e);
+  for (auto e : slot_used) if (e) (void)hipEventDestroy(e);
+  for (auto e : pool_ready) if (e) (void)hipEventDestroy(e);
+  for (auto e : pool_used) if (e) (void)hipEventDestroy(e);
+  for (auto e : staging_done) if (e) (void)hipEventDestroy(e);
+  for (auto p : slot) if (p) (void)hipFree(p);
+  for (auto p : dpool) if (p) (void)hipFree(p);
+  for (auto p : staging) if (p) (void)hipHostFree(p);
+  if (hot_bits_dev) (void)hipFree(hot_bits_dev);
+  if (compute) (void)hipStreamDestroy(compute);
+  if (copy) (void)hipStreamDestroy(copy);
+  st.wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
+  if (stats_out) *stats_out = st;
+  return rc;
+}
+
+}  // extern "C"
