@@ -156,7 +156,8 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
 /* "ExpandEmbedding" (Alg. 2; Sec. 3: the row of a vertex of G_{i-1} is the row of its
  * super vertex in G_i): M_fine[v,:] = M_coarse[map[v],:] for v < n_fine.  All pointers
  * are device memory; map holds n_fine ids in [0, n_coarse) (trusted).  M_fine and
- * M_coarse must not overlap. */
+ * M_coarse must not overlap.  A slice of the fine level can be projected by passing the
+ * matching slice of map and of M_fine. */
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev,
                  int64_t n_fine, int32_t d, float *M_fine_dev, void *hip_stream);
 
@@ -169,6 +170,8 @@ typedef struct {
   double upload_ms;  /* host -> device copy of G_i (wall clock) */
   double train_ms;   /* the e_i epoch launches (HIP events on the stream) */
   double project_ms; /* map upload + projection to level i-1 (wall clock; 0 at level 0) */
+  int32_t parts_K;   /* 0: trained with the epoch kernel; K > 0: trained with the part-pair
+                        rotation on K parts (train_ms is then the wall time of that call) */
 } gosh_level_stats;
 
 /* Alg. 2 ("GOSH") for levels that fit the device: with D = levels of h and
@@ -178,14 +181,27 @@ typedef struct {
  * counter, then (i > 0) project to level i-1 with map_{i-1}.  The paper prints the loop
  * as "D-1 to 1"; the text trains until M_0 is obtained, which is what is done here.
  * h: hierarchy (host).  M0_dev: device matrix n_0 x d, receives the embedding of G_0.
- * flags: as for gosh_train_epoch.  device_budget_bytes: if non-zero, a level whose
- * graph plus matrix exceed it is refused with GOSH_EBUDGET (use gosh_train_parts for
- * such a level).  stats: NULL or host array of D entries, filled per level.
+ * flags: as for gosh_train_epoch.  device_budget_bytes: if non-zero and the graph plus
+ * matrix of level 0 exceed it, the call is refused with GOSH_EBUDGET (use gosh_embed_host,
+ * which keeps such levels on the host).  stats: NULL or host array of D entries, filled per level.
  * Blocking: returns after the last level finished; intermediate device buffers are
  * allocated and freed inside the call. */
 int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p,
                float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
                float *M0_dev, gosh_level_stats *stats, void *hip_stream);
+
+/* Alg. 2 including its "fits into GPU" branch, with the result on the host.  Levels whose
+ * graph and matrix fit device_budget_bytes (0 = everything fits) are trained as in
+ * gosh_embed; the others are trained with gosh_train_parts(level i, e_i epochs, the same
+ * budget, P_gpu, S_gpu, B) on a host-resident matrix.  Projection runs on the device
+ * (slice by slice when the finer level lives on the host); only when both levels live
+ * on the host are the rows gathered there.  The initial matrix of a coarsest level that
+ * does not fit is produced on the device slice by slice (same values as
+ * gosh_init_embedding).  M0_host: host matrix n_0 x d (pinned memory recommended). */
+int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p,
+                    float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
+                    int32_t P_gpu, int32_t S_gpu, int32_t B, float *M0_host,
+                    gosh_level_stats *stats, void *hip_stream);
 
 /* ---- graphs larger than a device budget (Sec. 3.3, Alg. 5 "LargeGraphGPU") -------------- */
 

@@ -252,6 +252,48 @@ def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, 
     return M, graphs, maps, e_i
 
 
+def parts_split(n, d, budget, P_gpu, S_gpu, B):
+    """READING (number of parts; the paper leaves GetEmbeddingPartInfo open): the smallest
+    K for which min(P_gpu, K) part slots of ceil(n/K) rows, S_gpu pools of 2*ceil(n/K)*B
+    ids and one bit per vertex fit the budget."""
+    K = 1
+    while True:
+        ps = -(-n // K)
+        need = min(P_gpu, K) * ps * d * 4 + S_gpu * 2 * ps * B * 4 + ((n + 63) // 64) * 8
+        if need <= budget:
+            return K
+        K += 1
+        if K > n:
+            raise ValueError("budget too small")
+
+
+def embed_budget(xadj, adj, d, k, epochs, p, lr0, seed, budget, P_gpu=3, S_gpu=4, B=5,
+                 threshold=100, min_shrink=1.0, offsets64=False):
+    """Alg. 2 with its "fits into GPU" test: a level whose graph (offsets + adj) and matrix
+    exceed `budget` bytes is trained with the rotation of Alg. 5, the others with Alg. 3.
+    Coarse levels have 64-bit offsets; level 0 as given.  Returns (M_0, modes) where
+    modes[i] is 0 or the K used."""
+    graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink)
+    D = len(graphs)
+    e_i = epoch_split(epochs, p, D)
+    M = init_embedding(graphs[-1][0].size - 1, d, seed, D - 1)
+    modes = [0] * D
+    for i in range(D - 1, -1, -1):
+        x, a = graphs[i]
+        n = x.size - 1
+        off = 8 if (i > 0 or offsets64) else 4
+        size = (n + 1) * off + a.size * 4 + n * d * 4
+        if size <= budget:
+            train_level(x, a, M, k, lr0, int(e_i[i]), seed, i)
+        else:
+            K = parts_split(n, d, budget, P_gpu, S_gpu, B)
+            modes[i] = K
+            train_parts(x, a, M, k, int(e_i[i]), lr0, seed, i, K, B)
+        if i > 0:
+            M = project(M, maps[i - 1])
+    return M, modes
+
+
 def pair_order(K):
     npairs = K * (K + 1) // 2
     a = np.zeros(npairs, dtype=np.int32)

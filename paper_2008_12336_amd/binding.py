@@ -34,7 +34,8 @@ class gosh_csr(C.Structure):
 
 class gosh_level_stats(C.Structure):
     _fields_ = [("level", C.c_int32), ("n", C.c_int64), ("nnz", C.c_int64), ("epochs", C.c_int64),
-                ("upload_ms", C.c_double), ("train_ms", C.c_double), ("project_ms", C.c_double)]
+                ("upload_ms", C.c_double), ("train_ms", C.c_double), ("project_ms", C.c_double),
+                ("parts_K", C.c_int32)]
 
 
 class gosh_parts_stats(C.Structure):
@@ -78,6 +79,9 @@ EXPORTS = {
                                    C.c_float, C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_uint32,
                                    C.POINTER(gosh_parts_stats)]),
+    "gosh_embed_host": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_float,
+                                  C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_void_p, C.POINTER(gosh_level_stats), C.c_void_p]),
     "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                C.c_void_p, C.c_void_p]),
 }
@@ -282,8 +286,29 @@ def gosh_embed(h: Hierarchy, M0: torch.Tensor, k_neg: int, epochs: int, p: float
     stats = (gosh_level_stats * D)()
     _check(lib().gosh_embed(h.handle, d, k_neg, epochs, p, lr0, seed, flags, device_budget_bytes,
                             ptr, stats, _stream(stream)))
+    return _level_stats(stats)
+
+
+def _level_stats(stats):
     return [dict(level=s.level, n=s.n, nnz=s.nnz, epochs=s.epochs, upload_ms=s.upload_ms,
-                 train_ms=s.train_ms, project_ms=s.project_ms) for s in stats]
+                 train_ms=s.train_ms, project_ms=s.project_ms, parts_K=s.parts_K) for s in stats]
+
+
+def gosh_embed_host(h: Hierarchy, M0_host: torch.Tensor, k_neg: int, epochs: int, p: float,
+                    lr0: float, seed: int, flags: int = 0, device_budget_bytes: int = 0,
+                    P_gpu: int = 3, S_gpu: int = 4, B: int = 5, stream=None):
+    """Multilevel training into the HOST matrix M0_host; levels above the budget use the
+    part-pair rotation.  Returns per-level stats."""
+    if M0_host.is_cuda:
+        raise TypeError("M0_host must be a host tensor")
+    ptr, n0, d = _matrix(M0_host, "M0_host")
+    if n0 != h.graph_view(0).n:
+        raise ValueError("M0_host must have one row per vertex of G_0")
+    D = h.levels
+    stats = (gosh_level_stats * D)()
+    _check(lib().gosh_embed_host(h.handle, d, k_neg, epochs, p, lr0, seed, flags,
+                                 device_budget_bytes, P_gpu, S_gpu, B, ptr, stats, _stream(stream)))
+    return _level_stats(stats)
 
 
 def gosh_pair_order(K: int):

@@ -41,6 +41,11 @@ const Tuning &tuning();
 // Wavefronts the device keeps resident (8 on each of the 4 SIMDs of every CU).
 int resident_waves();
 
+// Rows first_row .. first_row+count-1 of the initial matrix of a level, written to
+// rows_dev (count x d): the arithmetic of gosh_init_embedding for a slice.
+int init_rows(float *rows_dev, int64_t first_row, int64_t count, int32_t d, uint64_t seed,
+              uint32_t level, hipStream_t st);
+
 // Per-device scratch for the hot-row bitmap (one bit per vertex), grown on demand and
 // kept until the process ends.  Calls on one device must not overlap on different
 // streams.

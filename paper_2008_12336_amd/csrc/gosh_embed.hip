@@ -1,9 +1,16 @@
 // Multilevel driver (Alg. 2 of the paper): train the coarsest graph, project the
 // embedding to the next finer graph, train that, ... until the embedding of G_0 exists.
-// Host orchestration only: every numerical step is one of the library's kernels.
+// A level whose graph and matrix fit the device budget is trained with the epoch kernel
+// (CopyToDevice + TrainInGPU); a level that does not is trained with the part-pair
+// rotation on a host-resident matrix (LargeGraphGPU).  Host orchestration only: every
+// numerical step is one of the library's kernels, except the row gather between two
+// levels that both live on the host.
 #include <hip/hip_runtime.h>
+#include <omp.h>
 
+#include <algorithm>
 #include <chrono>
+#include <cstring>
 #include <vector>
 
 #include "gosh_common.h"
@@ -12,10 +19,10 @@ namespace {
 
 struct DeviceBuffer {
   void *ptr = nullptr;
-  ~DeviceBuffer() { reset(); }
   DeviceBuffer() = default;
   DeviceBuffer(const DeviceBuffer &) = delete;
   DeviceBuffer &operator=(const DeviceBuffer &) = delete;
+  ~DeviceBuffer() { reset(); }
   int alloc(size_t bytes, const char *what) {
     reset();
     if (bytes == 0) bytes = 16;
@@ -33,6 +40,29 @@ struct DeviceBuffer {
   void swap(DeviceBuffer &o) { std::swap(ptr, o.ptr); }
 };
 
+struct PinnedBuffer {
+  void *ptr = nullptr;
+  PinnedBuffer() = default;
+  PinnedBuffer(const PinnedBuffer &) = delete;
+  PinnedBuffer &operator=(const PinnedBuffer &) = delete;
+  ~PinnedBuffer() { reset(); }
+  int alloc(size_t bytes, const char *what) {
+    reset();
+    if (bytes == 0) bytes = 16;
+    if (hipHostMalloc(&ptr, bytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      ptr = nullptr;
+      return gosh::fail(GOSH_ENOMEM, "cannot allocate %zu pinned host bytes for %s", bytes, what);
+    }
+    return GOSH_OK;
+  }
+  void reset() {
+    if (ptr) (void)hipHostFree(ptr);
+    ptr = nullptr;
+  }
+  void swap(PinnedBuffer &o) { std::swap(ptr, o.ptr); }
+};
+
 double ms_since(std::chrono::steady_clock::time_point t0) {
   return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
 }
@@ -43,20 +73,50 @@ double ms_since(std::chrono::steady_clock::time_point t0) {
     if (e_ != hipSuccess) return gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_)); \
   } while (0)
 
-}  // namespace
+size_t level_bytes(const gosh_csr &g, int32_t d) {
+  return static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4) + static_cast<size_t>(g.nnz) * 4 +
+         static_cast<size_t>(g.n) * d * 4;
+}
 
-extern "C" int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p,
-                          float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
-                          float *M0_dev, gosh_level_stats *stats, void *hip_stream) {
+// Rows of a slice that a staging buffer on the device may hold: the budget left beside
+// `resident` bytes, at least 64 rows' worth.
+int chunk_rows(uint64_t budget, size_t resident, int32_t d, int64_t n, int64_t *rows) {
+  const size_t per_row = static_cast<size_t>(d) * 4 + 4;
+  size_t room = budget == 0 ? (size_t{1} << 30) : (budget > resident ? budget - resident : 0);
+  int64_t r = static_cast<int64_t>(room / per_row);
+  if (r < std::min<int64_t>(n, 64))
+    return gosh::fail(GOSH_EBUDGET, "device budget leaves no room for a staging slice of 64 rows");
+  *rows = std::min<int64_t>(r, n);
+  return GOSH_OK;
+}
+
+struct Plan {
+  int32_t d, k_neg;
+  float lr0;
+  uint64_t seed;
+  uint32_t flags;
+  uint64_t budget;
+  int32_t P_gpu, S_gpu, B;
+};
+
+int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p, float *M0_dev,
+               float *M0_host, gosh_level_stats *stats, hipStream_t st) {
   const int D = gosh_hierarchy_levels(h);
   if (D < 1) return gosh::fail(GOSH_EINVAL, "hierarchy is null or empty");
-  if (int rc = gosh::check_matrix(M0_dev, d, "M0")) return rc;
+  const int32_t d = pl.d;
   std::vector<int64_t> e_i(static_cast<size_t>(D));
   if (int rc = gosh_epoch_split(epochs, p, D, e_i.data())) return rc;
-  hipStream_t st = gosh::as_stream(hip_stream);
+  std::vector<gosh_csr> G(static_cast<size_t>(D));
+  for (int i = 0; i < D; ++i)
+    if (int rc = gosh_hierarchy_graph(h, i, &G[static_cast<size_t>(i)])) return rc;
+  auto fits = [&](int i) {
+    return pl.budget == 0 || level_bytes(G[static_cast<size_t>(i)], d) <= pl.budget;
+  };
+  if (M0_dev != nullptr && !fits(0))
+    return gosh::fail(GOSH_EBUDGET,
+                      "level 0 needs %zu bytes on the device, budget is %llu: use gosh_embed_host",
+                      level_bytes(G[0], d), (unsigned long long)pl.budget);
 
-  DeviceBuffer m_cur, m_next;  // matrix of the level being trained / of the next finer one
-  float *M_i = nullptr;
   hipEvent_t ev0, ev1;
   GOSH_HIP(hipEventCreate(&ev0), "hipEventCreate");
   GOSH_HIP(hipEventCreate(&ev1), "hipEventCreate");
@@ -68,90 +128,211 @@ extern "C" int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int
     }
   } guard{ev0, ev1};
 
-  for (int i = D - 1; i >= 0; --i) {
-    gosh_csr host{};
-    if (int rc = gosh_hierarchy_graph(h, i, &host)) return rc;
-    const size_t off_bytes = static_cast<size_t>(host.n + 1) * (host.xadj_is64 ? 8 : 4);
-    const size_t adj_bytes = static_cast<size_t>(host.nnz) * 4;
-    const size_t mat_bytes = static_cast<size_t>(host.n) * d * 4;
-    if (device_budget_bytes != 0 && off_bytes + adj_bytes + mat_bytes > device_budget_bytes)
-      return gosh::fail(GOSH_EBUDGET,
-                        "level %d needs %zu bytes on the device, budget is %llu: train it with "
-                        "gosh_train_parts",
-                        i, off_bytes + adj_bytes + mat_bytes, (unsigned long long)device_budget_bytes);
+  // The matrix of the current level lives either on the device (cur_dev) or on the host
+  // (cur_host); the buffers own it unless it is the caller's output array.
+  DeviceBuffer dev_own, dev_next;
+  PinnedBuffer host_own, host_next;
+  float *cur_dev = nullptr, *cur_host = nullptr;
 
-    // CopyToDevice(G_i): the graph arrays of this level.
-    auto t0 = std::chrono::steady_clock::now();
-    DeviceBuffer xadj_dev, adj_dev;
-    if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
-    if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
-    GOSH_HIP(hipMemcpyAsync(xadj_dev.ptr, host.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
-    if (adj_bytes)
-      GOSH_HIP(hipMemcpyAsync(adj_dev.ptr, host.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
-    GOSH_HIP(hipStreamSynchronize(st), "upload graph");
-    const double upload_ms = ms_since(t0);
+  for (int i = D - 1; i >= 0; --i) {
+    const gosh_csr &g = G[static_cast<size_t>(i)];
+    const size_t mat_bytes = static_cast<size_t>(g.n) * d * 4;
+    gosh_level_stats ls{};
+    ls.level = i;
+    ls.n = g.n;
+    ls.nnz = g.nnz;
+    ls.epochs = e_i[static_cast<size_t>(i)];
 
     if (i == D - 1) {
       // "Randomly initialize M_{D-1}"
-      if (i == 0) {
-        M_i = M0_dev;
+      if (fits(i)) {
+        if (i == 0 && M0_dev) cur_dev = M0_dev;
+        else {
+          if (int rc = dev_own.alloc(mat_bytes, "coarsest embedding")) return rc;
+          cur_dev = static_cast<float *>(dev_own.ptr);
+        }
+        if (int rc = gosh_init_embedding(cur_dev, g.n, d, pl.seed, static_cast<uint32_t>(i), st)) return rc;
       } else {
-        if (int rc = m_cur.alloc(mat_bytes, "coarsest embedding")) return rc;
-        M_i = static_cast<float *>(m_cur.ptr);
+        if (i == 0) cur_host = M0_host;
+        else {
+          if (int rc = host_own.alloc(mat_bytes, "coarsest embedding")) return rc;
+          cur_host = static_cast<float *>(host_own.ptr);
+        }
+        int64_t rows = 0;
+        if (int rc = chunk_rows(pl.budget, 0, d, g.n, &rows)) return rc;
+        DeviceBuffer slice;
+        if (int rc = slice.alloc(static_cast<size_t>(rows) * d * 4, "initialisation slice")) return rc;
+        for (int64_t lo = 0; lo < g.n; lo += rows) {
+          const int64_t cnt = std::min(rows, g.n - lo);
+          if (int rc = gosh::init_rows(static_cast<float *>(slice.ptr), lo, cnt, d, pl.seed,
+                                       static_cast<uint32_t>(i), st))
+            return rc;
+          GOSH_HIP(hipMemcpyAsync(cur_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4,
+                                  hipMemcpyDeviceToHost, st), "copy initial rows");
+          GOSH_HIP(hipStreamSynchronize(st), "initialise on host");
+        }
       }
-      if (int rc = gosh_init_embedding(M_i, host.n, d, seed, static_cast<uint32_t>(i), st)) return rc;
     }
 
-    gosh_csr dev = host;
-    dev.xadj = xadj_dev.ptr;
-    dev.adj = static_cast<const int32_t *>(adj_dev.ptr);
-    GOSH_HIP(hipEventRecord(ev0, st), "hipEventRecord");
-    for (int64_t j = 0; j < e_i[static_cast<size_t>(i)]; ++j) {
-      const float lr = gosh_lr(lr0, j, e_i[static_cast<size_t>(i)]);
-      if (int rc = gosh_train_epoch(&dev, M_i, d, k_neg, lr, seed, static_cast<uint32_t>(j),
-                                    static_cast<uint32_t>(i), flags, st))
+    if (cur_dev) {
+      // CopyToDevice(G_i) + TrainInGPU
+      auto t0 = std::chrono::steady_clock::now();
+      const size_t off_bytes = static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4);
+      const size_t adj_bytes = static_cast<size_t>(g.nnz) * 4;
+      DeviceBuffer xadj_dev, adj_dev;
+      if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
+      if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
+      GOSH_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
+      if (adj_bytes)
+        GOSH_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
+      GOSH_HIP(hipStreamSynchronize(st), "upload graph");
+      ls.upload_ms = ms_since(t0);
+      gosh_csr dev = g;
+      dev.xadj = xadj_dev.ptr;
+      dev.adj = static_cast<const int32_t *>(adj_dev.ptr);
+      GOSH_HIP(hipEventRecord(ev0, st), "hipEventRecord");
+      for (int64_t j = 0; j < ls.epochs; ++j) {
+        const float lr = gosh_lr(pl.lr0, j, ls.epochs);
+        if (int rc = gosh_train_epoch(&dev, cur_dev, d, pl.k_neg, lr, pl.seed, static_cast<uint32_t>(j),
+                                      static_cast<uint32_t>(i), pl.flags, st))
+          return rc;
+      }
+      GOSH_HIP(hipEventRecord(ev1, st), "hipEventRecord");
+      GOSH_HIP(hipEventSynchronize(ev1), "train level");
+      float ms = 0.f;
+      GOSH_HIP(hipEventElapsedTime(&ms, ev0, ev1), "hipEventElapsedTime");
+      ls.train_ms = ms;
+    } else {
+      // LargeGraphGPU
+      gosh_parts_stats ps{};
+      if (int rc = gosh_train_parts(&g, cur_host, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed,
+                                    static_cast<uint32_t>(i), pl.budget, pl.P_gpu, pl.S_gpu, pl.B, 0,
+                                    pl.flags, &ps))
         return rc;
+      ls.parts_K = ps.K;
+      ls.train_ms = ps.wall_ms;
     }
-    GOSH_HIP(hipEventRecord(ev1, st), "hipEventRecord");
-    GOSH_HIP(hipEventSynchronize(ev1), "train level");
-    float train_ms = 0.f;
-    GOSH_HIP(hipEventElapsedTime(&train_ms, ev0, ev1), "hipEventElapsedTime");
 
-    double project_ms = 0.0;
     if (i > 0) {
       // ExpandEmbedding(M_i, map_{i-1})
-      t0 = std::chrono::steady_clock::now();
+      auto t0 = std::chrono::steady_clock::now();
+      const gosh_csr &fine = G[static_cast<size_t>(i - 1)];
       const int32_t *map_host = nullptr;
       int64_t n_fine = 0;
       if (int rc = gosh_hierarchy_map(h, i - 1, &map_host, &n_fine)) return rc;
-      DeviceBuffer map_dev;
-      if (int rc = map_dev.alloc(static_cast<size_t>(n_fine) * 4, "map")) return rc;
-      GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host, static_cast<size_t>(n_fine) * 4,
-                              hipMemcpyHostToDevice, st), "copy map");
-      float *M_fine = M0_dev;
-      if (i - 1 > 0) {
-        if (int rc = m_next.alloc(static_cast<size_t>(n_fine) * d * 4, "finer embedding")) return rc;
-        M_fine = static_cast<float *>(m_next.ptr);
+      const size_t fine_bytes = static_cast<size_t>(n_fine) * d * 4;
+      const bool next_on_dev = fits(i - 1);
+      float *next_dev = nullptr, *next_host = nullptr;
+      if (next_on_dev) {
+        if (i - 1 == 0 && M0_dev) next_dev = M0_dev;
+        else {
+          if (int rc = dev_next.alloc(fine_bytes, "finer embedding")) return rc;
+          next_dev = static_cast<float *>(dev_next.ptr);
+        }
+      } else {
+        if (i - 1 == 0) next_host = M0_host;
+        else {
+          if (int rc = host_next.alloc(fine_bytes, "finer embedding")) return rc;
+          next_host = static_cast<float *>(host_next.ptr);
+        }
       }
-      if (int rc = gosh_project(M_i, host.n, static_cast<const int32_t *>(map_dev.ptr), n_fine, d,
-                                M_fine, st))
-        return rc;
-      GOSH_HIP(hipStreamSynchronize(st), "project");
-      project_ms = ms_since(t0);
-      m_cur.swap(m_next);
-      m_next.reset();
-      M_i = M_fine;
+      if (cur_dev && next_dev) {
+        DeviceBuffer map_dev;
+        if (int rc = map_dev.alloc(static_cast<size_t>(n_fine) * 4, "map")) return rc;
+        GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host, static_cast<size_t>(n_fine) * 4,
+                                hipMemcpyHostToDevice, st), "copy map");
+        if (int rc = gosh_project(cur_dev, g.n, static_cast<const int32_t *>(map_dev.ptr), n_fine, d,
+                                  next_dev, st))
+          return rc;
+        GOSH_HIP(hipStreamSynchronize(st), "project");
+      } else if (cur_dev && next_host) {
+        // project slice by slice through a device staging buffer
+        int64_t rows = 0;
+        if (int rc = chunk_rows(pl.budget, mat_bytes, d, n_fine, &rows)) return rc;
+        DeviceBuffer slice, map_dev;
+        if (int rc = slice.alloc(static_cast<size_t>(rows) * d * 4, "projection slice")) return rc;
+        if (int rc = map_dev.alloc(static_cast<size_t>(rows) * 4, "map slice")) return rc;
+        for (int64_t lo = 0; lo < n_fine; lo += rows) {
+          const int64_t cnt = std::min(rows, n_fine - lo);
+          GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host + lo, static_cast<size_t>(cnt) * 4,
+                                  hipMemcpyHostToDevice, st), "copy map slice");
+          if (int rc = gosh_project(cur_dev, g.n, static_cast<const int32_t *>(map_dev.ptr), cnt, d,
+                                    static_cast<float *>(slice.ptr), st))
+            return rc;
+          GOSH_HIP(hipMemcpyAsync(next_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4,
+                                  hipMemcpyDeviceToHost, st), "copy projected slice");
+          GOSH_HIP(hipStreamSynchronize(st), "project slice");
+        }
+      } else {
+        // the coarse matrix is on the host: gather its rows there (both levels exceed the
+        // budget), then upload if the finer level happens to fit
+        float *target = next_host;
+        PinnedBuffer temp;
+        if (next_dev) {
+          if (int rc = temp.alloc(fine_bytes, "projection staging")) return rc;
+          target = static_cast<float *>(temp.ptr);
+        }
+        const size_t row_bytes = static_cast<size_t>(d) * 4;
+#pragma omp parallel for schedule(static)
+        for (int64_t v = 0; v < n_fine; ++v)
+          std::memcpy(target + v * d, cur_host + static_cast<int64_t>(map_host[v]) * d, row_bytes);
+        if (next_dev) {
+          GOSH_HIP(hipMemcpyAsync(next_dev, target, fine_bytes, hipMemcpyHostToDevice, st), "upload");
+          GOSH_HIP(hipStreamSynchronize(st), "upload projected level");
+        }
+      }
+      ls.project_ms = ms_since(t0);
+      (void)fine;
+      dev_own.swap(dev_next);
+      dev_next.reset();
+      host_own.swap(host_next);
+      host_next.reset();
+      cur_dev = next_dev;
+      cur_host = next_host;
     }
-    if (stats) {
-      gosh_level_stats &s = stats[i];
-      s.level = i;
-      s.n = host.n;
-      s.nnz = host.nnz;
-      s.epochs = e_i[static_cast<size_t>(i)];
-      s.upload_ms = upload_ms;
-      s.train_ms = train_ms;
-      s.project_ms = project_ms;
-    }
+    if (stats) stats[i] = ls;
+  }
+
+  // Deliver M_0 where the caller wants it.
+  if (M0_host && cur_dev) {
+    GOSH_HIP(hipMemcpyAsync(M0_host, cur_dev, static_cast<size_t>(G[0].n) * d * 4, hipMemcpyDeviceToHost, st),
+             "download M_0");
+    GOSH_HIP(hipStreamSynchronize(st), "download M_0");
   }
   return GOSH_OK;
 }
+
+int check_common(int32_t d, int32_t k_neg) {
+  if (int rc = gosh::check_dim(d)) return rc;
+  if (k_neg < 0 || k_neg > GOSH_MAX_NEG)
+    return gosh::fail(GOSH_EINVAL, "k_neg = %d: must be in [0, %d]", k_neg, GOSH_MAX_NEG);
+  return GOSH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p, float lr0,
+               uint64_t seed, uint32_t flags, uint64_t device_budget_bytes, float *M0_dev,
+               gosh_level_stats *stats, void *hip_stream) {
+  if (int rc = check_common(d, k_neg)) return rc;
+  if (int rc = gosh::check_matrix(M0_dev, d, "M0")) return rc;
+  // A level above level 0 can only exceed the budget if level 0 does too, which is refused.
+  const Plan pl{d, k_neg, lr0, seed, flags, device_budget_bytes, 3, 4, 5};
+  return embed_impl(h, pl, epochs, p, M0_dev, nullptr, stats, gosh::as_stream(hip_stream));
+}
+
+int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p,
+                    float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
+                    int32_t P_gpu, int32_t S_gpu, int32_t B, float *M0_host, gosh_level_stats *stats,
+                    void *hip_stream) {
+  if (int rc = check_common(d, k_neg)) return rc;
+  if (int rc = gosh::check_matrix(M0_host, d, "M0")) return rc;
+  if (P_gpu < 2 || S_gpu < 1 || B < 1)
+    return gosh::fail(GOSH_EINVAL, "need P_gpu >= 2, S_gpu >= 1, B >= 1");
+  const Plan pl{d, k_neg, lr0, seed, flags, device_budget_bytes, P_gpu, S_gpu, B};
+  return embed_impl(h, pl, epochs, p, nullptr, M0_host, stats, gosh::as_stream(hip_stream));
+}
+
+}  // extern "C"

@@ -7,7 +7,8 @@
 // carried by HIP streams and events, and one extra host thread draws the positives):
 //   * sampler thread: fills pools of positive samples on the host, a bounded number of
 //     pairs ahead (an OpenMP team fills one pool);
-//   * copy stream: part write-back / part upload / pool upload, overlapped with
+//   * copy-in stream: part upload / pool upload, and copy-out stream: part write-back
+//     (the two directions of the host link run at the same time), overlapped with
 //   * compute stream: one pair kernel per visited pair, in the fixed inside-out order.
 #include <hip/hip_runtime.h>
 #include <omp.h>
@@ -305,7 +306,8 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   const int NS = S + 1;  // host staging buffers for pools
   std::vector<int32_t *> staging(NS, nullptr);
   uint32_t *hot_bits_dev = nullptr;
-  hipStream_t compute = nullptr, copy = nullptr;
+  hipStream_t compute = nullptr, copy = nullptr, copy_out = nullptr;
+  std::vector<hipEvent_t> slot_flushed(P, nullptr);
   std::vector<hipEvent_t> slot_ready(P, nullptr), slot_used(P, nullptr), pool_ready(S, nullptr),
       pool_used(S, nullptr), staging_done(NS, nullptr);
   std::vector<hipEvent_t> k_begin, k_end;
@@ -330,10 +332,12 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
 
   PARTS_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
   PARTS_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
+  PARTS_HIP(hipStreamCreateWithFlags(&copy_out, hipStreamNonBlocking), "hipStreamCreate");
   for (int s = 0; s < P; ++s) {
     PARTS_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * d * 4), "hipMalloc part slot");
     PARTS_HIP(hipEventCreateWithFlags(&slot_ready[s], hipEventDisableTiming), "hipEventCreate");
     PARTS_HIP(hipEventCreateWithFlags(&slot_used[s], hipEventDisableTiming), "hipEventCreate");
+    PARTS_HIP(hipEventCreateWithFlags(&slot_flushed[s], hipEventDisableTiming), "hipEventCreate");
   }
   for (int s = 0; s < S; ++s) {
     PARTS_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
@@ -434,13 +438,20 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         if (nu > farthest) { farthest = nu; victim = s; }
       }
       if (victim < 0) return -1;
-      if (hipStreamWaitEvent(copy, slot_used[victim], 0) != hipSuccess) return -2;
       if (slot_part[victim] >= 0) {
+        // write the old part back on the outbound stream, then let the inbound stream reuse
+        // the slot; a later upload of the same part must also see these host bytes, which
+        // the inbound stream's wait on slot_flushed guarantees (it is recorded in order)
         const int32_t old = slot_part[victim];
         const size_t bytes = static_cast<size_t>(L.size(old)) * d * 4;
+        if (hipStreamWaitEvent(copy_out, slot_used[victim], 0) != hipSuccess) return -2;
         if (hipMemcpyAsync(M_host + static_cast<int64_t>(L.lo(old)) * d, slot[victim], bytes,
-                           hipMemcpyDeviceToHost, copy) != hipSuccess) return -2;
+                           hipMemcpyDeviceToHost, copy_out) != hipSuccess) return -2;
+        if (hipEventRecord(slot_flushed[victim], copy_out) != hipSuccess) return -2;
+        if (hipStreamWaitEvent(copy, slot_flushed[victim], 0) != hipSuccess) return -2;
         st.bytes_d2h += bytes;
+      } else if (hipStreamWaitEvent(copy, slot_used[victim], 0) != hipSuccess) {
+        return -2;
       }
       const size_t bytes = static_cast<size_t>(L.size(p)) * d * 4;
       if (hipMemcpyAsync(slot[victim], M_host + static_cast<int64_t>(L.lo(p)) * d, bytes,
@@ -544,13 +555,14 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         if (slot_part[s] < 0) continue;
         const int32_t old = slot_part[s];
         const size_t bytes = static_cast<size_t>(L.size(old)) * d * 4;
-        PARTS_HIP(hipStreamWaitEvent(copy, slot_used[s], 0), "hipStreamWaitEvent");
+        PARTS_HIP(hipStreamWaitEvent(copy_out, slot_used[s], 0), "hipStreamWaitEvent");
         PARTS_HIP(hipMemcpyAsync(M_host + static_cast<int64_t>(L.lo(old)) * d, slot[s], bytes,
-                                 hipMemcpyDeviceToHost, copy), "part write-back");
+                                 hipMemcpyDeviceToHost, copy_out), "part write-back");
         st.bytes_d2h += bytes;
       }
       PARTS_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
       PARTS_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
+      PARTS_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
       for (int64_t vi = 0; vi < visits; ++vi) {
         float ms = 0.f;
         if (k_begin[vi] && k_end[vi] && hipEventElapsedTime(&ms, k_begin[vi], k_end[vi]) == hipSuccess)
@@ -569,6 +581,8 @@ done:
   if (sampler.joinable()) sampler.join();
   if (compute) (void)hipStreamSynchronize(compute);
   if (copy) (void)hipStreamSynchronize(copy);
+  if (copy_out) (void)hipStreamSynchronize(copy_out);
+  for (auto e : slot_flushed) if (e) (void)hipEventDestroy(e);
   for (auto e : k_begin) if (e) (void)hipEventDestroy(e);
   for (auto e : k_end) if (e) (void)hipEventDestroy(e);
   for (auto e : slot_ready) if (e) (void)hipEventDestroy(e);
@@ -582,6 +596,7 @@ done:
   if (hot_bits_dev) (void)hipFree(hot_bits_dev);
   if (compute) (void)hipStreamDestroy(compute);
   if (copy) (void)hipStreamDestroy(copy);
+  if (copy_out) (void)hipStreamDestroy(copy_out);
   st.wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   if (stats_out) *stats_out = st;
   return rc;

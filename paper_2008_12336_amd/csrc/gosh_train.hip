@@ -90,12 +90,14 @@ __global__ __launch_bounds__(256) void mark_hot_kernel(const OffT *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------------
+// M points at row `first_row` of the matrix being initialised.
 __global__ __launch_bounds__(256) void init_embedding_kernel(float4 *__restrict__ M, int64_t total4,
-                                                             int32_t d4, uint32_t key0,
-                                                             uint32_t key1, uint32_t level) {
+                                                             int64_t first_row, int32_t d4,
+                                                             uint32_t key0, uint32_t key1,
+                                                             uint32_t level) {
   const double d = 4.0 * d4;
   for (int64_t i = blockIdx.x * 256LL + threadIdx.x; i < total4; i += gridDim.x * 256LL) {
-    const uint32_t v = static_cast<uint32_t>(i / d4), c4 = static_cast<uint32_t>(i % d4);
+    const uint32_t v = static_cast<uint32_t>(first_row + i / d4), c4 = static_cast<uint32_t>(i % d4);
     uint32_t w2, w3;
     const uint64_t w01 = philox_draw(v, c4, 0xFFFFFFFFu, level, key0, key1, &w2, &w3);
     const uint32_t w[4] = {static_cast<uint32_t>(w01), static_cast<uint32_t>(w01 >> 32), w2, w3};
@@ -190,18 +192,26 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
 
 }  // namespace
 
+namespace gosh {
+
+int init_rows(float *rows_dev, int64_t first_row, int64_t count, int32_t d, uint64_t seed,
+              uint32_t level, hipStream_t st) {
+  const int64_t total4 = count * (d / 4);
+  hipLaunchKernelGGL(init_embedding_kernel, dim3(grid_for(total4, 256, 1 << 16)), dim3(256), 0, st,
+                     reinterpret_cast<float4 *>(rows_dev), total4, first_row, d / 4,
+                     static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), level);
+  return check_launch("init_embedding_kernel");
+}
+
+}  // namespace gosh
+
 extern "C" {
 
 int gosh_init_embedding(float *M_dev, int64_t n, int32_t d, uint64_t seed, uint32_t level,
                         void *hip_stream) {
   if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
   if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
-  const int64_t total4 = n * (d / 4);
-  hipLaunchKernelGGL(init_embedding_kernel, dim3(grid_for(total4, 256, 1 << 16)), dim3(256), 0,
-                     gosh::as_stream(hip_stream), reinterpret_cast<float4 *>(M_dev), total4, d / 4,
-                     static_cast<uint32_t>(seed),
-                     static_cast<uint32_t>(seed >> 32), level);
-  return gosh::check_launch("init_embedding_kernel");
+  return gosh::init_rows(M_dev, 0, n, d, seed, level, gosh::as_stream(hip_stream));
 }
 
 int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint32_t epoch,
@@ -245,9 +255,9 @@ int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map
   if (int rc = gosh::check_matrix(M_coarse_dev, d, "M_coarse")) return rc;
   if (int rc = gosh::check_matrix(M_fine_dev, d, "M_fine")) return rc;
   if (map_dev == nullptr) return gosh::fail(GOSH_EINVAL, "map is null");
-  if (n_coarse < 1 || n_fine < 1 || n_coarse > n_fine)
-    return gosh::fail(GOSH_EINVAL, "need 1 <= n_coarse (%lld) <= n_fine (%lld)", (long long)n_coarse,
-                      (long long)n_fine);
+  if (n_coarse < 1 || n_fine < 1)
+    return gosh::fail(GOSH_EINVAL, "need n_coarse (%lld) >= 1 and n_fine (%lld) >= 1",
+                      (long long)n_coarse, (long long)n_fine);
   const int64_t total4 = n_fine * (d / 4);
   hipLaunchKernelGGL(project_kernel, dim3(grid_for(total4, 256, 1 << 16)), dim3(256), 0,
                      gosh::as_stream(hip_stream), reinterpret_cast<const float4 *>(M_coarse_dev),

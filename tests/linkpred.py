@@ -57,11 +57,16 @@ def aucroc(M, sets, max_train=200000, seed=0):
         nt = nt[rng.choice(len(nt), max_train, replace=False)]
     Xtr = np.vstack((_features(M, pt), _features(M, nt)))
     ytr = np.concatenate((np.ones(len(pt)), np.zeros(len(nt))))
-    scale = max(np.abs(Xtr).max(), 1e-12)
-    clf = LogisticRegression(max_iter=500, C=10.0)
-    clf.fit(Xtr / scale, ytr)
+    # Hub rows of a power-law graph can be orders of magnitude longer than the rest, so
+    # the features are standardised per column (statistics of the training pairs) and
+    # clipped; otherwise a handful of pairs sets the scale and the classifier sees zeros.
+    mean = Xtr.mean(axis=0)
+    std = np.maximum(Xtr.std(axis=0), 1e-30)
+    prep = lambda X: np.clip((X - mean) / std, -10.0, 10.0)
+    clf = LogisticRegression(max_iter=500, C=1.0)
+    clf.fit(prep(Xtr), ytr)
     Xte = np.vstack((_features(M, sets["pos_test"]), _features(M, sets["neg_test"])))
     yte = np.concatenate((np.ones(len(sets["pos_test"])), np.zeros(len(sets["neg_test"]))))
-    held = roc_auc_score(yte, clf.decision_function(Xte / scale))
-    fit = roc_auc_score(ytr, clf.decision_function(Xtr / scale))
+    held = roc_auc_score(yte, clf.decision_function(prep(Xte)))
+    fit = roc_auc_score(ytr, clf.decision_function(prep(Xtr)))
     return float(held), float(fit)

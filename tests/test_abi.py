@@ -95,6 +95,6 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.gosh_sample_epoch(C.byref(g), 3, 1, 0, 0, 0, None) == -1
     assert lib.gosh_init_embedding(ok_ptr, 0, 32, 1, 0, None) == -1
     assert lib.gosh_init_embedding(ok_ptr, 10, 30, 1, 0, None) == -1
-    assert lib.gosh_project(ok_ptr, 10, 0x3000, 5, 32, ok_ptr * 2, None) == -1  # coarse > fine
+    assert lib.gosh_project(ok_ptr, 0, 0x3000, 5, 32, ok_ptr * 2, None) == -1  # empty coarse level
     assert lib.gosh_project(ok_ptr, 5, 0, 10, 32, ok_ptr * 2, None) == -1
     assert lib.gosh_epoch_split(10, 0.5, 3, None) == -1

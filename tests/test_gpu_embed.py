@@ -78,3 +78,26 @@ def test_hogwild_vcycle_aucroc():
     say("[auc vcycle] per level ms: " + ", ".join(f"L{s['level']}:{s['train_ms']:.1f}" for s in stats))
     assert hg > 0.65 and ho > 0.65
     assert abs(hg - ho) <= 0.01 and abs(fg - fo) <= 0.01
+
+
+@pytest.mark.parametrize("budget_kib,expect_parts", [(0, 0), (4096, 0), (300, 1), (200, 2), (64, 4)])
+def test_budgeted_vcycle_on_host_matches_oracle(budget_kib, expect_parts):
+    """Alg. 2 with levels above the device budget trained by the rotation: sequential mode
+    against the oracle's composition of Alg. 3 / Alg. 5 levels."""
+    n = 1 << 11
+    c = graphgen.to_csr(n, graphgen.rmat(11, 1 << 14, 3))
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    d, k, epochs, p, lr0, seed = 32, 3, 40, 0.3, 0.05, 5
+    budget = budget_kib * 1024
+    want, modes = O.embed_budget(xadj, adj, d, k, epochs, p, lr0, seed,
+                                 budget if budget else 1 << 40, threshold=100, min_shrink=0.8)
+    h = G.gosh_coarsen(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
+    M0 = torch.zeros(n, d, dtype=torch.float32).pin_memory()
+    stats = G.gosh_embed_host(h, M0, k, epochs, p, lr0, seed, flags=G.GOSH_FLAG_SEQUENTIAL,
+                              device_budget_bytes=budget)
+    got_modes = [s["parts_K"] for s in stats]
+    err = rel_err(M0.numpy(), want)
+    say(f"[budget {budget_kib} KiB] oracle modes {modes} gpu modes {got_modes} err {err:.2e}")
+    assert got_modes == modes
+    assert sum(1 for m in modes if m) == expect_parts
+    assert err <= 1e-5
