@@ -281,7 +281,7 @@ def main() -> int:
                    "finite": finite},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "train_epoch_kernel", "kernel_ms_avg": avg_kernel_s * 1e3,
+                     "kernel": "sgd_kernel<EpochWork>", "kernel_ms_avg": avg_kernel_s * 1e3,
                      "kernel_ms_min": float(np.min(kernel_ms)),
                      "algorithmic_bytes_per_launch": row_bytes_per_launch},
         "cpu_baseline": cpu,

@@ -132,12 +132,9 @@ struct RowAgent32 {
 enum HotMode : int32_t { kHotNone = 0, kHotBitmap = 1, kHotAll = 2 };
 
 struct HotSet {
-  const uint32_t *bits;  // one bit per vertex, used when mode == kHotBitmap
+  const uint32_t *bits;  // one bit per vertex when mode == kHotBitmap; in the other modes
+                         // still a readable device word (the kernel reads word 0 blindly)
   int32_t mode;
-  __device__ __forceinline__ bool contains(int32_t v) const {
-    if (mode == kHotBitmap) return (bits[v >> 5] >> (v & 31)) & 1u;
-    return mode == kHotAll;
-  }
 };
 
 struct SgdArgs {
@@ -158,11 +155,21 @@ constexpr int kChunk = 4;  // sample rows in flight per source
 //     int64_t count()                         number of sources
 //     int32_t source_id(int64_t i)            vertex id of source i (random counter, self test)
 //     float  *source_row(int64_t i)
-//     int32_t sample(int64_t i, int32_t id, int32_t t)   vertex id of sample t, or -1 = none
+//     int32_t sample(int64_t i, int32_t id, int32_t t, bool want, bool positive)
+//                                             vertex id of sample t (-1 = none, or !want);
+//                                             must be free of branches around its memory
+//                                             reads (read a safe address when !want)
 //     float  *sample_row(int64_t i, int32_t v)
+//   Sample t of a source is a positive iff t % (k_neg + 1) == 0.
 //   P: row access policy; LPG lanes per source, UPL units per lane (LPG*UPL*P::F >= d).
 //   SEQ: a single lane group walks all sources in ascending index (the sequential-order
 //   result); otherwise lane groups stride over the sources.
+//
+// The body is written without branches around memory reads: a sample that does not
+// exist, or a column beyond d, reads a harmless valid address and is masked afterwards
+// (its step is forced to zero, its store is skipped).  All reads of a chunk are therefore
+// issued back to back and waited for once, which is what keeps their latencies overlapped;
+// with predicated reads the compiler splits the code into blocks and waits in each.
 template <class P, int LPG, int UPL, class W, bool SEQ>
 __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   constexpr int kGroupsPerWave = 64 / LPG;
@@ -179,17 +186,21 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   const int64_t first = SEQ ? 0 : wave * kGroupsPerWave + lane / LPG;
   const int32_t d = a.d;
   const int32_t per_round = a.k_neg + 1;
+  const bool use_bitmap = !SEQ && a.hot.mode == kHotBitmap;
+  const bool all_hot = !SEQ && a.hot.mode == kHotAll;
+  const uint32_t *const bits = a.hot.bits;  // always a readable word, also without a bitmap
 
   // Lane gl owns floats [(gl + i*LPG)*F, +F) of a row, i < UPL: consecutive lanes touch
-  // consecutive addresses, so each access instruction covers whole cache lines.
-  int32_t col[UPL];
+  // consecutive addresses, so each access instruction covers whole cache lines.  Columns
+  // beyond d are read from the last unit of the row instead and masked.
+  int32_t col[UPL], col_read[UPL];
   bool col_ok[UPL];
 #pragma unroll
   for (int i = 0; i < UPL; ++i) {
     col[i] = (gl + i * LPG) * F;
     col_ok[i] = col[i] < d;
+    col_read[i] = col_ok[i] ? col[i] : d - F;
   }
-  const U zero{};
 
   // The loop bound is uniform over the wave; groups past the end idle inside.
   const int64_t first_of_wave = SEQ ? 0 : wave * kGroupsPerWave;
@@ -200,52 +211,70 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
     float *const src_row = w.source_row(idx);
     U s[UPL];
 #pragma unroll
-    for (int i = 0; i < UPL; ++i) s[i] = col_ok[i] ? P::load(src_row + col[i]) : zero;
-    const bool src_hot = !SEQ && a.hot.contains(src);
+    for (int i = 0; i < UPL; ++i) {
+      s[i] = P::load(src_row + col_read[i]);
+#pragma unroll
+      for (int c = 0; c < F; ++c) s[i].v[c] = col_ok[i] ? s[i].v[c] : 0.f;
+    }
+    const uint32_t src_word = bits[use_bitmap ? (src >> 5) : 0];
     U s_before[UPL];
 #pragma unroll
     for (int i = 0; i < UPL; ++i) s_before[i] = s[i];
 
+    int32_t next_positive = 0;  // sample index of the next positive (one per round)
     for (int32_t t0 = 0; t0 < a.samples; t0 += kChunk) {
-      // Sample ids of this chunk: lane q of the group evaluates sample t0+q, then the
-      // ids are broadcast inside the group.
+      // Which samples of this chunk are positives (uniform over the wave).
+      bool is_pos[kChunk];
+#pragma unroll
+      for (int q = 0; q < kChunk; ++q) {
+        is_pos[q] = (t0 + q == next_positive);
+        if (is_pos[q]) next_positive += per_round;
+      }
+      // Lane q of the group evaluates sample t0+q (in several passes if the group has
+      // fewer than kChunk lanes), then the ids are broadcast inside the group.
       int32_t v[kChunk];
 #pragma unroll
       for (int p = 0; p < kChunk; p += LPG) {
         const int32_t t = t0 + p + gl;
-        int32_t mine = -1;
-        if (p + gl < kChunk && t < a.samples) mine = w.sample(idx, src, t);
+        const bool want = p + gl < kChunk && t < a.samples;
+        bool mine_pos = false;
+#pragma unroll
+        for (int q = 0; q < LPG && p + q < kChunk; ++q) mine_pos = (gl == q) ? is_pos[p + q] : mine_pos;
+        const int32_t mine = w.sample(idx, src, want ? t : 0, want, mine_pos);
 #pragma unroll
         for (int q = 0; q < LPG && p + q < kChunk; ++q) v[p + q] = __shfl(mine, q, LPG);
       }
-      // A sample that hits the source itself applies no update.
+
+      // Request every row of the chunk (a missing sample reads the source row instead).
+      U r[kChunk][UPL];
+      uint32_t word[kChunk];
+      bool valid[kChunk];
+#pragma unroll
+      for (int q = 0; q < kChunk; ++q) {
+        valid[q] = v[q] >= 0 && v[q] != src;  // a sample that hits the source applies no update
+        const float *row = valid[q] ? w.sample_row(idx, v[q]) : src_row;
+#pragma unroll
+        for (int i = 0; i < UPL; ++i) r[q][i] = P::load(row + col_read[i]);
+        word[q] = bits[(use_bitmap && valid[q]) ? (v[q] >> 5) : 0];
+      }
 #pragma unroll
       for (int q = 0; q < kChunk; ++q)
-        if (v[q] == src) v[q] = -1;
-
-      // Fetch all rows of the chunk before using any of them.
-      U r[kChunk][UPL];
-      float *row[kChunk];
-      bool hot[kChunk];
 #pragma unroll
-      for (int q = 0; q < kChunk; ++q) {
-        row[q] = v[q] >= 0 ? w.sample_row(idx, v[q]) : src_row;
+        for (int i = 0; i < UPL; ++i)
 #pragma unroll
-        for (int i = 0; i < UPL; ++i) r[q][i] = (v[q] >= 0 && col_ok[i]) ? P::load(row[q] + col[i]) : zero;
-        hot[q] = !SEQ && v[q] >= 0 && a.hot.contains(v[q]);
-      }
+          for (int c = 0; c < F; ++c) r[q][i].v[c] = col_ok[i] ? r[q][i].v[c] : 0.f;
 
 #pragma unroll
       for (int q = 0; q < kChunk; ++q) {
-        if (v[q] < 0) continue;  // uniform over the group
         float partial = 0.f;
 #pragma unroll
         for (int i = 0; i < UPL; ++i)
 #pragma unroll
           for (int c = 0; c < F; ++c) partial = fmaf(s[i].v[c], r[q][i].v[c], partial);
         const float x = group_sum<LPG>(partial);
-        const float label = ((t0 + q) % per_round == 0) ? 1.f : 0.f;
-        const float g = a.lr * (label - 1.f / (1.f + expf(-x)));
+        const float label = is_pos[q] ? 1.f : 0.f;
+        // a missing sample takes a zero step: both rows stay exactly as they are
+        const float g = valid[q] ? a.lr * (label - 1.f / (1.f + expf(-x))) : 0.f;
 #pragma unroll
         for (int i = 0; i < UPL; ++i)
 #pragma unroll
@@ -253,27 +282,34 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
             s[i].v[c] = fmaf(g, r[q][i].v[c], s[i].v[c]);
             r[q][i].v[c] = fmaf(g, s[i].v[c], r[q][i].v[c]);
           }
-        if (hot[q]) {  // uniform over the group
+        if (valid[q]) {  // uniform over the group; only writes inside
+          float *const row = w.sample_row(idx, v[q]);
+          const bool hot = all_hot || ((word[q] >> (v[q] & 31)) & 1u);
+          if (hot) {
 #pragma unroll
-          for (int i = 0; i < UPL; ++i)
+            for (int i = 0; i < UPL; ++i)
 #pragma unroll
-            for (int c = 0; c < F; ++c)
-              if (col_ok[i]) atomic_step(row[q] + col[i] + c, g * s[i].v[c]);
-        } else {
+              for (int c = 0; c < F; ++c)
+                if (col_ok[i]) atomic_step(row + col[i] + c, g * s[i].v[c]);
+          } else {
 #pragma unroll
-          for (int i = 0; i < UPL; ++i)
-            if (col_ok[i]) P::store(row[q] + col[i], r[q][i]);
+            for (int i = 0; i < UPL; ++i)
+              if (col_ok[i]) P::store(row + col[i], r[q][i]);
+          }
         }
         // A later sample of the same chunk that names the same vertex must see this
         // update: forward the registers instead of the stale prefetched copy.
 #pragma unroll
-        for (int z = q + 1; z < kChunk; ++z)
-          if (v[z] == v[q]) {
+        for (int z = q + 1; z < kChunk; ++z) {
+          const bool same = valid[q] && v[z] == v[q];
 #pragma unroll
-            for (int i = 0; i < UPL; ++i) r[z][i] = r[q][i];
-          }
+          for (int i = 0; i < UPL; ++i)
+#pragma unroll
+            for (int c = 0; c < F; ++c) r[z][i].v[c] = same ? r[q][i].v[c] : r[z][i].v[c];
+        }
       }
     }
+    const bool src_hot = all_hot || ((src_word >> (src & 31)) & 1u);
     if (src_hot) {
 #pragma unroll
       for (int i = 0; i < UPL; ++i)

@@ -55,18 +55,21 @@ struct PairWork {
   __device__ __forceinline__ float *source_row(int64_t i) const {
     return i < a_n ? a_rows + i * d : b_rows + (i - a_n) * d;
   }
-  __device__ __forceinline__ int32_t sample(int64_t i, int32_t src, int32_t t) const {
+  // Branch-free around the pool read: a lane that does not want a positive reads entry 0.
+  __device__ __forceinline__ int32_t sample(int64_t i, int32_t src, int32_t t, bool want,
+                                            bool positive) const {
     const int side = i >= a_n;
-    const int32_t round = t / per_round, j = t % per_round;
-    if (j == 0) {
-      const int64_t local = side ? i - a_n : i;
-      return (side ? pool_b : pool_a)[local * B + round];
-    }
+    const int64_t local = side ? i - a_n : i;
+    const int32_t *pool = side ? pool_b : pool_a;
+    const int32_t from_pool = pool[(want && positive) ? local * B + t / per_round : 0];
     const int32_t other_lo = side ? a_lo : b_lo, other_n = side ? a_n : b_n;
     const uint64_t r = philox_draw(static_cast<uint32_t>(src),
                                    static_cast<uint32_t>(side * B * per_round + t), rotation, word3,
                                    key0, key1);
-    return other_lo + static_cast<int32_t>(scale_draw(r, static_cast<uint32_t>(other_n)));
+    // an empty partner part (possible for the last parts of a split) offers no negative
+    const int32_t uniform =
+        other_n > 0 ? other_lo + static_cast<int32_t>(scale_draw(r, static_cast<uint32_t>(other_n))) : -1;
+    return want ? (positive ? from_pool : uniform) : -1;
   }
   __device__ __forceinline__ float *sample_row(int64_t i, int32_t v) const {
     return i >= a_n ? a_rows + static_cast<int64_t>(v - a_lo) * d
@@ -80,7 +83,8 @@ __global__ __launch_bounds__(256) void pair_stream_kernel(PairWork w, int32_t sa
   const int64_t total = w.count() * samples;
   for (int64_t x = blockIdx.x * 256LL + threadIdx.x; x < total; x += gridDim.x * 256LL) {
     const int64_t i = x / samples;
-    out[x] = w.sample(i, w.source_id(i), static_cast<int32_t>(x % samples));
+    const int32_t t = static_cast<int32_t>(x % samples);
+    out[x] = w.sample(i, w.source_id(i), t, true, t % w.per_round == 0);
   }
 }
 
@@ -381,6 +385,12 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       hot.bits = hot_bits_dev;
     }
     hot.mode = mode;
+  }
+  if (hot.bits == nullptr) {
+    // the kernel reads word 0 of the bitmap unconditionally
+    PARTS_HIP(hipMalloc(&hot_bits_dev, 64), "hipMalloc hot bitmap");
+    PARTS_HIP(hipMemset(hot_bits_dev, 0, 64), "hipMemset hot bitmap");
+    hot.bits = hot_bits_dev;
   }
 
   // ---- sampler thread: pools of positives, at most NS visits ahead of their release ------

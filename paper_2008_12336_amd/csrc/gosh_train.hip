@@ -63,8 +63,23 @@ struct EpochWork {
   __device__ __forceinline__ int64_t count() const { return s.n; }
   __device__ __forceinline__ int32_t source_id(int64_t i) const { return static_cast<int32_t>(i); }
   __device__ __forceinline__ float *source_row(int64_t i) const { return M + i * d; }
-  __device__ __forceinline__ int32_t sample(int64_t, int32_t src, int32_t t) const {
-    return draw_sample<OffT>(s, static_cast<uint32_t>(src), static_cast<uint32_t>(t));
+  // Sample t of a source is draw t; the positive reads the neighbour list.  Written
+  // without branches around the reads: lanes that do not want a positive read the
+  // first offset again instead of a neighbour entry.
+  __device__ __forceinline__ int32_t sample(int64_t, int32_t src, int32_t t, bool want,
+                                            bool positive) const {
+    const uint64_t r = philox_draw(static_cast<uint32_t>(src), static_cast<uint32_t>(t), s.epoch,
+                                   s.level, s.key0, s.key1);
+    const OffT *xadj = static_cast<const OffT *>(s.xadj);
+    const OffT begin = xadj[src];
+    const uint32_t deg = static_cast<uint32_t>(xadj[src + 1] - begin);
+    const bool read_adj = want && positive && deg != 0;
+    const int32_t *entry = read_adj ? s.adj + (begin + static_cast<OffT>(scale_draw(r, deg)))
+                                    : reinterpret_cast<const int32_t *>(xadj);
+    const int32_t neighbour = *entry;
+    const int32_t uniform = static_cast<int32_t>(scale_draw(r, s.n));
+    const int32_t id = positive ? (read_adj ? neighbour : -1) : uniform;
+    return want ? id : -1;
   }
   __device__ __forceinline__ float *sample_row(int64_t, int32_t v) const {
     return M + static_cast<int64_t>(v) * d;
@@ -185,6 +200,12 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
       a.hot.bits = static_cast<const uint32_t *>(bits);
     }
     a.hot.mode = mode;
+  }
+  if (a.hot.bits == nullptr) {
+    // the kernel reads word 0 of the bitmap unconditionally
+    void *bits = nullptr;
+    if (int rc = gosh::hot_scratch(8, &bits)) return rc;
+    a.hot.bits = static_cast<const uint32_t *>(bits);
   }
   gosh::SgdLauncher<EpochWork<OffT>>::launch(w, a, n, seq, gosh::tuning().row_policy == 0, max_waves, st);
   return gosh::check_launch("sgd_kernel (epoch)");

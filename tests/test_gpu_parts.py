@@ -50,6 +50,7 @@ def budget_for(n, d, K, P, S, B):
     (500, 8, 1, 3, 4, 5, 3, 10),
     (900, 64, 5, 3, 2, 3, 2, 45),
     (700, 100, 6, 4, 3, 1, 5, 12),
+    (9, 8, 4, 3, 2, 2, 3, 16),  # ceil(9/4) = 3 rows per part: the fourth part is empty
 ])
 def test_sequential_rotation_matches_oracle(n, d, K, P, S, B, k, epochs):
     say(f"[parts-seq] n={n} d={d} K={K} P={P} S={S} B={B} k={k} epochs={epochs}")
@@ -60,10 +61,10 @@ def test_sequential_rotation_matches_oracle(n, d, K, P, S, B, k, epochs):
     O.train_parts(xadj, adj, want, k, epochs, 0.1, 7, 2, K, B)
     budget = budget_for(n, d, K, P, S, B)
     plan = G.gosh_parts_plan(n, d, epochs, budget, P, S, B)
-    assert plan["K"] == K
+    assert plan["K"] <= K
     M = torch.from_numpy(M0.copy()).pin_memory()
     st = G.gosh_train_parts(n, c.xadj, c.adj, M, k, epochs, 0.1, 7, level=2, device_budget_bytes=budget,
-                            P_gpu=P, S_gpu=S, B=B, flags=G.GOSH_FLAG_SEQUENTIAL)
+                            P_gpu=P, S_gpu=S, B=B, force_K=K, flags=G.GOSH_FLAG_SEQUENTIAL)
     err = rel_err(M.numpy(), want)
     say(f"            K={st['K']} rotations={st['rotations']} visits={st['pair_visits']} err={err:.2e} "
         f"h2d={st['bytes_h2d']} d2h={st['bytes_d2h']}")
