@@ -107,6 +107,26 @@ struct RowPlain128 {
   }
 };
 
+// RowAgent64: 64-bit agent-scope accesses, two consecutive floats per lane.  Used for
+// d <= 64, where a row is at most two lines: one instruction per row and lane group
+// instead of four keeps the request count per row down (rows that small are bound by
+// the number of memory requests, not by bytes).
+struct RowAgent64 {
+  static constexpr int F = 2;
+  static __device__ __forceinline__ Unit<2> load(const float *p) {
+    const uint64_t b = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return Unit<2>{{__uint_as_float(static_cast<uint32_t>(b)),
+                    __uint_as_float(static_cast<uint32_t>(b >> 32))}};
+  }
+  static __device__ __forceinline__ void store(float *p, const Unit<2> &u) {
+    const uint64_t b = static_cast<uint64_t>(__float_as_uint(u.v[0])) |
+                       (static_cast<uint64_t>(__float_as_uint(u.v[1])) << 32);
+    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), b, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  }
+};
+
 struct RowAgent32 {
   static constexpr int F = 1;
   static __device__ __forceinline__ Unit<1> load(const float *p) {
@@ -324,10 +344,13 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   }
 }
 
-// Launches sgd_kernel for a given dimension: picks the lane-group size (the smallest
-// power of two covering d/4 128-bit vectors, two vectors per lane above 64) and the
-// row policy (plain 128-bit in sequential mode, interleaved agent-scope 32-bit
-// otherwise).  `a.active_waves` is filled in here from `count`.
+// Launches sgd_kernel for a given dimension.  Geometry:
+//   sequential mode        plain 128-bit units, LPG = pow2ceil(d/4) lanes (<= 64)
+//   concurrent, d <= 64    64-bit agent-scope units, LPG = pow2ceil(d/2) lanes, one unit
+//                          per lane (2..32 sources per wavefront)
+//   concurrent, d  > 64    32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
+//                          lanes (<= 64), four or eight units per lane
+// `a.active_waves` is filled in here from `count`.
 template <class W>
 struct SgdLauncher {
   template <class P, int LPG, int UPL>
@@ -346,36 +369,42 @@ struct SgdLauncher {
     }
   }
 
-  template <int LPG, int V128>
-  static void pick_policy(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
-                          int64_t max_waves, hipStream_t st) {
-    if (seq || plain_rows) run<RowPlain128, LPG, V128>(w, a, count, seq, max_waves, st);
-    else run<RowAgent32, LPG, 4 * V128>(w, a, count, seq, max_waves, st);
+  static int pow2_lanes(int units) {
+    int lanes = 1;
+    while (lanes < units && lanes < 64) lanes *= 2;
+    return lanes;
   }
+
+  // Lane groups per wavefront in concurrent mode (to size the launch and the hot-row rule).
+  static int groups_per_wave(int32_t d) { return 64 / (d <= 64 ? pow2_lanes(d / 2) : pow2_lanes(d / 4)); }
 
   static void launch(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
                      int64_t max_waves, hipStream_t st) {
-    const int d4 = a.d / 4;
-    int lpg = 1;
-    while (lpg < d4 && lpg < 64) lpg *= 2;
-    if (d4 > 64) return pick_policy<64, 2>(w, a, count, seq, plain_rows, max_waves, st);
-    switch (lpg) {
-      case 64: return pick_policy<64, 1>(w, a, count, seq, plain_rows, max_waves, st);
-      case 32: return pick_policy<32, 1>(w, a, count, seq, plain_rows, max_waves, st);
-      case 16: return pick_policy<16, 1>(w, a, count, seq, plain_rows, max_waves, st);
-      case 8: return pick_policy<8, 1>(w, a, count, seq, plain_rows, max_waves, st);
-      case 4: return pick_policy<4, 1>(w, a, count, seq, plain_rows, max_waves, st);
-      case 2: return pick_policy<2, 1>(w, a, count, seq, plain_rows, max_waves, st);
-      default: return pick_policy<1, 1>(w, a, count, seq, plain_rows, max_waves, st);
+    const int d = a.d;
+    if (seq || plain_rows) {
+      if (d > 256) return run<RowPlain128, 64, 2>(w, a, count, seq, max_waves, st);
+      switch (pow2_lanes(d / 4)) {
+        case 64: return run<RowPlain128, 64, 1>(w, a, count, seq, max_waves, st);
+        case 32: return run<RowPlain128, 32, 1>(w, a, count, seq, max_waves, st);
+        case 16: return run<RowPlain128, 16, 1>(w, a, count, seq, max_waves, st);
+        case 8: return run<RowPlain128, 8, 1>(w, a, count, seq, max_waves, st);
+        case 4: return run<RowPlain128, 4, 1>(w, a, count, seq, max_waves, st);
+        case 2: return run<RowPlain128, 2, 1>(w, a, count, seq, max_waves, st);
+        default: return run<RowPlain128, 1, 1>(w, a, count, seq, max_waves, st);
+      }
     }
-  }
-
-  // Lane groups per wavefront for dimension d (to size the launch and the hot-row rule).
-  static int groups_per_wave(int32_t d) {
-    const int d4 = d / 4;
-    int lpg = 1;
-    while (lpg < d4 && lpg < 64) lpg *= 2;
-    return 64 / lpg;
+    if (d <= 64) {
+      switch (pow2_lanes(d / 2)) {
+        case 32: return run<RowAgent64, 32, 1>(w, a, count, seq, max_waves, st);
+        case 16: return run<RowAgent64, 16, 1>(w, a, count, seq, max_waves, st);
+        case 8: return run<RowAgent64, 8, 1>(w, a, count, seq, max_waves, st);
+        case 4: return run<RowAgent64, 4, 1>(w, a, count, seq, max_waves, st);
+        default: return run<RowAgent64, 2, 1>(w, a, count, seq, max_waves, st);
+      }
+    }
+    if (d > 256) return run<RowAgent32, 64, 8>(w, a, count, seq, max_waves, st);
+    if (d > 128) return run<RowAgent32, 64, 4>(w, a, count, seq, max_waves, st);
+    return run<RowAgent32, 32, 4>(w, a, count, seq, max_waves, st);
   }
 };
 
