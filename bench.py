@@ -71,6 +71,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     h = G.gosh_coarsen(n, xadj_h, adj_h, threshold=w.get("threshold", 100),
                        min_shrink=w.get("min_shrink", 0.8))
     t_coarsen = time.perf_counter() - t0
+    coarsen_stages = [dict(level=i, **h.times(i)) for i in range(h.levels - 1)]
     M0 = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     t0 = time.perf_counter()
     stats = G.gosh_embed(h, M0, k, args.epochs, 0.3, w["lr0"], args.seed, flags=args.flags)
@@ -94,7 +95,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
            "data": "synthetic",
            "config": {"workload": args.workload + "_levels", "desc": w["desc"], "n": n,
                       "undirected_edges": n_edges, "d": d, "k_neg": k, "total_epochs": args.epochs,
-                      "coarsen_s": t_coarsen, "embed_wall_s": t_embed, "graph_build_s": t_graph,
+                      "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
                       "levels": levels}}
     print(json.dumps(out))
     return 0

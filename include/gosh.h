@@ -112,6 +112,10 @@ int gosh_hierarchy_map(const gosh_hierarchy *h, int32_t i, const int32_t **map, 
  * conservation checkable: sum(mult_{i+1}) + (weight of entries inside clusters) =
  * sum(mult_i). */
 int gosh_hierarchy_mult(const gosh_hierarchy *h, int32_t i, const int64_t **mult, int64_t *len);
+/* Wall-clock milliseconds the three stages of Alg. 4 took when level i was coarsened
+ * (0 <= i < D-1): ms3[0] degree sort, ms3[1] marking sweep, ms3[2] rebuilding the CSR of
+ * G_{i+1} (Sec. 3.2.1 names these three stages). */
+int gosh_hierarchy_times(const gosh_hierarchy *h, int32_t i, double *ms3);
 void gosh_hierarchy_free(gosh_hierarchy *h);
 
 /* ---- device entry points ---------------------------------------------------------- */

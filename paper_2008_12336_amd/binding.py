@@ -57,6 +57,7 @@ EXPORTS = {
                                      C.POINTER(C.c_int64)]),
     "gosh_hierarchy_mult": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int64)),
                                       C.POINTER(C.c_int64)]),
+    "gosh_hierarchy_times": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_double)]),
     "gosh_hierarchy_free": (None, [C.c_void_p]),
     "gosh_init_embedding": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_uint32,
                                       C.c_void_p]),
@@ -233,6 +234,12 @@ class Hierarchy:
         _check(lib().gosh_hierarchy_map(self._h, i, C.byref(ptr), C.byref(n)))
         return np.ctypeslib.as_array(ptr, shape=(n.value,))
 
+    def times(self, i: int):
+        """{sort_ms, mark_ms, build_ms} of coarsening level i."""
+        ms = (C.c_double * 3)()
+        _check(lib().gosh_hierarchy_times(self._h, i, ms))
+        return dict(sort_ms=ms[0], mark_ms=ms[1], build_ms=ms[2])
+
     def mult(self, i: int):
         import numpy as np
 
@@ -270,6 +277,10 @@ def gosh_hierarchy_map(h: Hierarchy, i: int):
 
 def gosh_hierarchy_mult(h: Hierarchy, i: int):
     return h.mult(i)
+
+
+def gosh_hierarchy_times(h: Hierarchy, i: int):
+    return h.times(i)
 
 
 def gosh_hierarchy_free(h: Hierarchy) -> None:

@@ -1,13 +1,14 @@
 // MultiEdgeCollapse coarsening hierarchy (Alg. 4 of the paper) on the host.
 //
-// The marking sweep keeps the sequential semantics of Alg. 4 (its result depends on
-// the visiting order, and the maps have to be reproducible bit for bit), but the
-// stages around it -- degree counting sort, grouping by cluster, rebuilding the CSR
-// of the coarse graph -- are parallel with OpenMP in a way that cannot change the
-// output: every thread owns a contiguous range and writes to precomputed offsets.
+// The result is that of the sequential Alg. 4 (its maps depend on the visiting order and
+// have to be reproducible bit for bit), but every stage -- degree counting sort, marking,
+// grouping by cluster, rebuilding the CSR of the coarse graph -- runs in parallel with
+// OpenMP in a way that cannot change the output.
 #include <omp.h>
 
 #include <algorithm>
+#include <atomic>
+#include <climits>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -23,6 +24,7 @@ struct gosh_hierarchy {
     std::vector<int32_t> adj;
     std::vector<int64_t> mult;  // fine entries merged into each entry (empty at level 0)
     std::vector<int32_t> map;   // this level -> next coarser level (empty on the last)
+    double sort_ms = 0, mark_ms = 0, build_ms = 0;  // stages of coarsening THIS level
   };
   std::vector<Level> levels;
 };
@@ -83,28 +85,117 @@ void degree_order(const Csr<OffT> &g, int threads, std::vector<int32_t> &order) 
   }
 }
 
-// The marking sweep of Alg. 4.  Returns the number of clusters.
+// The marking sweep of Alg. 4, with the result of the sequential sweep but computed in
+// parallel.  Returns the number of clusters.
+//
+// In the sequential sweep a vertex becomes a hub iff it is still unmarked when its turn
+// comes, i.e. iff none of the neighbours that precede it in the order and may take it
+// (deg(u) <= delta or deg(v) <= delta) is itself a hub; a non-hub belongs to the first
+// such hub in the order.  That is a greedy independent-set recurrence over the order, and
+// it can be resolved out of order:
+//   * a vertex with deg > delta is always a hub (whoever precedes it has a degree at least
+//     as large, so the merge condition fails);
+//   * a low-degree vertex with a high-degree neighbour is never a hub;
+//   * the remaining low-degree vertices are decided in rounds: hub once every preceding
+//     neighbour is decided and none is a hub, non-hub as soon as one is.  Rounds stop when
+//     they no longer pay (long chains of equal degrees), and what is left is swept
+//     sequentially in order.
+// Cluster ids are the hubs' positions among the hubs in the order, as in Alg. 4.
 template <typename OffT>
 int64_t mark_clusters(const Csr<OffT> &g, int64_t nnz, const std::vector<int32_t> &order,
-                      std::vector<int32_t> &map) {
+                      int threads, std::vector<int32_t> &map) {
   const int64_t n = g.n;
-  map.assign(static_cast<size_t>(n), -1);
-  // deg <= |E|/|V|  <=>  deg * n <= nnz (exact, no rounding)
+  enum : uint8_t { kUndecided = 0, kHub = 1, kTaken = 2 };
+  std::vector<int32_t> rank(static_cast<size_t>(n));
   std::vector<uint8_t> low(static_cast<size_t>(n));
+  std::vector<std::atomic<uint8_t>> status(static_cast<size_t>(n));
+#pragma omp parallel for num_threads(threads) schedule(static)
+  for (int64_t t = 0; t < n; ++t) rank[static_cast<size_t>(order[static_cast<size_t>(t)])] = static_cast<int32_t>(t);
+  // deg <= |E|/|V|  <=>  deg * n <= nnz (exact, no rounding)
+#pragma omp parallel for num_threads(threads) schedule(static)
   for (int64_t v = 0; v < n; ++v) low[static_cast<size_t>(v)] = g.degree(v) * n <= nnz;
+
+  // first classification: needs no knowledge of other decisions
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 4096)
+  for (int64_t v = 0; v < n; ++v) {
+    uint8_t st = kUndecided;
+    if (!low[static_cast<size_t>(v)]) {
+      st = kHub;
+    } else {
+      bool has_predecessor = false;
+      for (OffT e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
+        const int32_t u = g.adj[e];
+        if (!low[static_cast<size_t>(u)]) { st = kTaken; break; }
+        if (rank[static_cast<size_t>(u)] < rank[static_cast<size_t>(v)]) has_predecessor = true;
+      }
+      if (st == kUndecided && !has_predecessor) st = kHub;
+    }
+    status[static_cast<size_t>(v)].store(st, std::memory_order_relaxed);
+  }
+
+  // rounds over the undecided low-degree vertices
+  std::vector<int32_t> pending;
+  for (int64_t v = 0; v < n; ++v)
+    if (status[static_cast<size_t>(v)].load(std::memory_order_relaxed) == kUndecided) pending.push_back(static_cast<int32_t>(v));
+  for (int round = 0; round < 64 && pending.size() > 4096; ++round) {
+    const int64_t before = static_cast<int64_t>(pending.size());
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1024)
+    for (int64_t i = 0; i < before; ++i) {
+      const int32_t v = pending[static_cast<size_t>(i)];
+      bool blocked = false, taken = false;
+      for (OffT e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
+        const int32_t u = g.adj[e];
+        if (rank[static_cast<size_t>(u)] >= rank[static_cast<size_t>(v)]) continue;
+        const uint8_t su = status[static_cast<size_t>(u)].load(std::memory_order_relaxed);
+        if (su == kHub) { taken = true; break; }
+        if (su == kUndecided) blocked = true;
+      }
+      // A decision, once made, is final and equals the sequential one, so reading a
+      // neighbour decided in this same round can only save a round.
+      if (taken) status[static_cast<size_t>(v)].store(kTaken, std::memory_order_relaxed);
+      else if (!blocked) status[static_cast<size_t>(v)].store(kHub, std::memory_order_relaxed);
+    }
+    std::vector<int32_t> still;
+    for (int32_t v : pending)
+      if (status[static_cast<size_t>(v)].load(std::memory_order_relaxed) == kUndecided) still.push_back(v);
+    pending.swap(still);
+    if (static_cast<int64_t>(pending.size()) * 10 > before * 9) break;  // rounds stopped paying
+  }
+  // whatever is left: the sequential sweep, in order
+  std::sort(pending.begin(), pending.end(), [&](int32_t p, int32_t q) {
+    return rank[static_cast<size_t>(p)] < rank[static_cast<size_t>(q)];
+  });
+  for (int32_t v : pending) {
+    bool taken = false;
+    for (OffT e = g.xadj[v]; e < g.xadj[v + 1] && !taken; ++e) {
+      const int32_t u = g.adj[e];
+      taken = rank[static_cast<size_t>(u)] < rank[static_cast<size_t>(v)] &&
+              status[static_cast<size_t>(u)].load(std::memory_order_relaxed) == kHub;
+    }
+    status[static_cast<size_t>(v)].store(taken ? kTaken : kHub, std::memory_order_relaxed);
+  }
+
+  // hubs are numbered in the order; every other vertex joins its first hub in the order
+  map.assign(static_cast<size_t>(n), -1);
   int32_t next_cluster = 0;
   for (int64_t t = 0; t < n; ++t) {
-    const int32_t hub = order[static_cast<size_t>(t)];
-    if (map[static_cast<size_t>(hub)] != -1) continue;
-    const int32_t cluster = next_cluster++;
-    map[static_cast<size_t>(hub)] = cluster;
-    const bool hub_low = low[static_cast<size_t>(hub)];
-    const OffT end = g.xadj[hub + 1];
-    for (OffT e = g.xadj[hub]; e < end; ++e) {
+    const int32_t v = order[static_cast<size_t>(t)];
+    if (status[static_cast<size_t>(v)].load(std::memory_order_relaxed) == kHub) map[static_cast<size_t>(v)] = next_cluster++;
+  }
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 4096)
+  for (int64_t v = 0; v < n; ++v) {
+    if (status[static_cast<size_t>(v)].load(std::memory_order_relaxed) != kTaken) continue;
+    int32_t best_rank = INT32_MAX, best = -1;
+    for (OffT e = g.xadj[v]; e < g.xadj[v + 1]; ++e) {
       const int32_t u = g.adj[e];
-      if ((hub_low || low[static_cast<size_t>(u)]) && map[static_cast<size_t>(u)] == -1)
-        map[static_cast<size_t>(u)] = cluster;
+      const int32_t ru = rank[static_cast<size_t>(u)];
+      if (ru < best_rank && ru < rank[static_cast<size_t>(v)] &&
+          status[static_cast<size_t>(u)].load(std::memory_order_relaxed) == kHub) {
+        best_rank = ru;
+        best = u;
+      }
     }
+    map[static_cast<size_t>(v)] = map[static_cast<size_t>(best)];
   }
   return next_cluster;
 }
@@ -127,57 +218,76 @@ void build_coarse(const Csr<OffT> &g, const int64_t *mult_in, const std::vector<
       members[static_cast<size_t>(cursor[static_cast<size_t>(map[static_cast<size_t>(v)])]++)] = static_cast<int32_t>(v);
   }
 
-  // Pass 1 builds each coarse row in a thread-private buffer and records its length;
-  // pass 2 (after a scan of the lengths) copies the rows to their final place.  Rows
-  // are produced by the same code in both passes, so only their order in memory, not
-  // their content, depends on the schedule.
+  // Every thread builds whole coarse rows into a private buffer (the paper's thread-private
+  // edge regions, Sec. 3.2.2) and records where each row went; a scan of the row lengths
+  // then fixes the final offsets and the rows are copied to their place.  A row's content
+  // does not depend on which thread built it, so the output is schedule-independent.
+  //
+  // Inside a row, parallel entries are merged with a per-thread stamp array over the
+  // coarse ids (stamp[b] == a  <=>  b already seen in row a), so only distinct neighbours
+  // are sorted; a row that reaches a large share of all coarse vertices is emitted by
+  // scanning the stamp array in id order instead of sorting.
   out.xadj.assign(static_cast<size_t>(n_coarse) + 1, 0);
   struct Entry {
     int32_t to;
     int64_t mult;
   };
-  auto make_row = [&](int64_t a, std::vector<Entry> &row) {
-    row.clear();
-    for (int64_t m = first[static_cast<size_t>(a)]; m < first[static_cast<size_t>(a) + 1]; ++m) {
-      const int32_t x = members[static_cast<size_t>(m)];
-      for (OffT e = g.xadj[x]; e < g.xadj[x + 1]; ++e) {
-        const int32_t b = map[static_cast<size_t>(g.adj[e])];
-        if (b != a) row.push_back(Entry{b, mult_in ? mult_in[e] : 1});
-      }
-    }
-    std::sort(row.begin(), row.end(), [](const Entry &p, const Entry &q) { return p.to < q.to; });
-    size_t w = 0;
-    for (size_t r = 0; r < row.size(); ++r) {
-      if (w > 0 && row[w - 1].to == row[r].to) row[w - 1].mult += row[r].mult;
-      else row[w++] = row[r];
-    }
-    row.resize(w);
+  struct Placed {
+    int32_t thread;
+    int64_t offset;
   };
+  std::vector<Placed> placed(static_cast<size_t>(n_coarse));
+  std::vector<std::vector<Entry>> built(static_cast<size_t>(threads));
 #pragma omp parallel num_threads(threads)
   {
+    const int tid = omp_get_thread_num();
+    std::vector<Entry> &mine = built[static_cast<size_t>(tid)];
+    std::vector<int32_t> stamp(static_cast<size_t>(n_coarse), -1);
+    std::vector<int64_t> where(static_cast<size_t>(n_coarse));
     std::vector<Entry> row;
-#pragma omp for schedule(dynamic, 256)
+    // cluster ids follow the degree order of their hubs, so the largest rows come first;
+    // small dynamic chunks keep them on different threads
+#pragma omp for schedule(dynamic, 4)
     for (int64_t a = 0; a < n_coarse; ++a) {
-      make_row(a, row);
+      row.clear();
+      for (int64_t m = first[static_cast<size_t>(a)]; m < first[static_cast<size_t>(a) + 1]; ++m) {
+        const int32_t x = members[static_cast<size_t>(m)];
+        for (OffT e = g.xadj[x]; e < g.xadj[x + 1]; ++e) {
+          const int32_t b = map[static_cast<size_t>(g.adj[e])];
+          if (b == a) continue;
+          const int64_t w = mult_in ? mult_in[e] : 1;
+          if (stamp[static_cast<size_t>(b)] != a) {
+            stamp[static_cast<size_t>(b)] = static_cast<int32_t>(a);
+            where[static_cast<size_t>(b)] = static_cast<int64_t>(row.size());
+            row.push_back(Entry{b, w});
+          } else {
+            row[static_cast<size_t>(where[static_cast<size_t>(b)])].mult += w;
+          }
+        }
+      }
+      placed[static_cast<size_t>(a)] = Placed{tid, static_cast<int64_t>(mine.size())};
       out.xadj[static_cast<size_t>(a) + 1] = static_cast<int64_t>(row.size());
+      if (static_cast<int64_t>(row.size()) * 16 > n_coarse) {
+        for (int64_t b = 0; b < n_coarse; ++b)
+          if (stamp[static_cast<size_t>(b)] == a) mine.push_back(row[static_cast<size_t>(where[static_cast<size_t>(b)])]);
+      } else {
+        std::sort(row.begin(), row.end(), [](const Entry &p, const Entry &q) { return p.to < q.to; });
+        mine.insert(mine.end(), row.begin(), row.end());
+      }
     }
   }
   for (int64_t a = 0; a < n_coarse; ++a) out.xadj[static_cast<size_t>(a) + 1] += out.xadj[static_cast<size_t>(a)];
   const int64_t nnz_coarse = out.xadj[static_cast<size_t>(n_coarse)];
   out.adj.resize(static_cast<size_t>(nnz_coarse));
   out.mult.resize(static_cast<size_t>(nnz_coarse));
-#pragma omp parallel num_threads(threads)
-  {
-    std::vector<Entry> row;
-#pragma omp for schedule(dynamic, 256)
-    for (int64_t a = 0; a < n_coarse; ++a) {
-      make_row(a, row);
-      int64_t pos = out.xadj[static_cast<size_t>(a)];
-      for (const Entry &en : row) {
-        out.adj[static_cast<size_t>(pos)] = en.to;
-        out.mult[static_cast<size_t>(pos)] = en.mult;
-        ++pos;
-      }
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 64)
+  for (int64_t a = 0; a < n_coarse; ++a) {
+    const Placed &pl = placed[static_cast<size_t>(a)];
+    const Entry *src = built[static_cast<size_t>(pl.thread)].data() + pl.offset;
+    const int64_t begin = out.xadj[static_cast<size_t>(a)], len = out.xadj[static_cast<size_t>(a) + 1] - begin;
+    for (int64_t r = 0; r < len; ++r) {
+      out.adj[static_cast<size_t>(begin + r)] = src[r].to;
+      out.mult[static_cast<size_t>(begin + r)] = src[r].mult;
     }
   }
   out.view.n = n_coarse;
@@ -193,11 +303,18 @@ int64_t coarsen_level(gosh_hierarchy &h, int threads) {
   gosh_hierarchy::Level &fine = h.levels.back();
   const Csr<OffT> g{fine.view.n, static_cast<const OffT *>(fine.view.xadj), fine.view.adj};
   std::vector<int32_t> order;
+  const double t0 = omp_get_wtime();
   degree_order(g, threads, order);
-  const int64_t n_coarse = mark_clusters(g, fine.view.nnz, order, fine.map);
+  const double t1 = omp_get_wtime();
+  const int64_t n_coarse = mark_clusters(g, fine.view.nnz, order, threads, fine.map);
+  const double t2 = omp_get_wtime();
   gosh_hierarchy::Level next;
   const int64_t *mult_in = fine.mult.empty() ? nullptr : fine.mult.data();
   build_coarse(g, mult_in, fine.map, n_coarse, threads, next);
+  const double t3 = omp_get_wtime();
+  fine.sort_ms = (t1 - t0) * 1e3;
+  fine.mark_ms = (t2 - t1) * 1e3;
+  fine.build_ms = (t3 - t2) * 1e3;
   h.levels.push_back(std::move(next));
   // the move kept the vectors' heap blocks, but re-point the view to be explicit
   gosh_hierarchy::Level &stored = h.levels.back();
@@ -289,6 +406,17 @@ int gosh_hierarchy_mult(const gosh_hierarchy *h, int32_t i, const int64_t **mult
   const auto &m = h->levels[static_cast<size_t>(i)].mult;
   *mult = m.empty() ? nullptr : m.data();
   *len = static_cast<int64_t>(m.size());
+  return GOSH_OK;
+}
+
+int gosh_hierarchy_times(const gosh_hierarchy *h, int32_t i, double *ms3) {
+  if (h == nullptr || ms3 == nullptr) return gosh::fail(GOSH_EINVAL, "null argument");
+  if (i < 0 || i + 1 >= static_cast<int32_t>(h->levels.size()))
+    return gosh::fail(GOSH_EINVAL, "level %d out of range [0, %zu)", i, h->levels.size() - 1);
+  const auto &l = h->levels[static_cast<size_t>(i)];
+  ms3[0] = l.sort_ms;
+  ms3[1] = l.mark_ms;
+  ms3[2] = l.build_ms;
   return GOSH_OK;
 }
 

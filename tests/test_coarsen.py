@@ -110,3 +110,36 @@ def test_csr_validate():
     badx = xt.clone(); badx[2] = 0
     with pytest.raises(G.GoshError):
         G.gosh_csr_validate(G.csr_view(6, badx, at))
+
+
+def _ring_lattice(n, reach):
+    """Every vertex has the same degree 2*reach: nobody is above the mean degree, so the
+    whole marking is decided by the order alone (long dependency chains)."""
+    pairs = [(i, (i + r) % n) for i in range(n) for r in range(1, reach + 1)]
+    return csr_from_pairs(n, pairs)
+
+
+@pytest.mark.parametrize("name", ["path", "ring3", "uniform", "mixed"])
+def test_marking_with_long_dependency_chains(name):
+    """Graphs on which the out-of-order marking needs many rounds or falls back to the
+    in-order sweep must still give the sequential result."""
+    if name == "path":
+        n = 30000
+        xadj, adj = csr_from_pairs(n, [(i, i + 1) for i in range(n - 1)])
+    elif name == "ring3":
+        n = 20000
+        xadj, adj = _ring_lattice(n, 3)
+    elif name == "uniform":
+        n = 60000
+        c = graphgen.to_csr(n, graphgen.er_gnm(n, 4 * n, 11))
+        xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    else:
+        n = 50000
+        path = [(i, i + 1) for i in range(30000)]
+        c = graphgen.chung_lu(n, 120000, 12)
+        xadj, adj = csr_from_pairs(n, path + [tuple(e) for e in c.tolist()])
+    for threads in (1, 6):
+        graphs, maps, mults = O.coarsen(xadj, adj, threshold=n // 2, min_shrink=1.0, max_levels=2)
+        h = product_hierarchy(n, xadj, adj, False, threshold=n // 2, min_shrink=1.0, max_levels=2,
+                              n_threads=threads)
+        assert_same_hierarchy(h, graphs, maps, mults)
