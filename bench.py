@@ -32,6 +32,13 @@ WORKLOADS = {
                  threshold=10000, min_shrink=0.8,
                  desc="R-MAT, 2^22 vertices, 2^26 undirected edge draws, d=128 fp32, k=3, "
                       "hierarchy to |V| < 10,000 or shrink below 20 %"),
+    # BASELINE config 5: the paper's largest workload shape, trained with the part-pair
+    # rotation under an 8 GB device budget (use --mode parts).
+    "cfg5": dict(gen="chung_lu", n=65_000_000, m=1_800_000_000, d=128, k=3, lr0=0.035,
+                 offsets64=True, budget=8 << 30,
+                 desc="Chung-Lu power law (exponent 2.1), 6.5e7 vertices, 1.8e9 undirected edge "
+                      "draws, int64 offsets, d=128 fp32 (33 GB matrix on the host), k=3, "
+                      "8 GB device budget"),
     # BASELINE config 2 (matrix 512 MB: partly cache resident).
     "cfg2": dict(gen="rmat", log2n=20, log2m=24, d=128, k=3, lr0=0.045, offsets64=False,
                  desc="R-MAT (0.57,0.19,0.19,0.05), 2^20 vertices, 2^24 undirected edge draws, "
@@ -110,13 +117,19 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     d, k, B = w["d"], w["k"], 5
     xadj_h, adj_h = csr.xadj.cpu(), csr.adj.cpu()
     del csr
+    torch.cuda.empty_cache()
     M_dev = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     G.gosh_init_embedding(M_dev, args.seed, 0)
     M_host = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
     M_host.copy_(M_dev)
     del M_dev
     torch.cuda.empty_cache()
-    budget = int(n * d * 4 / args.budget_ratio)
+    print("[bench] matrix on the pinned host", file=sys.stderr, flush=True)
+    if "budget" in w and args.log2n is None:
+        budget = int(w["budget"])
+    else:
+        budget = int(n * d * 4 / args.budget_ratio)
+    print(f"[bench] parts: n={n} budget={budget}", file=sys.stderr, flush=True)
     plan = G.gosh_parts_plan(n, d, 1, budget, 3, 4, B)
     epochs = B * plan["K"]  # exactly one rotation
     st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, epochs, w["lr0"], args.seed,
@@ -185,7 +198,9 @@ def main() -> int:
         if getattr(args, key) is not None:
             w[key] = getattr(args, key)
             scaled = True
-    n, m, d, k = 1 << w["log2n"], 1 << w["log2m"], w["d"], w["k"]
+    n = w["n"] if "n" in w and args.log2n is None else 1 << w["log2n"]
+    m = w["m"] if "m" in w and args.log2m is None else 1 << w["log2m"]
+    d, k = w["d"], w["k"]
     dev = "cuda:0"
 
     t0 = time.time()
@@ -193,6 +208,7 @@ def main() -> int:
         edges = graphgen.chung_lu(n, m, args.seed, gamma=2.1, device=dev)
     else:
         edges = graphgen.rmat(w["log2n"], m, args.seed, device=dev)
+    print(f"[bench] graph generated: {int(edges.shape[0])} edges", file=sys.stderr, flush=True)
     csr = graphgen.to_csr(n, edges, offsets64=w["offsets64"])
     n_edges = int(edges.shape[0])
     del edges

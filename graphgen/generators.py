@@ -176,18 +176,35 @@ def holdout_split(edges: torch.Tensor, frac: float, seed: int):
 
 
 def to_csr(n: int, edges: torch.Tensor, offsets64: bool = False) -> CSR:
-    """Symmetrise an undirected edge list (each edge once) into sorted CSR."""
-    u = torch.cat((edges[:, 0], edges[:, 1]))
-    v = torch.cat((edges[:, 1], edges[:, 0]))
-    key = torch.sort(u * n + v).values
-    del u, v
-    rows = key // n
-    adj = (key % n).to(torch.int32)
+    """Symmetrise an undirected edge list (each edge once as (u, v), u < v, sorted by
+    (u, v)) into sorted CSR.
+
+    The row of a vertex r is its smaller neighbours (pairs in which r is the larger
+    endpoint) followed by its larger neighbours (pairs in which r is the smaller one);
+    both runs are ascending, so only the reversed pairs need a sort."""
+    dev = edges.device
+    m = edges.shape[0]
+    u, v = edges[:, 0], edges[:, 1]
+    cnt_hi = torch.bincount(u, minlength=n)  # larger neighbours of each vertex
+    cnt_lo = torch.bincount(v, minlength=n)  # smaller neighbours of each vertex
+    xadj = torch.zeros(n + 1, dtype=torch.int64, device=dev)
+    torch.cumsum(cnt_lo + cnt_hi, 0, out=xadj[1:])
+    adj = torch.empty(2 * m, dtype=torch.int32, device=dev)
+    ar = torch.arange(m, dtype=torch.int64, device=dev)
+    # forward pairs are already grouped by u with v ascending
+    start_hi = torch.cumsum(cnt_hi, 0) - cnt_hi
+    pos = xadj[:-1][u] + cnt_lo[u] + (ar - start_hi[u])
+    adj[pos] = v.to(torch.int32)
+    del pos, start_hi, cnt_hi
+    # reversed pairs: sort by (v, u)
+    key = torch.sort(v * n + u).values
+    vs = key // n
+    us = (key - vs * n).to(torch.int32)
     del key
-    counts = torch.bincount(rows, minlength=n)
-    del rows
-    xadj = torch.zeros(n + 1, dtype=torch.int64, device=edges.device)
-    torch.cumsum(counts, 0, out=xadj[1:])
+    start_lo = torch.cumsum(cnt_lo, 0) - cnt_lo
+    pos = xadj[:-1][vs] + (ar - start_lo[vs])
+    adj[pos] = us
+    del pos, vs, us, ar, start_lo, cnt_lo
     if not offsets64:
         assert int(xadj[-1]) < 2 ** 31
         xadj = xadj.to(torch.int32)
