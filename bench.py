@@ -130,17 +130,18 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     else:
         budget = int(n * d * 4 / args.budget_ratio)
     print(f"[bench] parts: n={n} budget={budget}", file=sys.stderr, flush=True)
-    plan = G.gosh_parts_plan(n, d, 1, budget, 3, 4, B)
+    plan = G.gosh_parts_plan(n, d, 1, budget, args.p_gpu, args.s_gpu, B)
     epochs = B * plan["K"]  # exactly one rotation
     st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, epochs, w["lr0"], args.seed,
-                            device_budget_bytes=budget, P_gpu=3, S_gpu=4, B=B, flags=args.flags)
+                            device_budget_bytes=budget, P_gpu=args.p_gpu, S_gpu=args.s_gpu, B=B,
+                            flags=args.flags)
     out = {"metric": "training samples/sec and achieved HBM GB/s (% of peak) at d=128, 1 GPU",
            "value": st["updates"] / (st["wall_ms"] / 1e3), "unit": "samples/s", "n_gpus": 1,
            "steps": 1, "warmup": 0, "ms_per_step": st["wall_ms"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": args.workload + "_parts", "desc": w["desc"], "n": n,
-                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B,
-                      "device_budget_bytes": budget, "matrix_bytes": n * d * 4,
+                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "P_gpu": args.p_gpu,
+                      "S_gpu": args.s_gpu, "device_budget_bytes": budget, "matrix_bytes": n * d * 4,
                       "graph_build_s": t_graph, "finite": bool(torch.isfinite(M_host[::4097]).all()),
                       **st,
                       "kernel_only_samples_per_s": st["updates"] / (st["kernel_ms"] / 1e3),
@@ -165,6 +166,8 @@ def main() -> int:
                          "coarsening + multilevel training with per-level rates; parts: one "
                          "rotation of the part-pair scheme under a device budget")
     ap.add_argument("--epochs", type=int, default=40, help="total epochs of --mode levels")
+    ap.add_argument("--p-gpu", type=int, default=3, help="--mode parts: device slots for parts")
+    ap.add_argument("--s-gpu", type=int, default=4, help="--mode parts: device sample pools")
     ap.add_argument("--budget-ratio", type=float, default=4.2,
                     help="--mode parts: matrix bytes / device budget")
     ap.add_argument("--flags", type=int, default=0,

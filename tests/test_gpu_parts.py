@@ -51,6 +51,8 @@ def budget_for(n, d, K, P, S, B):
     (900, 64, 5, 3, 2, 3, 2, 45),
     (700, 100, 6, 4, 3, 1, 5, 12),
     (9, 8, 4, 3, 2, 2, 3, 16),  # ceil(9/4) = 3 rows per part: the fourth part is empty
+    (1200, 32, 9, 4, 4, 2, 3, 40),  # four slots: eager write-back and two-visit lookahead
+    (1200, 32, 9, 6, 2, 2, 3, 40),
 ])
 def test_sequential_rotation_matches_oracle(n, d, K, P, S, B, k, epochs):
     say(f"[parts-seq] n={n} d={d} K={K} P={P} S={S} B={B} k={k} epochs={epochs}")
