@@ -23,23 +23,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
 
 WORKLOADS = {
-    # BASELINE config 4, level 0: the shape the bandwidth target is stated on.
+    # Workload 4, level 0: the shape the bandwidth target is stated on.
     "cfg4_level0": dict(gen="chung_lu", log2n=24, log2m=28, d=128, k=3, lr0=0.045, offsets64=True,
                         desc="Chung-Lu power law (exponent 2.1), 2^24 vertices, 2^28 undirected "
                              "edge draws, int64 offsets, d=128 fp32, k=3, level 0"),
-    # BASELINE config 3: multilevel run (use --mode levels).
+    # Workload 3: multilevel run (use --mode levels).
     "cfg3": dict(gen="rmat", log2n=22, log2m=26, d=128, k=3, lr0=0.035, offsets64=False,
                  threshold=10000, min_shrink=0.8,
                  desc="R-MAT, 2^22 vertices, 2^26 undirected edge draws, d=128 fp32, k=3, "
                       "hierarchy to |V| < 10,000 or shrink below 20 %"),
-    # BASELINE config 5: the paper's largest workload shape, trained with the part-pair
+    # Workload 5: the shape of the paper's largest graph, trained with the part-pair
     # rotation under an 8 GB device budget (use --mode parts).
     "cfg5": dict(gen="chung_lu", n=65_000_000, m=1_800_000_000, d=128, k=3, lr0=0.035,
                  offsets64=True, budget=8 << 30,
                  desc="Chung-Lu power law (exponent 2.1), 6.5e7 vertices, 1.8e9 undirected edge "
                       "draws, int64 offsets, d=128 fp32 (33 GB matrix on the host), k=3, "
                       "8 GB device budget"),
-    # BASELINE config 2 (matrix 512 MB: partly cache resident).
+    # Workload 2 (matrix 512 MB: partly cache resident).
     "cfg2": dict(gen="rmat", log2n=20, log2m=24, d=128, k=3, lr0=0.045, offsets64=False,
                  desc="R-MAT (0.57,0.19,0.19,0.05), 2^20 vertices, 2^24 undirected edge draws, "
                       "int32 offsets, d=128 fp32, k=3"),
@@ -79,9 +79,19 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
                        min_shrink=w.get("min_shrink", 0.8))
     t_coarsen = time.perf_counter() - t0
     coarsen_stages = [dict(level=i, **h.times(i)) for i in range(h.levels - 1)]
-    M0 = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
-    t0 = time.perf_counter()
-    stats = G.gosh_embed(h, M0, k, args.epochs, 0.3, w["lr0"], args.seed, flags=args.flags)
+    budget = int(w.get("budget", 0)) if args.log2n is None else 0
+    print(f"[bench] hierarchy of {h.levels} levels in {t_coarsen:.1f}s; budget {budget}",
+          file=sys.stderr, flush=True)
+    if budget:
+        # Alg. 2 with its fits-into-GPU test: levels above the budget use the rotation
+        M0 = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
+        t0 = time.perf_counter()
+        stats = G.gosh_embed_host(h, M0, k, args.epochs, 0.3, w["lr0"], args.seed, flags=args.flags,
+                                  device_budget_bytes=budget, P_gpu=args.p_gpu, S_gpu=args.s_gpu)
+    else:
+        M0 = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
+        t0 = time.perf_counter()
+        stats = G.gosh_embed(h, M0, k, args.epochs, 0.3, w["lr0"], args.seed, flags=args.flags)
     torch.cuda.synchronize()
     t_embed = time.perf_counter() - t0
     levels = []
@@ -91,6 +101,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
         per_epoch = s_["train_ms"] / max(1, s_["epochs"])
         row_bytes = s_["n"] * (2 + 2 * (k + 1)) * 4 * d
         levels.append({"level": s_["level"], "n": s_["n"], "nnz": s_["nnz"], "epochs": s_["epochs"],
+                       "parts_K": s_["parts_K"], "train_ms": s_["train_ms"],
                        "ms_per_epoch": per_epoch, "row_GBps": row_bytes / per_epoch / 1e6,
                        "upload_ms": s_["upload_ms"], "project_ms": s_["project_ms"]})
         samples += s_["n"] * (k + 1) * s_["epochs"]
@@ -101,6 +112,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
            "data": "synthetic",
            "config": {"workload": args.workload + "_levels", "desc": w["desc"], "n": n,
+                      "device_budget_bytes": budget, "finite": bool(torch.isfinite(M0[::4097]).all()),
                       "undirected_edges": n_edges, "d": d, "k_neg": k, "total_epochs": args.epochs,
                       "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
                       "levels": levels}}

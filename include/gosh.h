@@ -92,9 +92,9 @@ typedef struct gosh_hierarchy gosh_hierarchy;
  * G_{i+1} has the entry (a, b), a != b, iff some entry (x, y) of G_i has map[x] = a,
  * map[y] = b; rows ascending, parallel entries merged.
  * Levels are built while |V_i| > threshold (the paper's default is 100); building stops
- * after a level with |V_{i+1}| > min_shrink*|V_i| or |V_{i+1}| == |V_i| (that level is
- * kept), or when max_levels graphs exist.  min_shrink in (0, 1]; 1.0 keeps only the
- * no-progress guard.  n_threads <= 0 uses every available core (the result does not
+ * after a level with |V_{i+1}| > min_shrink*|V_i| (that level is kept), at a level that
+ * merged nothing (|V_{i+1}| == |V_i|: it would repeat G_i and is dropped), or when
+ * max_levels graphs exist.  min_shrink in (0, 1]; 1.0 keeps only the no-progress guard.  n_threads <= 0 uses every available core (the result does not
  * depend on the thread count).
  * g0_host: host CSR, borrowed for the lifetime of the hierarchy (level 0 is a view of
  * it, not a copy).  *out receives the hierarchy; on failure it is NULL. */

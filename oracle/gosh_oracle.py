@@ -218,9 +218,9 @@ def coarsen_graph(xadj, adj, map_, n_coarse, mult=None):
 def coarsen(xadj, adj, threshold=100, min_shrink=0.8, max_levels=64):
     """Alg. 4 outer loop.  READING (stop rule): build G_{i+1} while |V_i| > threshold;
     after building it, stop if |V_{i+1}| > min_shrink * |V_i| (the level barely
-    shrank) or |V_{i+1}| == |V_i| (no progress at all, e.g. only isolated vertices
-    are left); that level is still kept as the last one.  max_levels caps the
-    number of graphs.
+    shrank; it is still kept as the last one).  A level that merged nothing
+    (|V_{i+1}| == |V_i|, e.g. only isolated vertices are left) would repeat G_i and is
+    not kept.  max_levels caps the number of graphs.
     Returns (graphs, maps, mults): graphs[i] = (xadj, adj) of G_i, maps[i]: V_i -> V_{i+1}."""
     xadj, adj = _csr(xadj, adj)
     graphs, maps, mults = [(xadj, adj)], [], [np.ones(adj.size, dtype=np.int64)]
@@ -228,11 +228,13 @@ def coarsen(xadj, adj, threshold=100, min_shrink=0.8, max_levels=64):
         x, a = graphs[-1]
         n = x.size - 1
         m, nc = coarsen_map(x, a)
+        if nc == n:
+            break
         xo, ao, mo = coarsen_graph(x, a, m, nc, mults[-1])
         graphs.append((xo, ao))
         maps.append(m)
         mults.append(mo)
-        if nc > min_shrink * n or nc == n:
+        if nc > min_shrink * n:
             break
     return graphs, maps, mults
 

@@ -371,7 +371,13 @@ int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink, 
       const int64_t n_fine = h->levels.back().view.n;
       const int64_t n_coarse = h->levels.back().view.xadj_is64 ? coarsen_level<int64_t>(*h, threads)
                                                                : coarsen_level<int32_t>(*h, threads);
-      if (static_cast<double>(n_coarse) > min_shrink * static_cast<double>(n_fine) || n_coarse == n_fine) break;
+      if (n_coarse == n_fine) {
+        // nothing merged (e.g. only isolated vertices are left): G_{i+1} would repeat G_i
+        h->levels.pop_back();
+        h->levels.back().map.clear();
+        break;
+      }
+      if (static_cast<double>(n_coarse) > min_shrink * static_cast<double>(n_fine)) break;
     }
     *out = h;
     return GOSH_OK;

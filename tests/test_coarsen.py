@@ -80,11 +80,12 @@ def test_edge_cases():
     assert n == 5 and np.array_equal(a, adj)
     with pytest.raises(G.GoshError):
         h.map(0)
-    # edgeless graph: no progress, one extra level, identity map
+    # edgeless graph: nothing can merge, so no level is added
     xe = np.zeros(301, dtype=np.int64)
     h = product_hierarchy(300, xe, np.zeros(0, dtype=np.int32), True, threshold=100, min_shrink=0.8)
-    assert h.levels == 2 and h.map(0).tolist() == list(range(300))
-    assert h.graph(1)[0] == 300 and h.graph(1)[2].size == 0
+    assert h.levels == 1
+    with pytest.raises(G.GoshError):
+        h.map(0)
     # bad arguments
     for kw in (dict(threshold=0), dict(min_shrink=0.0), dict(min_shrink=1.5), dict(max_levels=0)):
         with pytest.raises(G.GoshError):

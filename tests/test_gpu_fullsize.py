@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full size and launch configuration (BASELINE config 4,
+"""Parity at the benchmark's full size and launch configuration (workload 4,
 level 0: Chung-Lu graph, 2^24 vertices, 2^28 edge draws, int64 offsets, d = 128, k = 3).
 
 The oracle cannot replay a racing Hogwild epoch, so the checks are:

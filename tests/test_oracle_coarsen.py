@@ -109,10 +109,11 @@ def test_hierarchy_stop_rules_and_weight_conservation():
     sizes = [g[0].size - 1 for g in graphs]
     assert len(maps) == len(graphs) - 1 and len(graphs) >= 3
     # sizes fall strictly until either the threshold is passed or nothing merges any
-    # more (isolated vertices can never merge); that last level is kept and ends the loop
-    assert all(a > b for a, b in zip(sizes[:-1], sizes[1:-1]))
-    assert sizes[-1] <= 100 or sizes[-1] == sizes[-2]
+    # more (isolated vertices can never merge; a level that would repeat the last is dropped)
+    assert all(a > b for a, b in zip(sizes, sizes[1:]))
     assert sizes[-2] > 100  # the loop only builds from graphs above the threshold
+    if sizes[-1] > 100:
+        assert O.coarsen_map(*graphs[-1])[1] == sizes[-1]  # stopped because nothing merges
     tight, _, _ = O.coarsen(xadj, adj, threshold=100, min_shrink=0.8)
     tsz = [g[0].size - 1 for g in tight]
     assert tsz == sizes[:len(tsz)] and tsz[-1] > 0.8 * tsz[-2]
@@ -126,7 +127,7 @@ def test_hierarchy_stop_rules_and_weight_conservation():
     # a graph that cannot shrink (no edges) still terminates
     xe = np.zeros(301, dtype=np.int64)
     g2, m2, _ = O.coarsen(xe, np.zeros(0, dtype=np.int32), threshold=100, min_shrink=0.8)
-    assert len(g2) == 2 and m2[0].tolist() == list(range(300))
+    assert len(g2) == 1 and m2 == []
     # max_levels is a hard cap
     g3, _, _ = O.coarsen(xadj, adj, threshold=1, min_shrink=1.0, max_levels=2)
     assert len(g3) == 2
