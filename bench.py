@@ -65,7 +65,7 @@ def read_traffic(workload: str):
 
 
 def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
-    """Coarsening (host, timed separately) + Alg. 2 over all levels, per-level rates."""
+    """Coarsening (timed separately) + Alg. 2 over all levels, per-level rates."""
     import torch
 
     import paper_2008_12336_amd as G
@@ -75,8 +75,9 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     del csr
     torch.cuda.empty_cache()
     t0 = time.perf_counter()
-    h = G.gosh_coarsen(n, xadj_h, adj_h, threshold=w.get("threshold", 100),
-                       min_shrink=w.get("min_shrink", 0.8))
+    coarsen = G.gosh_coarsen_device if args.coarsen == "device" else G.gosh_coarsen
+    h = coarsen(n, xadj_h, adj_h, threshold=w.get("threshold", 100),
+                min_shrink=w.get("min_shrink", 0.8))
     t_coarsen = time.perf_counter() - t0
     coarsen_stages = [dict(level=i, **h.times(i)) for i in range(h.levels - 1)]
     budget = int(w.get("budget", 0)) if args.log2n is None else 0
@@ -114,7 +115,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
            "config": {"workload": args.workload + "_levels", "desc": w["desc"], "n": n,
                       "device_budget_bytes": budget, "finite": bool(torch.isfinite(M0[::4097]).all()),
                       "undirected_edges": n_edges, "d": d, "k_neg": k, "total_epochs": args.epochs,
-                      "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
+                      "coarsen": args.coarsen, "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
                       "levels": levels}}
     print(json.dumps(out))
     return 0
@@ -177,6 +178,8 @@ def main() -> int:
                     help="epoch: the epoch kernel on one graph (the headline number); levels: "
                          "coarsening + multilevel training with per-level rates; parts: one "
                          "rotation of the part-pair scheme under a device budget")
+    ap.add_argument("--coarsen", default="device", choices=["device", "host"],
+                    help="--mode levels: where the coarse graphs are rebuilt")
     ap.add_argument("--epochs", type=int, default=40, help="total epochs of --mode levels")
     ap.add_argument("--p-gpu", type=int, default=3, help="--mode parts: device slots for parts")
     ap.add_argument("--s-gpu", type=int, default=4, help="--mode parts: device sample pools")

@@ -101,6 +101,14 @@ typedef struct gosh_hierarchy gosh_hierarchy;
 int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
                  int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
 
+/* The same hierarchy, bit for bit, with the "Coarsen" step of every level (the rebuild of
+ * the CSR of G_{i+1}, Sec. 3.2.1) done on the current HIP device: a radix sort and a
+ * reduction of (cluster, cluster) keys.  Sorting and marking stay on the host.  The
+ * device needs about 40 bytes per entry of the largest level; GOSH_ENOMEM / GOSH_EHIP if
+ * it cannot.  Blocking. */
+int gosh_coarsen_device(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
+                        int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
+
 /* D, the number of graphs G_0..G_{D-1} (0 for NULL). */
 int gosh_hierarchy_levels(const gosh_hierarchy *h);
 /* Borrowed host view of G_i (coarse levels have 64-bit offsets). */

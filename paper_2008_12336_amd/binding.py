@@ -51,6 +51,8 @@ EXPORTS = {
     "gosh_csr_validate": (C.c_int, [C.POINTER(gosh_csr)]),
     "gosh_coarsen": (C.c_int, [C.POINTER(gosh_csr), C.c_int64, C.c_double, C.c_int32, C.c_int32,
                                C.POINTER(C.c_void_p)]),
+    "gosh_coarsen_device": (C.c_int, [C.POINTER(gosh_csr), C.c_int64, C.c_double, C.c_int32,
+                                      C.c_int32, C.POINTER(C.c_void_p)]),
     "gosh_hierarchy_levels": (C.c_int, [C.c_void_p]),
     "gosh_hierarchy_graph": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(gosh_csr)]),
     "gosh_hierarchy_map": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
@@ -251,16 +253,27 @@ class Hierarchy:
         return np.ctypeslib.as_array(ptr, shape=(n.value,))
 
 
+def _coarsen(fn, n, xadj, adj, threshold, min_shrink, max_levels, n_threads) -> Hierarchy:
+    if xadj.is_cuda or adj.is_cuda:
+        raise TypeError("coarsening takes host (CPU) tensors")
+    g = csr_view(n, xadj, adj)
+    out = C.c_void_p()
+    _check(fn(C.byref(g), threshold, min_shrink, max_levels, n_threads, C.byref(out)))
+    return Hierarchy(out, (xadj, adj))
+
+
 def gosh_coarsen(n: int, xadj: torch.Tensor, adj: torch.Tensor, threshold: int = 100,
                  min_shrink: float = 1.0, max_levels: int = 64, n_threads: int = 0) -> Hierarchy:
     """Coarsen a HOST graph (CPU tensors).  The tensors are kept alive by the result."""
-    if xadj.is_cuda or adj.is_cuda:
-        raise TypeError("gosh_coarsen takes host (CPU) tensors")
-    g = csr_view(n, xadj, adj)
-    out = C.c_void_p()
-    _check(lib().gosh_coarsen(C.byref(g), threshold, min_shrink, max_levels, n_threads,
-                              C.byref(out)))
-    return Hierarchy(out, (xadj, adj))
+    return _coarsen(lib().gosh_coarsen, n, xadj, adj, threshold, min_shrink, max_levels, n_threads)
+
+
+def gosh_coarsen_device(n: int, xadj: torch.Tensor, adj: torch.Tensor, threshold: int = 100,
+                        min_shrink: float = 1.0, max_levels: int = 64,
+                        n_threads: int = 0) -> Hierarchy:
+    """Same hierarchy, with the CSR rebuild of every level done on the current device."""
+    return _coarsen(lib().gosh_coarsen_device, n, xadj, adj, threshold, min_shrink, max_levels,
+                    n_threads)
 
 
 def gosh_hierarchy_levels(h: Hierarchy) -> int:

@@ -14,15 +14,16 @@
 #include <numeric>
 #include <vector>
 
+#include "gosh_coarsen_internal.h"
 #include "gosh_common.h"
 
 struct gosh_hierarchy {
   struct Level {
     // Level 0 borrows the caller's arrays; coarser levels own theirs (64-bit offsets).
     gosh_csr view{};
-    std::vector<int64_t> xadj;
-    std::vector<int32_t> adj;
-    std::vector<int64_t> mult;  // fine entries merged into each entry (empty at level 0)
+    gosh::RawVector<int64_t> xadj;
+    gosh::RawVector<int32_t> adj;
+    gosh::RawVector<int64_t> mult;  // fine entries merged into each entry (empty at level 0)
     std::vector<int32_t> map;   // this level -> next coarser level (empty on the last)
     double sort_ms = 0, mark_ms = 0, build_ms = 0;  // stages of coarsening THIS level
   };
@@ -278,6 +279,8 @@ void build_coarse(const Csr<OffT> &g, const int64_t *mult_in, const std::vector<
   }
   for (int64_t a = 0; a < n_coarse; ++a) out.xadj[static_cast<size_t>(a) + 1] += out.xadj[static_cast<size_t>(a)];
   const int64_t nnz_coarse = out.xadj[static_cast<size_t>(n_coarse)];
+  // left uninitialised: the loop below writes every element, faulting the pages in from
+  // all threads
   out.adj.resize(static_cast<size_t>(nnz_coarse));
   out.mult.resize(static_cast<size_t>(nnz_coarse));
 #pragma omp parallel for num_threads(threads) schedule(dynamic, 64)
@@ -297,9 +300,10 @@ void build_coarse(const Csr<OffT> &g, const int64_t *mult_in, const std::vector<
   out.view.xadj_is64 = 1;
 }
 
-// One level: map of `fine` and the next level appended to h.  Returns |V_{i+1}|.
+// One level: map of `fine` and the next level appended to h.  Returns |V_{i+1}|, or a
+// negative status if the device rebuild failed.
 template <typename OffT>
-int64_t coarsen_level(gosh_hierarchy &h, int threads) {
+int64_t coarsen_level(gosh_hierarchy &h, int threads, gosh::DeviceCarry *carry) {
   gosh_hierarchy::Level &fine = h.levels.back();
   const Csr<OffT> g{fine.view.n, static_cast<const OffT *>(fine.view.xadj), fine.view.adj};
   std::vector<int32_t> order;
@@ -310,13 +314,22 @@ int64_t coarsen_level(gosh_hierarchy &h, int threads) {
   const double t2 = omp_get_wtime();
   gosh_hierarchy::Level next;
   const int64_t *mult_in = fine.mult.empty() ? nullptr : fine.mult.data();
-  build_coarse(g, mult_in, fine.map, n_coarse, threads, next);
+  if (carry != nullptr) {
+    if (int rc = gosh::build_coarse_on_device(fine.view, mult_in, fine.map.data(), n_coarse, threads, carry,
+                                              next.xadj, next.adj, next.mult))
+      return rc;
+    next.view.n = n_coarse;
+    next.view.nnz = static_cast<int64_t>(next.adj.size());
+    next.view.xadj_is64 = 1;
+  } else {
+    build_coarse(g, mult_in, fine.map, n_coarse, threads, next);
+  }
   const double t3 = omp_get_wtime();
   fine.sort_ms = (t1 - t0) * 1e3;
   fine.mark_ms = (t2 - t1) * 1e3;
   fine.build_ms = (t3 - t2) * 1e3;
   h.levels.push_back(std::move(next));
-  // the move kept the vectors' heap blocks, but re-point the view to be explicit
+  // the move kept the vectors' heap blocks; point the view at them
   gosh_hierarchy::Level &stored = h.levels.back();
   stored.view.xadj = stored.xadj.data();
   stored.view.adj = stored.adj.data();
@@ -351,8 +364,9 @@ int gosh_csr_validate(const gosh_csr *g_host) {
   return g_host->xadj_is64 ? validate<int64_t>(g_host) : validate<int32_t>(g_host);
 }
 
-int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink, int32_t max_levels,
-                 int32_t n_threads, gosh_hierarchy **out) {
+static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
+                        int32_t max_levels, int32_t n_threads, bool rebuild_on_device,
+                        gosh_hierarchy **out) {
   if (out == nullptr) return gosh::fail(GOSH_EINVAL, "out is null");
   *out = nullptr;
   if (int rc = gosh::check_csr(g0_host)) return rc;
@@ -362,15 +376,26 @@ int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink, 
   if (max_levels < 1) return gosh::fail(GOSH_EINVAL, "max_levels = %d: must be >= 1", max_levels);
   int threads = n_threads > 0 ? n_threads : omp_get_max_threads();
   if (threads < 1) threads = 1;
+  gosh_hierarchy *h = nullptr;
+  struct CarryOwner {
+    gosh::DeviceCarry *p = nullptr;
+    ~CarryOwner() { gosh::device_carry_free(p); }
+  } carry;
   try {
-    gosh_hierarchy *h = new gosh_hierarchy();
+    if (rebuild_on_device) carry.p = gosh::device_carry_new();
+    h = new gosh_hierarchy();
     h->levels.reserve(static_cast<size_t>(std::min<int32_t>(max_levels, 64)));
     h->levels.emplace_back();
     h->levels[0].view = *g0_host;
     while (h->levels.back().view.n > threshold && static_cast<int32_t>(h->levels.size()) < max_levels) {
       const int64_t n_fine = h->levels.back().view.n;
-      const int64_t n_coarse = h->levels.back().view.xadj_is64 ? coarsen_level<int64_t>(*h, threads)
-                                                               : coarsen_level<int32_t>(*h, threads);
+      const int64_t n_coarse = h->levels.back().view.xadj_is64
+                                   ? coarsen_level<int64_t>(*h, threads, carry.p)
+                                   : coarsen_level<int32_t>(*h, threads, carry.p);
+      if (n_coarse < 0) {  // status of a failed device rebuild
+        delete h;
+        return static_cast<int>(n_coarse);
+      }
       if (n_coarse == n_fine) {
         // nothing merged (e.g. only isolated vertices are left): G_{i+1} would repeat G_i
         h->levels.pop_back();
@@ -382,8 +407,19 @@ int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink, 
     *out = h;
     return GOSH_OK;
   } catch (const std::bad_alloc &) {
+    delete h;
     return gosh::fail(GOSH_ENOMEM, "out of host memory while coarsening");
   }
+}
+
+int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink, int32_t max_levels,
+                 int32_t n_threads, gosh_hierarchy **out) {
+  return coarsen_impl(g0_host, threshold, min_shrink, max_levels, n_threads, false, out);
+}
+
+int gosh_coarsen_device(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
+                        int32_t max_levels, int32_t n_threads, gosh_hierarchy **out) {
+  return coarsen_impl(g0_host, threshold, min_shrink, max_levels, n_threads, true, out);
 }
 
 int gosh_hierarchy_levels(const gosh_hierarchy *h) { return h ? static_cast<int>(h->levels.size()) : 0; }
