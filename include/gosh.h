@@ -101,13 +101,25 @@ typedef struct gosh_hierarchy gosh_hierarchy;
 int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
                  int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
 
-/* The same hierarchy, bit for bit, with the "Coarsen" step of every level (the rebuild of
- * the CSR of G_{i+1}, Sec. 3.2.1) done on the current HIP device: a radix sort and a
- * reduction of (cluster, cluster) keys.  Sorting and marking stay on the host.  The
- * device needs about 40 bytes per entry of the largest level; GOSH_ENOMEM / GOSH_EHIP if
- * it cannot.  Blocking. */
+/* MultiEdgeCollapse on the current HIP device: the same hierarchy, bit for bit (Alg. 4 has
+ * one result), with the degree order a device radix sort, the marking sweep resolved in
+ * parallel rounds, and "Coarsen" (the rebuild of the CSR of G_{i+1}, Sec. 3.2.1) a sort
+ * and a reduction of (cluster, cluster) keys.  g0_host is uploaded once (offsets and
+ * neighbour ids are range-checked on the device: GOSH_EINVAL); every level then STAYS on
+ * that device, where gosh_embed / gosh_embed_host read it without another upload, and the
+ * host arrays behind gosh_hierarchy_graph / _map / _mult are downloaded on first request.
+ * A graph whose marking does not resolve in a bounded number of rounds (long chains of
+ * equal degrees) is marked on the host instead.  Device memory: about 36 bytes per entry
+ * of G_0 while running, 12 bytes per entry of all levels afterwards (until
+ * gosh_hierarchy_release_device or gosh_hierarchy_free, called with the same device
+ * current).  GOSH_ENOMEM / GOSH_EHIP if the device cannot.  Blocking; null stream. */
 int gosh_coarsen_device(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
                         int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
+
+/* Brings every array of a device-built hierarchy to the host and frees its device copies
+ * (no-op for a host-built one).  Accessors and training keep working, from the host
+ * copies.  Blocking. */
+int gosh_hierarchy_release_device(gosh_hierarchy *h);
 
 /* D, the number of graphs G_0..G_{D-1} (0 for NULL). */
 int gosh_hierarchy_levels(const gosh_hierarchy *h);

@@ -53,6 +53,7 @@ EXPORTS = {
                                C.POINTER(C.c_void_p)]),
     "gosh_coarsen_device": (C.c_int, [C.POINTER(gosh_csr), C.c_int64, C.c_double, C.c_int32,
                                       C.c_int32, C.POINTER(C.c_void_p)]),
+    "gosh_hierarchy_release_device": (C.c_int, [C.c_void_p]),
     "gosh_hierarchy_levels": (C.c_int, [C.c_void_p]),
     "gosh_hierarchy_graph": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(gosh_csr)]),
     "gosh_hierarchy_map": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
@@ -202,6 +203,10 @@ class Hierarchy:
             lib().gosh_hierarchy_free(self._h)
             self._h = None
 
+    def release_device(self) -> None:
+        """Bring a device-built hierarchy to the host and free its device copies."""
+        _check(lib().gosh_hierarchy_release_device(self._h))
+
     @property
     def handle(self):
         return self._h
@@ -294,6 +299,10 @@ def gosh_hierarchy_mult(h: Hierarchy, i: int):
 
 def gosh_hierarchy_times(h: Hierarchy, i: int):
     return h.times(i)
+
+
+def gosh_hierarchy_release_device(h: Hierarchy) -> None:
+    h.release_device()
 
 
 def gosh_hierarchy_free(h: Hierarchy) -> None:

@@ -20,14 +20,25 @@
 struct gosh_hierarchy {
   struct Level {
     // Level 0 borrows the caller's arrays; coarser levels own theirs (64-bit offsets).
-    gosh_csr view{};
+    // A hierarchy built on the device keeps every level there (dev) and fills the host
+    // arrays only when an accessor asks for them (host_* say which are filled).
+    int64_t n = 0, nnz = 0;
+    gosh_csr view{};  // host view, valid once host_graph is set
     gosh::RawVector<int64_t> xadj;
     gosh::RawVector<int32_t> adj;
-    gosh::RawVector<int64_t> mult;  // fine entries merged into each entry (empty at level 0)
-    std::vector<int32_t> map;   // this level -> next coarser level (empty on the last)
+    gosh::RawVector<int64_t> mult;  // fine entries merged into each entry (none at level 0)
+    std::vector<int32_t> map;       // this level -> next coarser level (none on the last)
+    bool has_mult = false, has_map = false;
+    bool host_graph = false, host_mult = false, host_map = false;
+    gosh::DeviceLevel dev;
     double sort_ms = 0, mark_ms = 0, build_ms = 0;  // stages of coarsening THIS level
   };
   std::vector<Level> levels;
+  gosh::DeviceCoarsener *dc = nullptr;  // device-built hierarchies: staging for downloads
+  ~gosh_hierarchy() {
+    for (Level &l : levels) gosh::device_level_free(l.dev);
+    gosh::device_coarsener_free(dc);
+  }
 };
 
 namespace {
@@ -293,47 +304,115 @@ void build_coarse(const Csr<OffT> &g, const int64_t *mult_in, const std::vector<
       out.mult[static_cast<size_t>(begin + r)] = src[r].mult;
     }
   }
+  out.n = n_coarse;
+  out.nnz = nnz_coarse;
   out.view.n = n_coarse;
   out.view.nnz = nnz_coarse;
   out.view.xadj = out.xadj.data();
   out.view.adj = out.adj.data();
   out.view.xadj_is64 = 1;
+  out.has_mult = out.host_mult = true;
+  out.host_graph = true;
 }
 
-// One level: map of `fine` and the next level appended to h.  Returns |V_{i+1}|, or a
-// negative status if the device rebuild failed.
+// The marking of one host graph: fills level.map, returns |V_{i+1}|.
 template <typename OffT>
-int64_t coarsen_level(gosh_hierarchy &h, int threads, gosh::DeviceCarry *carry) {
-  gosh_hierarchy::Level &fine = h.levels.back();
-  const Csr<OffT> g{fine.view.n, static_cast<const OffT *>(fine.view.xadj), fine.view.adj};
+int64_t mark_on_host(gosh_hierarchy::Level &level, int threads) {
+  const Csr<OffT> g{level.view.n, static_cast<const OffT *>(level.view.xadj), level.view.adj};
   std::vector<int32_t> order;
   const double t0 = omp_get_wtime();
   degree_order(g, threads, order);
   const double t1 = omp_get_wtime();
-  const int64_t n_coarse = mark_clusters(g, fine.view.nnz, order, threads, fine.map);
+  const int64_t n_coarse = mark_clusters(g, level.view.nnz, order, threads, level.map);
+  level.sort_ms = (t1 - t0) * 1e3;
+  level.mark_ms = (omp_get_wtime() - t1) * 1e3;
+  level.has_map = level.host_map = true;
+  return n_coarse;
+}
+
+// One level on the host: map of the last level and the next level appended to h.
+// Returns |V_{i+1}|.
+template <typename OffT>
+int64_t coarsen_level(gosh_hierarchy &h, int threads) {
+  gosh_hierarchy::Level &fine = h.levels.back();
+  const int64_t n_coarse = mark_on_host<OffT>(fine, threads);
   const double t2 = omp_get_wtime();
+  const Csr<OffT> g{fine.view.n, static_cast<const OffT *>(fine.view.xadj), fine.view.adj};
   gosh_hierarchy::Level next;
-  const int64_t *mult_in = fine.mult.empty() ? nullptr : fine.mult.data();
-  if (carry != nullptr) {
-    if (int rc = gosh::build_coarse_on_device(fine.view, mult_in, fine.map.data(), n_coarse, threads, carry,
-                                              next.xadj, next.adj, next.mult))
-      return rc;
-    next.view.n = n_coarse;
-    next.view.nnz = static_cast<int64_t>(next.adj.size());
-    next.view.xadj_is64 = 1;
-  } else {
-    build_coarse(g, mult_in, fine.map, n_coarse, threads, next);
-  }
-  const double t3 = omp_get_wtime();
-  fine.sort_ms = (t1 - t0) * 1e3;
-  fine.mark_ms = (t2 - t1) * 1e3;
-  fine.build_ms = (t3 - t2) * 1e3;
+  build_coarse(g, fine.mult.empty() ? nullptr : fine.mult.data(), fine.map, n_coarse, threads, next);
+  fine.build_ms = (omp_get_wtime() - t2) * 1e3;
   h.levels.push_back(std::move(next));
   // the move kept the vectors' heap blocks; point the view at them
   gosh_hierarchy::Level &stored = h.levels.back();
   stored.view.xadj = stored.xadj.data();
   stored.view.adj = stored.adj.data();
   return n_coarse;
+}
+
+// Host copies of a device-built level, made on first request.
+int ensure_host_graph(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+  if (l.host_graph) return GOSH_OK;
+  if (!l.dev.present()) return gosh::fail(GOSH_EINVAL, "level has neither a host nor a device copy");
+  l.xadj.resize(static_cast<size_t>(l.n) + 1);
+  l.adj.resize(static_cast<size_t>(l.nnz));
+  if (int rc = gosh::device_download(h.dc, l.xadj.data(), l.dev.xadj, (static_cast<size_t>(l.n) + 1) * 8)) return rc;
+  if (int rc = gosh::device_download(h.dc, l.adj.data(), l.dev.adj, static_cast<size_t>(l.nnz) * 4)) return rc;
+  l.view.n = l.n;
+  l.view.nnz = l.nnz;
+  l.view.xadj = l.xadj.data();
+  l.view.adj = l.adj.data();
+  l.view.xadj_is64 = 1;
+  l.host_graph = true;
+  return GOSH_OK;
+}
+
+int ensure_host_map(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+  if (l.host_map || !l.has_map) return GOSH_OK;
+  if (l.dev.map == nullptr) return gosh::fail(GOSH_EINVAL, "map has neither a host nor a device copy");
+  l.map.resize(static_cast<size_t>(l.n));
+  if (int rc = gosh::device_download(h.dc, l.map.data(), l.dev.map, static_cast<size_t>(l.n) * 4)) return rc;
+  l.host_map = true;
+  return GOSH_OK;
+}
+
+int ensure_host_mult(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+  if (l.host_mult || !l.has_mult) return GOSH_OK;
+  if (l.dev.mult == nullptr) return gosh::fail(GOSH_EINVAL, "multiplicities have neither a host nor a device copy");
+  l.mult.resize(static_cast<size_t>(l.nnz));
+  if (int rc = gosh::device_download(h.dc, l.mult.data(), l.dev.mult, static_cast<size_t>(l.nnz) * 8)) return rc;
+  l.host_mult = true;
+  return GOSH_OK;
+}
+
+// One level on the device.  *n_coarse = |V_{i+1}|; the next level is appended unless
+// nothing merged.
+int coarsen_level_on_device(gosh_hierarchy &h, int threads, int64_t *n_coarse) {
+  gosh_hierarchy::Level &fine = h.levels.back();
+  bool done = false;
+  const double t0 = omp_get_wtime();
+  if (int rc = gosh::device_mark(h.dc, fine.dev, n_coarse, &done, &fine.sort_ms)) return rc;
+  if (done) {
+    fine.mark_ms = (omp_get_wtime() - t0) * 1e3 - fine.sort_ms;
+    fine.has_map = true;
+  } else {
+    // a chain of equal degrees: the in-order sweep of the host finishes it
+    if (int rc = ensure_host_graph(h, fine)) return rc;
+    *n_coarse = fine.view.xadj_is64 ? mark_on_host<int64_t>(fine, threads) : mark_on_host<int32_t>(fine, threads);
+    if (int rc = gosh::device_level_set_map(fine.dev, fine.map.data())) return rc;
+  }
+  if (*n_coarse == fine.n) return GOSH_OK;
+  const double t2 = omp_get_wtime();
+  gosh_hierarchy::Level next;
+  if (int rc = gosh::device_rebuild(h.dc, fine.dev, *n_coarse, next.dev)) {
+    gosh::device_level_free(next.dev);
+    return rc;
+  }
+  fine.build_ms = (omp_get_wtime() - t2) * 1e3;
+  next.n = next.dev.n;
+  next.nnz = next.dev.nnz;
+  next.has_mult = true;
+  h.levels.push_back(std::move(next));
+  return GOSH_OK;
 }
 
 template <typename OffT>
@@ -365,8 +444,7 @@ int gosh_csr_validate(const gosh_csr *g_host) {
 }
 
 static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
-                        int32_t max_levels, int32_t n_threads, bool rebuild_on_device,
-                        gosh_hierarchy **out) {
+                        int32_t max_levels, int32_t n_threads, bool on_device, gosh_hierarchy **out) {
   if (out == nullptr) return gosh::fail(GOSH_EINVAL, "out is null");
   *out = nullptr;
   if (int rc = gosh::check_csr(g0_host)) return rc;
@@ -377,33 +455,46 @@ static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_s
   int threads = n_threads > 0 ? n_threads : omp_get_max_threads();
   if (threads < 1) threads = 1;
   gosh_hierarchy *h = nullptr;
-  struct CarryOwner {
-    gosh::DeviceCarry *p = nullptr;
-    ~CarryOwner() { gosh::device_carry_free(p); }
-  } carry;
   try {
-    if (rebuild_on_device) carry.p = gosh::device_carry_new();
     h = new gosh_hierarchy();
     h->levels.reserve(static_cast<size_t>(std::min<int32_t>(max_levels, 64)));
     h->levels.emplace_back();
+    h->levels[0].n = g0_host->n;
+    h->levels[0].nnz = g0_host->nnz;
     h->levels[0].view = *g0_host;
-    while (h->levels.back().view.n > threshold && static_cast<int32_t>(h->levels.size()) < max_levels) {
-      const int64_t n_fine = h->levels.back().view.n;
-      const int64_t n_coarse = h->levels.back().view.xadj_is64
-                                   ? coarsen_level<int64_t>(*h, threads, carry.p)
-                                   : coarsen_level<int32_t>(*h, threads, carry.p);
-      if (n_coarse < 0) {  // status of a failed device rebuild
+    h->levels[0].host_graph = true;
+    const bool wants_levels = g0_host->n > threshold && max_levels > 1;
+    if (on_device && wants_levels) {
+      h->dc = gosh::device_coarsener_new(threads);
+      if (int rc = gosh::device_level_upload(*g0_host, h->levels[0].dev)) {
         delete h;
-        return static_cast<int>(n_coarse);
+        return rc;
+      }
+    }
+    while (h->levels.back().n > threshold && static_cast<int32_t>(h->levels.size()) < max_levels) {
+      const int64_t n_fine = h->levels.back().n;
+      int64_t n_coarse = 0;
+      if (on_device) {
+        if (int rc = coarsen_level_on_device(*h, threads, &n_coarse)) {
+          delete h;
+          return rc;
+        }
+      } else {
+        n_coarse = h->levels.back().view.xadj_is64 ? coarsen_level<int64_t>(*h, threads)
+                                                   : coarsen_level<int32_t>(*h, threads);
       }
       if (n_coarse == n_fine) {
         // nothing merged (e.g. only isolated vertices are left): G_{i+1} would repeat G_i
-        h->levels.pop_back();
-        h->levels.back().map.clear();
+        if (!on_device) h->levels.pop_back();
+        gosh_hierarchy::Level &last = h->levels.back();
+        last.map.clear();
+        last.has_map = last.host_map = false;
+        gosh::device_level_drop_map(last.dev);
         break;
       }
       if (static_cast<double>(n_coarse) > min_shrink * static_cast<double>(n_fine)) break;
     }
+    gosh::device_coarsener_trim(h->dc);
     *out = h;
     return GOSH_OK;
   } catch (const std::bad_alloc &) {
@@ -428,6 +519,8 @@ int gosh_hierarchy_graph(const gosh_hierarchy *h, int32_t i, gosh_csr *view) {
   if (h == nullptr || view == nullptr) return gosh::fail(GOSH_EINVAL, "null argument");
   if (i < 0 || i >= static_cast<int32_t>(h->levels.size()))
     return gosh::fail(GOSH_EINVAL, "level %d out of range [0, %zu)", i, h->levels.size());
+  gosh_hierarchy &hm = *const_cast<gosh_hierarchy *>(h);  // filling a host copy is not a visible change
+  if (int rc = ensure_host_graph(hm, hm.levels[static_cast<size_t>(i)])) return rc;
   *view = h->levels[static_cast<size_t>(i)].view;
   return GOSH_OK;
 }
@@ -436,6 +529,8 @@ int gosh_hierarchy_map(const gosh_hierarchy *h, int32_t i, const int32_t **map, 
   if (h == nullptr || map == nullptr || len == nullptr) return gosh::fail(GOSH_EINVAL, "null argument");
   if (i < 0 || i + 1 >= static_cast<int32_t>(h->levels.size()))
     return gosh::fail(GOSH_EINVAL, "map %d out of range [0, %zu)", i, h->levels.size() - 1);
+  gosh_hierarchy &hm = *const_cast<gosh_hierarchy *>(h);
+  if (int rc = ensure_host_map(hm, hm.levels[static_cast<size_t>(i)])) return rc;
   *map = h->levels[static_cast<size_t>(i)].map.data();
   *len = static_cast<int64_t>(h->levels[static_cast<size_t>(i)].map.size());
   return GOSH_OK;
@@ -445,9 +540,22 @@ int gosh_hierarchy_mult(const gosh_hierarchy *h, int32_t i, const int64_t **mult
   if (h == nullptr || mult == nullptr || len == nullptr) return gosh::fail(GOSH_EINVAL, "null argument");
   if (i < 0 || i >= static_cast<int32_t>(h->levels.size()))
     return gosh::fail(GOSH_EINVAL, "level %d out of range [0, %zu)", i, h->levels.size());
+  gosh_hierarchy &hm = *const_cast<gosh_hierarchy *>(h);
+  if (int rc = ensure_host_mult(hm, hm.levels[static_cast<size_t>(i)])) return rc;
   const auto &m = h->levels[static_cast<size_t>(i)].mult;
   *mult = m.empty() ? nullptr : m.data();
   *len = static_cast<int64_t>(m.size());
+  return GOSH_OK;
+}
+
+int gosh_hierarchy_release_device(gosh_hierarchy *h) {
+  if (h == nullptr) return GOSH_OK;
+  for (gosh_hierarchy::Level &l : h->levels) {
+    if (int rc = ensure_host_graph(*h, l)) return rc;
+    if (int rc = ensure_host_map(*h, l)) return rc;
+    if (int rc = ensure_host_mult(*h, l)) return rc;
+    gosh::device_level_free(l.dev);
+  }
   return GOSH_OK;
 }
 
@@ -465,3 +573,25 @@ int gosh_hierarchy_times(const gosh_hierarchy *h, int32_t i, double *ms3) {
 void gosh_hierarchy_free(gosh_hierarchy *h) { delete h; }
 
 }  // extern "C"
+
+namespace gosh {
+
+int hierarchy_shape(const gosh_hierarchy *h, int32_t i, gosh_csr *shape) {
+  if (h == nullptr || shape == nullptr) return fail(GOSH_EINVAL, "null argument");
+  if (i < 0 || i >= static_cast<int32_t>(h->levels.size()))
+    return fail(GOSH_EINVAL, "level %d out of range [0, %zu)", i, h->levels.size());
+  const gosh_hierarchy::Level &l = h->levels[static_cast<size_t>(i)];
+  *shape = gosh_csr{};
+  shape->n = l.n;
+  shape->nnz = l.nnz;
+  shape->xadj_is64 = l.host_graph ? l.view.xadj_is64 : l.dev.xadj_is64;
+  return GOSH_OK;
+}
+
+const DeviceLevel *hierarchy_device_level(const gosh_hierarchy *h, int32_t i) {
+  if (h == nullptr || i < 0 || i >= static_cast<int32_t>(h->levels.size())) return nullptr;
+  const DeviceLevel &dev = h->levels[static_cast<size_t>(i)].dev;
+  return dev.present() ? &dev : nullptr;
+}
+
+}  // namespace gosh

@@ -1,14 +1,30 @@
-// Rebuilding the CSR of a coarse graph on the device ("Coarsen" in Alg. 4 of the paper).
+// MultiEdgeCollapse (Alg. 4 of the paper) on the device: the degree order, the marking
+// sweep and the rebuild of the coarse CSR, with the results of the sequential algorithm.
 //
-// Every fine entry (x, y) becomes the 64-bit key map[x] * n_coarse + map[y] (entries
+// Order: a stable radix sort of the vertex ids by descending degree.
+//
+// Marking: in the sequential sweep a vertex becomes a hub iff none of the neighbours that
+// precede it in the order and may take it (one of the two degrees is at most the mean
+// degree) is itself a hub.  That recurrence is resolved out of order: a vertex above the
+// mean degree is always a hub, a low-degree vertex with such a neighbour never is, and
+// the remaining low-degree vertices are decided in rounds (hub once every preceding
+// neighbour is decided and none is a hub, taken as soon as one is).  A decision is final
+// and equals the sequential one, so stale reads can only delay it.  Hubs are numbered by
+// a scan over the order; every other vertex joins its first hub in the order.
+//
+// Rebuild: every fine entry (x, y) becomes the 64-bit key map[x] * n' + map[y] (entries
 // inside one cluster get a sentinel key above all others); a radix sort of the keys with
 // their multiplicities followed by a reduction of equal keys leaves exactly the distinct
 // coarse entries, in row-major ascending order, with the merged multiplicities -- the
 // same arrays the host implementation produces, since sorted distinct keys are unique.
-// Sort and reduce-by-key are rocPRIM device primitives; the surrounding kernels are here.
+//
+// Sort, scan and reduce-by-key are rocPRIM device primitives; the kernels around them
+// are here.  Everything runs on the null stream and the calls block.
 #include <hip/hip_runtime.h>
+#include <omp.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstring>
 
 #include <rocprim/rocprim.hpp>
@@ -17,6 +33,166 @@
 #include "gosh_common.h"
 
 namespace {
+
+constexpr uint32_t kHighBit = 0x80000000u;   // set in rk[v] when deg(v) is above the mean
+constexpr uint32_t kRankMask = 0x7FFFFFFFu;  // rk[v] & kRankMask = position of v in the order
+enum : int32_t { kUndecided = 0, kHub = 1, kTaken = 2 };
+
+__device__ inline int64_t first_wave() { return (blockIdx.x * 256LL + threadIdx.x) >> 6; }
+__device__ inline int64_t wave_count() { return (gridDim.x * 256LL) >> 6; }
+
+__device__ inline int32_t load_status(const int32_t *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void store_status(int32_t *p, int32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// key = 2^31 - 1 - degree: ascending keys are descending degrees; stable => ties by id.
+template <typename OffT>
+__global__ __launch_bounds__(256) void degree_keys_kernel(const OffT *__restrict__ xadj, int64_t n,
+                                                          uint32_t *__restrict__ keys,
+                                                          int32_t *__restrict__ ids) {
+  for (int64_t v = blockIdx.x * 256LL + threadIdx.x; v < n; v += gridDim.x * 256LL) {
+    keys[v] = kRankMask - static_cast<uint32_t>(xadj[v + 1] - xadj[v]);
+    ids[v] = static_cast<int32_t>(v);
+  }
+}
+
+// rk[order[t]] = t, with the high bit set when the degree exceeds the mean degree
+// (deg * n > nnz, exact in 64-bit integers).
+__global__ __launch_bounds__(256) void rank_kernel(const uint32_t *__restrict__ sorted_keys,
+                                                   const int32_t *__restrict__ order, int64_t n,
+                                                   int64_t nnz, uint32_t *__restrict__ rk) {
+  for (int64_t t = blockIdx.x * 256LL + threadIdx.x; t < n; t += gridDim.x * 256LL) {
+    const int64_t deg = static_cast<int64_t>(kRankMask - sorted_keys[t]);
+    rk[order[t]] = static_cast<uint32_t>(t) | (deg * n > nnz ? kHighBit : 0u);
+  }
+}
+
+// First classification, one wavefront per vertex: needs no knowledge of other decisions.
+template <typename OffT>
+__global__ __launch_bounds__(256) void classify_kernel(const OffT *__restrict__ xadj,
+                                                       const int32_t *__restrict__ adj,
+                                                       const uint32_t *__restrict__ rk, int64_t n,
+                                                       int32_t *__restrict__ status,
+                                                       int32_t *__restrict__ pending,
+                                                       unsigned long long *__restrict__ pending_count) {
+  const int lane = threadIdx.x & 63;
+  for (int64_t v = first_wave(); v < n; v += wave_count()) {
+    const uint32_t r = rk[v];
+    int32_t st = kHub;
+    if (!(r & kHighBit)) {
+      bool high_neighbour = false, predecessor = false;
+      const int64_t begin = static_cast<int64_t>(xadj[v]), end = static_cast<int64_t>(xadj[v + 1]);
+      for (int64_t e = begin + lane; e < end; e += 64) {
+        const uint32_t ru = rk[adj[e]];
+        high_neighbour |= (ru & kHighBit) != 0;
+        predecessor |= (ru & kRankMask) < r;
+      }
+      if (__ballot(high_neighbour) != 0) st = kTaken;
+      else if (__ballot(predecessor) != 0) st = kUndecided;
+    }
+    if (lane == 0) {
+      status[v] = st;
+      if (st == kUndecided) pending[atomicAdd(pending_count, 1ull)] = static_cast<int32_t>(v);
+    }
+  }
+}
+
+// One round over the undecided vertices, one wavefront per vertex.
+template <typename OffT>
+__global__ __launch_bounds__(256) void round_kernel(const OffT *__restrict__ xadj,
+                                                    const int32_t *__restrict__ adj,
+                                                    const uint32_t *__restrict__ rk,
+                                                    int32_t *__restrict__ status,
+                                                    const int32_t *__restrict__ pending, int64_t count,
+                                                    int32_t *__restrict__ still,
+                                                    unsigned long long *__restrict__ still_count) {
+  const int lane = threadIdx.x & 63;
+  for (int64_t i = first_wave(); i < count; i += wave_count()) {
+    const int32_t v = pending[i];
+    const uint32_t r = rk[v];  // low degree: no high bit
+    bool taken = false, blocked = false;
+    const int64_t begin = static_cast<int64_t>(xadj[v]), end = static_cast<int64_t>(xadj[v + 1]);
+    for (int64_t e = begin + lane; e < end; e += 64) {
+      const int32_t u = adj[e];
+      if ((rk[u] & kRankMask) < r) {
+        const int32_t su = load_status(status + u);
+        taken |= su == kHub;
+        blocked |= su == kUndecided;
+      }
+    }
+    const bool any_taken = __ballot(taken) != 0, any_blocked = __ballot(blocked) != 0;
+    if (lane == 0) {
+      if (any_taken) store_status(status + v, kTaken);
+      else if (!any_blocked) store_status(status + v, kHub);
+      else still[atomicAdd(still_count, 1ull)] = v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void hub_flags_kernel(const int32_t *__restrict__ status,
+                                                        const int32_t *__restrict__ order, int64_t n,
+                                                        int32_t *__restrict__ flags) {
+  for (int64_t t = blockIdx.x * 256LL + threadIdx.x; t < n; t += gridDim.x * 256LL)
+    flags[t] = status[order[t]] == kHub ? 1 : 0;
+}
+
+// Cluster ids are the hubs' positions among the hubs in the order.
+__global__ __launch_bounds__(256) void number_hubs_kernel(const int32_t *__restrict__ flags,
+                                                          const int32_t *__restrict__ index,
+                                                          const int32_t *__restrict__ order, int64_t n,
+                                                          int32_t *__restrict__ map) {
+  for (int64_t t = blockIdx.x * 256LL + threadIdx.x; t < n; t += gridDim.x * 256LL)
+    if (flags[t]) map[order[t]] = index[t];
+}
+
+// Every taken vertex joins its first hub in the order, one wavefront per vertex.  The
+// hubs' own entries of map (read here) were written by the launch before this one; this
+// launch writes only entries of taken vertices.
+template <typename OffT>
+__global__ __launch_bounds__(256) void join_kernel(const OffT *__restrict__ xadj,
+                                                   const int32_t *__restrict__ adj,
+                                                   const uint32_t *__restrict__ rk,
+                                                   const int32_t *__restrict__ status,
+                                                   const int32_t *__restrict__ order, int64_t n,
+                                                   int32_t *map) {
+  const int lane = threadIdx.x & 63;
+  for (int64_t v = first_wave(); v < n; v += wave_count()) {
+    if (status[v] != kTaken) continue;
+    const uint32_t r = rk[v];
+    uint32_t best = kRankMask;
+    const int64_t begin = static_cast<int64_t>(xadj[v]), end = static_cast<int64_t>(xadj[v + 1]);
+    for (int64_t e = begin + lane; e < end; e += 64) {
+      const int32_t u = adj[e];
+      const uint32_t ru = rk[u] & kRankMask;
+      if (ru < r && ru < best && status[u] == kHub) best = ru;
+    }
+    for (int offset = 32; offset > 0; offset >>= 1) best = min(best, __shfl_xor(best, offset, 64));
+    // a taken vertex has a hub before it, so best is a valid position; the guard keeps a
+    // broken invariant from turning into a wild read
+    if (lane == 0 && best < static_cast<uint32_t>(n)) map[v] = map[order[best]];
+  }
+}
+
+// Shape checks before any kernel follows the offsets or the neighbour ids: *bad becomes
+// nonzero if the offsets do not run from 0 to nnz without decreasing, or (second kernel)
+// if a neighbour id is outside [0, n).
+template <typename OffT>
+__global__ __launch_bounds__(256) void check_offsets_kernel(const OffT *__restrict__ xadj, int64_t n,
+                                                            int64_t nnz, int32_t *__restrict__ bad) {
+  for (int64_t v = blockIdx.x * 256LL + threadIdx.x; v < n; v += gridDim.x * 256LL) {
+    const int64_t lo = static_cast<int64_t>(xadj[v]), hi = static_cast<int64_t>(xadj[v + 1]);
+    if (lo > hi || lo < 0 || hi > nnz || (v == 0 && lo != 0) || (v == n - 1 && hi != nnz)) *bad = 1;
+  }
+}
+
+__global__ __launch_bounds__(256) void check_neighbours_kernel(const int32_t *__restrict__ adj, int64_t nnz,
+                                                               int64_t n, int32_t *__restrict__ bad) {
+  for (int64_t e = blockIdx.x * 256LL + threadIdx.x; e < nnz; e += gridDim.x * 256LL)
+    if (adj[e] < 0 || adj[e] >= n) *bad = 1;
+}
 
 // One wavefront per fine row: lanes stride over the row's entries (coalesced reads).
 template <typename OffT>
@@ -28,9 +204,7 @@ __global__ __launch_bounds__(256) void make_keys_kernel(const OffT *__restrict__
                                                         uint64_t *__restrict__ keys,
                                                         int64_t *__restrict__ vals) {
   const int lane = threadIdx.x & 63;
-  const int64_t wave0 = (blockIdx.x * 256LL + threadIdx.x) >> 6;
-  const int64_t nwaves = (gridDim.x * 256LL) >> 6;
-  for (int64_t x = wave0; x < n; x += nwaves) {
+  for (int64_t x = first_wave(); x < n; x += wave_count()) {
     const uint64_t a = static_cast<uint64_t>(map[x]);
     const int64_t begin = static_cast<int64_t>(xadj[x]), end = static_cast<int64_t>(xadj[x + 1]);
     for (int64_t e = begin + lane; e < end; e += 64) {
@@ -41,8 +215,7 @@ __global__ __launch_bounds__(256) void make_keys_kernel(const OffT *__restrict__
   }
 }
 
-// xadj_out[a] = number of distinct keys below a * n_coarse (binary search per coarse row);
-// adj_out[i] = column of distinct key i.
+// xadj_out[a] = number of distinct keys below a * n_coarse (binary search per coarse row).
 __global__ __launch_bounds__(256) void offsets_kernel(const uint64_t *__restrict__ unique_keys,
                                                       int64_t n_unique, uint64_t n_coarse,
                                                       int64_t *__restrict__ xadj_out) {
@@ -58,11 +231,15 @@ __global__ __launch_bounds__(256) void offsets_kernel(const uint64_t *__restrict
   }
 }
 
+// adj_out[i] = column of distinct key i; mult_out[i] = its merged multiplicity.
 __global__ __launch_bounds__(256) void columns_kernel(const uint64_t *__restrict__ unique_keys,
-                                                      int64_t n_unique, uint64_t n_coarse,
-                                                      int32_t *__restrict__ adj_out) {
-  for (int64_t i = blockIdx.x * 256LL + threadIdx.x; i < n_unique; i += gridDim.x * 256LL)
+                                                      const int64_t *__restrict__ sums, int64_t n_unique,
+                                                      uint64_t n_coarse, int32_t *__restrict__ adj_out,
+                                                      int64_t *__restrict__ mult_out) {
+  for (int64_t i = blockIdx.x * 256LL + threadIdx.x; i < n_unique; i += gridDim.x * 256LL) {
     adj_out[i] = static_cast<int32_t>(unique_keys[i] % n_coarse);
+    mult_out[i] = sums[i];
+  }
 }
 
 // Device blocks recycled over the levels of one run: hipMalloc and hipFree of gigabyte
@@ -75,8 +252,10 @@ struct Pool {
     bool busy;
   };
   std::vector<Block> blocks;
-  ~Pool() {
+  ~Pool() { trim(); }
+  void trim() {
     for (Block &b : blocks) (void)hipFree(b.p);
+    blocks.clear();
   }
   void *take(size_t bytes) {
     Block *best = nullptr;
@@ -100,7 +279,7 @@ struct Pool {
   }
 };
 
-// The blocks one call holds; whatever is not handed on goes back to the pool on return.
+// The blocks one call holds; they go back to the pool on return.
 struct Buffers {
   Pool &pool;
   std::vector<void *> ptrs;
@@ -117,10 +296,6 @@ struct Buffers {
     ptrs.push_back(p);
     *out = static_cast<T *>(p);
     return GOSH_OK;
-  }
-  void forget(void *p) {
-    for (void *&q : ptrs)
-      if (q == p) q = nullptr;
   }
   void release(void *p) {
     for (void *&q : ptrs)
@@ -139,156 +314,331 @@ struct Buffers {
 
 int blocks_for(int64_t items, int per_block) {
   int64_t b = (items + per_block - 1) / per_block;
-  return static_cast<int>(std::min<int64_t>(std::max<int64_t>(b, 1), 1 << 20));
+  return static_cast<int>(std::min<int64_t>(std::max<int64_t>(b, 1), 1 << 16));
+}
+
+// Exact-sized block that outlives the run (a level's array).
+template <typename T>
+int persistent(T **out, size_t count, const char *what) {
+  void *p = nullptr;
+  const size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+  if (hipMalloc(&p, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return gosh::fail(GOSH_ENOMEM, "cannot allocate %zu device bytes for %s", bytes, what);
+  }
+  *out = static_cast<T *>(p);
+  return GOSH_OK;
+}
+
+double ms_since(std::chrono::steady_clock::time_point t0) {
+  return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
 }
 
 }  // namespace
 
 namespace gosh {
 
-struct DeviceCarry {
-  Pool pool;  // destroyed last: every block below lives in it
-  int64_t n = -1, nnz = -1;
-  int64_t *xadj = nullptr;
-  int32_t *adj = nullptr;
-  int64_t *mult = nullptr;
-  // two pinned staging slots for large downloads, made on first use
+struct DeviceCoarsener {
+  Pool pool;
+  int threads = 1;
+  // Two pinned staging slots for large downloads, made on first use and kept.  The copy
+  // stream is NOT kept: a process has few hardware queues, and an idle stream of ours
+  // would make the streams of a later training call share one.
   static constexpr size_t kSlotBytes = size_t(64) << 20;
   char *slot[2] = {nullptr, nullptr};
-  hipStream_t stream = nullptr;
-  hipEvent_t landed[2] = {nullptr, nullptr};
-  ~DeviceCarry() {
-    drop();
-    for (int i = 0; i < 2; ++i) {
+  ~DeviceCoarsener() {
+    for (int i = 0; i < 2; ++i)
       if (slot[i]) (void)hipHostFree(slot[i]);
-      if (landed[i]) (void)hipEventDestroy(landed[i]);
-    }
-    if (stream) (void)hipStreamDestroy(stream);
-  }
-  void drop() {
-    if (xadj) pool.give(xadj);
-    if (adj) pool.give(adj);
-    if (mult) pool.give(mult);
-    xadj = nullptr, adj = nullptr, mult = nullptr, n = -1, nnz = -1;
   }
 };
 
-DeviceCarry *device_carry_new() { return new DeviceCarry(); }
+DeviceCoarsener *device_coarsener_new(int threads) {
+  DeviceCoarsener *dc = new DeviceCoarsener();
+  dc->threads = std::max(threads, 1);
+  return dc;
+}
 
-void device_carry_free(DeviceCarry *c) { delete c; }
+void device_coarsener_free(DeviceCoarsener *dc) { delete dc; }
 
-namespace {
+void device_coarsener_trim(DeviceCoarsener *dc) {
+  if (dc) dc->pool.trim();
+}
 
-// Device -> pageable host copy.  Large copies go through two pinned slots: while one slot
-// receives the next piece by DMA, all threads copy the previous one to its place (which
-// also spreads the page faults of a fresh destination over the threads).
-int download(void *dst, const void *src_d, size_t bytes, int threads, DeviceCarry *carry) {
+void device_level_free(DeviceLevel &level) {
+  if (level.xadj) (void)hipFree(level.xadj);
+  if (level.adj) (void)hipFree(level.adj);
+  if (level.mult) (void)hipFree(level.mult);
+  if (level.map) (void)hipFree(level.map);
+  level = DeviceLevel();
+}
+
+void device_level_drop_map(DeviceLevel &level) {
+  if (level.map) (void)hipFree(level.map);
+  level.map = nullptr;
+}
+
+int device_level_upload(const gosh_csr &host, DeviceLevel &out) {
+  device_level_free(out);
+  COARSE_HIP(hipGetDevice(&out.device), "hipGetDevice");
+  out.n = host.n;
+  out.nnz = host.nnz;
+  out.xadj_is64 = host.xadj_is64 ? 1 : 0;
+  const size_t off_bytes = static_cast<size_t>(host.n + 1) * (host.xadj_is64 ? 8 : 4);
+  char *offsets = nullptr;
+  if (int rc = persistent(&offsets, off_bytes, "offsets")) return rc;
+  out.xadj = offsets;
+  if (int rc = persistent(&out.adj, static_cast<size_t>(host.nnz), "adjacency")) return rc;
+  COARSE_HIP(hipMemcpy(out.xadj, host.xadj, off_bytes, hipMemcpyHostToDevice), "copy offsets");
+  if (host.nnz > 0)
+    COARSE_HIP(hipMemcpy(out.adj, host.adj, static_cast<size_t>(host.nnz) * 4, hipMemcpyHostToDevice),
+               "copy adjacency");
+  // the kernels follow offsets and neighbour ids without further checks
+  int32_t *bad_dev = nullptr;
+  if (int rc = persistent(&bad_dev, 1, "check flag")) return rc;
+  struct FlagGuard {
+    int32_t *p;
+    ~FlagGuard() { (void)hipFree(p); }
+  } guard{bad_dev};
+  int32_t bad = 0;
+  COARSE_HIP(hipMemset(bad_dev, 0, 4), "clear check flag");
+  const int off_blocks = blocks_for(host.n, 256);
+  if (host.xadj_is64)
+    hipLaunchKernelGGL(check_offsets_kernel<int64_t>, dim3(off_blocks), dim3(256), 0, nullptr,
+                       static_cast<const int64_t *>(out.xadj), out.n, out.nnz, bad_dev);
+  else
+    hipLaunchKernelGGL(check_offsets_kernel<int32_t>, dim3(off_blocks), dim3(256), 0, nullptr,
+                       static_cast<const int32_t *>(out.xadj), out.n, out.nnz, bad_dev);
+  if (int rc = gosh::check_launch("check_offsets_kernel")) return rc;
+  COARSE_HIP(hipMemcpy(&bad, bad_dev, 4, hipMemcpyDeviceToHost), "read check flag");
+  if (bad) return gosh::fail(GOSH_EINVAL, "xadj does not run from 0 to nnz without decreasing");
+  if (host.nnz > 0) {
+    hipLaunchKernelGGL(check_neighbours_kernel, dim3(blocks_for(host.nnz, 256)), dim3(256), 0, nullptr, out.adj,
+                       out.nnz, out.n, bad_dev);
+    if (int rc = gosh::check_launch("check_neighbours_kernel")) return rc;
+    COARSE_HIP(hipMemcpy(&bad, bad_dev, 4, hipMemcpyDeviceToHost), "read check flag");
+    if (bad) return gosh::fail(GOSH_EINVAL, "a neighbour id is outside [0, n)");
+  }
+  return GOSH_OK;
+}
+
+int device_level_set_map(DeviceLevel &level, const int32_t *map_host) {
+  if (level.map == nullptr)
+    if (int rc = persistent(&level.map, static_cast<size_t>(level.n), "map")) return rc;
+  COARSE_HIP(hipMemcpy(level.map, map_host, static_cast<size_t>(level.n) * 4, hipMemcpyHostToDevice), "copy map");
+  return GOSH_OK;
+}
+
+// Large copies go through two pinned slots: while one slot receives the next piece by DMA,
+// all threads copy the previous one to its place (which also spreads the page faults of a
+// fresh destination over the threads).
+int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t bytes) {
   if (bytes == 0) return GOSH_OK;
-  if (bytes < 4 * DeviceCarry::kSlotBytes) {
-    COARSE_HIP(hipMemcpy(dst, src_d, bytes, hipMemcpyDeviceToHost), "download");
+  if (dc == nullptr || bytes < 4 * DeviceCoarsener::kSlotBytes) {
+    COARSE_HIP(hipMemcpy(dst, src_dev, bytes, hipMemcpyDeviceToHost), "download");
     return GOSH_OK;
   }
-  if (carry->stream == nullptr) {
-    COARSE_HIP(hipStreamCreate(&carry->stream), "create copy stream");
-    for (int i = 0; i < 2; ++i) {
-      COARSE_HIP(hipEventCreateWithFlags(&carry->landed[i], hipEventDisableTiming), "create copy event");
+  for (int i = 0; i < 2; ++i)
+    if (dc->slot[i] == nullptr) {
       void *p = nullptr;
-      COARSE_HIP(hipHostMalloc(&p, DeviceCarry::kSlotBytes, hipHostMallocDefault), "allocate pinned staging");
-      carry->slot[i] = static_cast<char *>(p);
+      COARSE_HIP(hipHostMalloc(&p, DeviceCoarsener::kSlotBytes, hipHostMallocDefault), "allocate pinned staging");
+      dc->slot[i] = static_cast<char *>(p);
     }
-  }
-  const size_t slot_bytes = DeviceCarry::kSlotBytes;
+  struct CopyQueue {
+    hipStream_t stream = nullptr;
+    hipEvent_t landed[2] = {nullptr, nullptr};
+    ~CopyQueue() {
+      for (int i = 0; i < 2; ++i)
+        if (landed[i]) (void)hipEventDestroy(landed[i]);
+      if (stream) (void)hipStreamDestroy(stream);
+    }
+  } q;
+  COARSE_HIP(hipStreamCreate(&q.stream), "create copy stream");
+  for (int i = 0; i < 2; ++i)
+    COARSE_HIP(hipEventCreateWithFlags(&q.landed[i], hipEventDisableTiming), "create copy event");
+  const size_t slot_bytes = DeviceCoarsener::kSlotBytes;
   const size_t pieces = (bytes + slot_bytes - 1) / slot_bytes;
   auto piece_bytes = [&](size_t c) { return std::min(slot_bytes, bytes - c * slot_bytes); };
   auto start = [&](size_t c) -> hipError_t {
-    hipError_t e = hipMemcpyAsync(carry->slot[c & 1], static_cast<const char *>(src_d) + c * slot_bytes,
-                                  piece_bytes(c), hipMemcpyDeviceToHost, carry->stream);
-    return e != hipSuccess ? e : hipEventRecord(carry->landed[c & 1], carry->stream);
+    hipError_t e = hipMemcpyAsync(dc->slot[c & 1], static_cast<const char *>(src_dev) + c * slot_bytes,
+                                  piece_bytes(c), hipMemcpyDeviceToHost, q.stream);
+    return e != hipSuccess ? e : hipEventRecord(q.landed[c & 1], q.stream);
   };
   COARSE_HIP(start(0), "start download");
   for (size_t c = 0; c < pieces; ++c) {
+    // slot (c + 1) & 1 was emptied in the previous iteration
     if (c + 1 < pieces) COARSE_HIP(start(c + 1), "start download");
-    COARSE_HIP(hipEventSynchronize(carry->landed[c & 1]), "wait for download");
+    COARSE_HIP(hipEventSynchronize(q.landed[c & 1]), "wait for download");
     char *to = static_cast<char *>(dst) + c * slot_bytes;
-    const char *from = carry->slot[c & 1];
+    const char *from = dc->slot[c & 1];
     const int64_t len = static_cast<int64_t>(piece_bytes(c));
     const int64_t grain = int64_t(1) << 20;
     const int64_t grains = (len + grain - 1) / grain;
-#pragma omp parallel for num_threads(threads) schedule(static)
+#pragma omp parallel for num_threads(dc->threads) schedule(static)
     for (int64_t g = 0; g < grains; ++g)
       memcpy(to + g * grain, from + g * grain, static_cast<size_t>(std::min(grain, len - g * grain)));
   }
   return GOSH_OK;
 }
 
+namespace {
+
+template <typename OffT>
+int mark_impl(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *done, double *order_ms) {
+  const int64_t n = fine.n, nnz = fine.nnz;
+  const OffT *xadj = static_cast<const OffT *>(fine.xadj);
+  const int32_t *adj = fine.adj;
+  *done = false;
+  Buffers buf(dc->pool);
+  const auto t_order = std::chrono::steady_clock::now();
+
+  // degree order
+  uint32_t *keys = nullptr, *keys_sorted = nullptr, *rk = nullptr;
+  int32_t *ids = nullptr, *order = nullptr;
+  if (int rc = buf.alloc(&keys, static_cast<size_t>(n), "degree keys")) return rc;
+  if (int rc = buf.alloc(&keys_sorted, static_cast<size_t>(n), "sorted degree keys")) return rc;
+  if (int rc = buf.alloc(&ids, static_cast<size_t>(n), "vertex ids")) return rc;
+  if (int rc = buf.alloc(&order, static_cast<size_t>(n), "order")) return rc;
+  if (int rc = buf.alloc(&rk, static_cast<size_t>(n), "ranks")) return rc;
+  const int flat_blocks = blocks_for(n, 256);
+  hipLaunchKernelGGL(degree_keys_kernel<OffT>, dim3(flat_blocks), dim3(256), 0, nullptr, xadj, n, keys, ids);
+  if (int rc = gosh::check_launch("degree_keys_kernel")) return rc;
+  {
+    size_t temp_bytes = 0;
+    COARSE_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, ids, order,
+                                         static_cast<size_t>(n), 0u, 31u, nullptr),
+               "degree sort (size query)");
+    char *temp = nullptr;
+    if (int rc = buf.alloc(&temp, temp_bytes, "sort workspace")) return rc;
+    COARSE_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, ids, order,
+                                         static_cast<size_t>(n), 0u, 31u, nullptr),
+               "degree sort");
+    COARSE_HIP(hipDeviceSynchronize(), "degree sort");
+    buf.release(temp);
+  }
+  hipLaunchKernelGGL(rank_kernel, dim3(flat_blocks), dim3(256), 0, nullptr, keys_sorted, order, n, nnz, rk);
+  if (int rc = gosh::check_launch("rank_kernel")) return rc;
+  COARSE_HIP(hipDeviceSynchronize(), "ranks");
+  buf.release(keys);
+  buf.release(keys_sorted);
+  buf.release(ids);
+  *order_ms = ms_since(t_order);
+
+  // first classification
+  int32_t *status = nullptr, *pending = nullptr, *still = nullptr;
+  unsigned long long *counters = nullptr;  // sizes of the two pending lists
+  if (int rc = buf.alloc(&status, static_cast<size_t>(n), "status")) return rc;
+  if (int rc = buf.alloc(&pending, static_cast<size_t>(n), "pending list")) return rc;
+  if (int rc = buf.alloc(&still, static_cast<size_t>(n), "pending list")) return rc;
+  if (int rc = buf.alloc(&counters, 2, "pending counters")) return rc;
+  COARSE_HIP(hipMemset(counters, 0, 16), "clear counters");
+  const int wave_blocks = blocks_for(n, 4);  // four wavefronts (vertices) per block
+  hipLaunchKernelGGL(classify_kernel<OffT>, dim3(wave_blocks), dim3(256), 0, nullptr, xadj, adj, rk, n, status,
+                     pending, counters);
+  if (int rc = gosh::check_launch("classify_kernel")) return rc;
+  unsigned long long count = 0;
+  COARSE_HIP(hipMemcpy(&count, counters, 8, hipMemcpyDeviceToHost), "read pending count");
+
+  // rounds: each decides at least the first pending vertex of the order, usually most
+  const int kMaxRounds = 256;
+  int which = 0;  // counters[which] is the size of `pending`
+  for (int round = 0; count > 0; ++round) {
+    if (round == kMaxRounds) return GOSH_OK;  // *done stays false
+    COARSE_HIP(hipMemset(counters + (which ^ 1), 0, 8), "clear counter");
+    hipLaunchKernelGGL(round_kernel<OffT>, dim3(blocks_for(static_cast<int64_t>(count), 4)), dim3(256), 0, nullptr,
+                       xadj, adj, rk, status, pending, static_cast<int64_t>(count), still, counters + (which ^ 1));
+    if (int rc = gosh::check_launch("round_kernel")) return rc;
+    unsigned long long left = 0;
+    COARSE_HIP(hipMemcpy(&left, counters + (which ^ 1), 8, hipMemcpyDeviceToHost), "read pending count");
+    // a long chain: a few vertices per round would take forever
+    if (round >= 16 && left > 4096 && left * 100 > count * 99) return GOSH_OK;
+    std::swap(pending, still);
+    which ^= 1;
+    count = left;
+  }
+  buf.release(pending);
+  buf.release(still);
+
+  // number the hubs in the order
+  int32_t *flags = nullptr, *index = nullptr;
+  if (int rc = buf.alloc(&flags, static_cast<size_t>(n), "hub flags")) return rc;
+  if (int rc = buf.alloc(&index, static_cast<size_t>(n), "hub numbers")) return rc;
+  hipLaunchKernelGGL(hub_flags_kernel, dim3(flat_blocks), dim3(256), 0, nullptr, status, order, n, flags);
+  if (int rc = gosh::check_launch("hub_flags_kernel")) return rc;
+  {
+    size_t temp_bytes = 0;
+    COARSE_HIP(rocprim::exclusive_scan(nullptr, temp_bytes, flags, index, int32_t(0), static_cast<size_t>(n),
+                                       rocprim::plus<int32_t>(), nullptr),
+               "hub scan (size query)");
+    char *temp = nullptr;
+    if (int rc = buf.alloc(&temp, temp_bytes, "scan workspace")) return rc;
+    COARSE_HIP(rocprim::exclusive_scan(temp, temp_bytes, flags, index, int32_t(0), static_cast<size_t>(n),
+                                       rocprim::plus<int32_t>(), nullptr),
+               "hub scan");
+    COARSE_HIP(hipDeviceSynchronize(), "hub scan");
+    buf.release(temp);
+  }
+  int32_t last_flag = 0, last_index = 0;
+  COARSE_HIP(hipMemcpy(&last_flag, flags + (n - 1), 4, hipMemcpyDeviceToHost), "read hub count");
+  COARSE_HIP(hipMemcpy(&last_index, index + (n - 1), 4, hipMemcpyDeviceToHost), "read hub count");
+  if (fine.map == nullptr)
+    if (int rc = persistent(&fine.map, static_cast<size_t>(n), "map")) return rc;
+  hipLaunchKernelGGL(number_hubs_kernel, dim3(flat_blocks), dim3(256), 0, nullptr, flags, index, order, n, fine.map);
+  if (int rc = gosh::check_launch("number_hubs_kernel")) return rc;
+  hipLaunchKernelGGL(join_kernel<OffT>, dim3(wave_blocks), dim3(256), 0, nullptr, xadj, adj, rk, status, order, n,
+                     fine.map);
+  if (int rc = gosh::check_launch("join_kernel")) return rc;
+  COARSE_HIP(hipDeviceSynchronize(), "marking");
+  *n_coarse = static_cast<int64_t>(last_flag) + last_index;
+  *done = true;
+  return GOSH_OK;
+}
+
 }  // namespace
 
-int build_coarse_on_device(const gosh_csr &fine, const int64_t *mult_in, const int32_t *map,
-                           int64_t n_coarse, int threads, DeviceCarry *carry,
-                           RawVector<int64_t> &xadj_out, RawVector<int32_t> &adj_out,
-                           RawVector<int64_t> &mult_out) {
+int device_mark(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *done, double *order_ms) {
+  if (dc == nullptr || !fine.present() || fine.n < 1) return gosh::fail(GOSH_EINVAL, "device level is missing");
+  return fine.xadj_is64 ? mark_impl<int64_t>(dc, fine, n_coarse, done, order_ms)
+                        : mark_impl<int32_t>(dc, fine, n_coarse, done, order_ms);
+}
+
+int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coarse, DeviceLevel &coarse) {
+  if (dc == nullptr || !fine.present() || fine.map == nullptr)
+    return gosh::fail(GOSH_EINVAL, "device level or its map is missing");
+  device_level_free(coarse);
   const int64_t n = fine.n, nnz = fine.nnz;
-  xadj_out.assign(static_cast<size_t>(n_coarse) + 1, 0);
-  adj_out.clear();
-  mult_out.clear();
-  if (carry == nullptr) return gosh::fail(GOSH_EINVAL, "device state is null");
-  if (nnz == 0) {
-    carry->drop();
-    return GOSH_OK;
-  }
   const uint64_t nc = static_cast<uint64_t>(n_coarse);
   const uint64_t sentinel = nc * nc;  // above every real key
   unsigned end_bit = 1;
   while (end_bit < 64 && (sentinel >> end_bit) != 0) ++end_bit;
+  coarse.device = fine.device;
+  coarse.n = n_coarse;
+  coarse.xadj_is64 = 1;
+  int64_t *xadj_out = nullptr;
+  if (int rc = persistent(&xadj_out, static_cast<size_t>(n_coarse) + 1, "coarse offsets")) return rc;
+  coarse.xadj = xadj_out;
+  if (nnz == 0) {
+    coarse.nnz = 0;
+    COARSE_HIP(hipMemset(xadj_out, 0, (static_cast<size_t>(n_coarse) + 1) * 8), "clear coarse offsets");
+    if (int rc = persistent(&coarse.adj, 0, "coarse adjacency")) return rc;
+    if (int rc = persistent(&coarse.mult, 0, "coarse multiplicities")) return rc;
+    return GOSH_OK;
+  }
 
-  Buffers buf(carry->pool);
-  int32_t *map_d = nullptr;
-  if (int rc = buf.alloc(&map_d, static_cast<size_t>(n), "map")) return rc;
-  COARSE_HIP(hipMemcpy(map_d, map, static_cast<size_t>(n) * 4, hipMemcpyHostToDevice), "copy map");
+  Buffers buf(dc->pool);
   uint64_t *keys = nullptr, *keys_sorted = nullptr;
   int64_t *vals = nullptr, *vals_sorted = nullptr;
   if (int rc = buf.alloc(&keys, static_cast<size_t>(nnz), "keys")) return rc;
   if (int rc = buf.alloc(&vals, static_cast<size_t>(nnz), "values")) return rc;
   const int key_blocks = blocks_for(n, 4);  // four wavefronts (rows) per block
-  const bool carried = carry->n == n && carry->nnz == nnz && fine.xadj_is64 && mult_in != nullptr;
-  if (carried) {
-    hipLaunchKernelGGL(make_keys_kernel<int64_t>, dim3(key_blocks), dim3(256), 0, nullptr, carry->xadj,
-                       carry->adj, carry->mult, map_d, n, nc, sentinel, keys, vals);
-    if (int rc = gosh::check_launch("make_keys_kernel")) return rc;
-    COARSE_HIP(hipDeviceSynchronize(), "make keys");
-  } else {
-    void *xadj_d = nullptr;
-    int32_t *adj_d = nullptr;
-    int64_t *mult_d = nullptr;
-    const size_t off_bytes = static_cast<size_t>(n + 1) * (fine.xadj_is64 ? 8 : 4);
-    {
-      char *p = nullptr;
-      if (int rc = buf.alloc(&p, off_bytes, "offsets")) return rc;
-      xadj_d = p;
-    }
-    if (int rc = buf.alloc(&adj_d, static_cast<size_t>(nnz), "adjacency")) return rc;
-    COARSE_HIP(hipMemcpy(xadj_d, fine.xadj, off_bytes, hipMemcpyHostToDevice), "copy offsets");
-    COARSE_HIP(hipMemcpy(adj_d, fine.adj, static_cast<size_t>(nnz) * 4, hipMemcpyHostToDevice), "copy adjacency");
-    if (mult_in) {
-      if (int rc = buf.alloc(&mult_d, static_cast<size_t>(nnz), "multiplicities")) return rc;
-      COARSE_HIP(hipMemcpy(mult_d, mult_in, static_cast<size_t>(nnz) * 8, hipMemcpyHostToDevice),
-                 "copy multiplicities");
-    }
-    if (fine.xadj_is64)
-      hipLaunchKernelGGL(make_keys_kernel<int64_t>, dim3(key_blocks), dim3(256), 0, nullptr,
-                         static_cast<const int64_t *>(xadj_d), adj_d, mult_d, map_d, n, nc, sentinel, keys, vals);
-    else
-      hipLaunchKernelGGL(make_keys_kernel<int32_t>, dim3(key_blocks), dim3(256), 0, nullptr,
-                         static_cast<const int32_t *>(xadj_d), adj_d, mult_d, map_d, n, nc, sentinel, keys, vals);
-    if (int rc = gosh::check_launch("make_keys_kernel")) return rc;
-    COARSE_HIP(hipDeviceSynchronize(), "make keys");
-    buf.release(xadj_d);
-    buf.release(adj_d);
-    if (mult_d) buf.release(mult_d);
-  }
-  // the fine graph is no longer needed on the device
-  carry->drop();
-  buf.release(map_d);
+  if (fine.xadj_is64)
+    hipLaunchKernelGGL(make_keys_kernel<int64_t>, dim3(key_blocks), dim3(256), 0, nullptr,
+                       static_cast<const int64_t *>(fine.xadj), fine.adj, fine.mult, fine.map, n, nc, sentinel,
+                       keys, vals);
+  else
+    hipLaunchKernelGGL(make_keys_kernel<int32_t>, dim3(key_blocks), dim3(256), 0, nullptr,
+                       static_cast<const int32_t *>(fine.xadj), fine.adj, fine.mult, fine.map, n, nc, sentinel,
+                       keys, vals);
+  if (int rc = gosh::check_launch("make_keys_kernel")) return rc;
 
   if (int rc = buf.alloc(&keys_sorted, static_cast<size_t>(nnz), "sorted keys")) return rc;
   if (int rc = buf.alloc(&vals_sorted, static_cast<size_t>(nnz), "sorted values")) return rc;
@@ -305,20 +655,15 @@ int build_coarse_on_device(const gosh_csr &fine, const int64_t *mult_in, const i
     COARSE_HIP(hipDeviceSynchronize(), "radix sort");
     buf.release(temp);
   }
-  buf.release(keys);
-  buf.release(vals);
-  // distinct keys and their summed multiplicities
-  unsigned long long *count_d = nullptr;
-  if (int rc = buf.alloc(&count_d, 1, "distinct count")) return rc;
-  // at most one distinct key per fine entry; usually far fewer, but the count is only
-  // known afterwards
-  uint64_t *unique_keys = nullptr;
-  int64_t *sums = nullptr;
-  if (int rc = buf.alloc(&unique_keys, static_cast<size_t>(nnz), "distinct keys")) return rc;
-  if (int rc = buf.alloc(&sums, static_cast<size_t>(nnz), "merged multiplicities")) return rc;
+  // distinct keys and their summed multiplicities go where the unsorted ones were (at most
+  // one distinct key per fine entry; the count is only known afterwards)
+  uint64_t *unique_keys = keys;
+  int64_t *sums = vals;
+  unsigned long long *count_dev = nullptr;
+  if (int rc = buf.alloc(&count_dev, 1, "distinct count")) return rc;
   temp_bytes = 0;
   COARSE_HIP(rocprim::reduce_by_key(nullptr, temp_bytes, keys_sorted, vals_sorted, static_cast<size_t>(nnz),
-                                    unique_keys, sums, count_d, rocprim::plus<int64_t>(),
+                                    unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
                                     rocprim::equal_to<uint64_t>(), nullptr),
              "reduce by key (size query)");
   unsigned long long n_unique = 0;
@@ -326,10 +671,10 @@ int build_coarse_on_device(const gosh_csr &fine, const int64_t *mult_in, const i
     char *temp = nullptr;
     if (int rc = buf.alloc(&temp, temp_bytes, "reduce workspace")) return rc;
     COARSE_HIP(rocprim::reduce_by_key(temp, temp_bytes, keys_sorted, vals_sorted, static_cast<size_t>(nnz),
-                                      unique_keys, sums, count_d, rocprim::plus<int64_t>(),
+                                      unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
                                       rocprim::equal_to<uint64_t>(), nullptr),
                "reduce by key");
-    COARSE_HIP(hipMemcpy(&n_unique, count_d, sizeof(n_unique), hipMemcpyDeviceToHost), "copy distinct count");
+    COARSE_HIP(hipMemcpy(&n_unique, count_dev, sizeof(n_unique), hipMemcpyDeviceToHost), "copy distinct count");
     buf.release(temp);
   }
   buf.release(keys_sorted);
@@ -341,38 +686,18 @@ int build_coarse_on_device(const gosh_csr &fine, const int64_t *mult_in, const i
     if (last == sentinel) --n_unique;
   }
   const int64_t nnz_coarse = static_cast<int64_t>(n_unique);
-
-  adj_out.resize(static_cast<size_t>(nnz_coarse));
-  mult_out.resize(static_cast<size_t>(nnz_coarse));
-
-  int64_t *xadj_out_d = nullptr;
-  int32_t *adj_out_d = nullptr;
-  if (int rc = buf.alloc(&xadj_out_d, static_cast<size_t>(n_coarse) + 1, "coarse offsets")) return rc;
-  if (int rc = buf.alloc(&adj_out_d, static_cast<size_t>(nnz_coarse), "coarse adjacency")) return rc;
+  coarse.nnz = nnz_coarse;
+  if (int rc = persistent(&coarse.adj, static_cast<size_t>(nnz_coarse), "coarse adjacency")) return rc;
+  if (int rc = persistent(&coarse.mult, static_cast<size_t>(nnz_coarse), "coarse multiplicities")) return rc;
   hipLaunchKernelGGL(offsets_kernel, dim3(blocks_for(n_coarse + 1, 256)), dim3(256), 0, nullptr, unique_keys,
-                     nnz_coarse, nc, xadj_out_d);
+                     nnz_coarse, nc, xadj_out);
   if (int rc = gosh::check_launch("offsets_kernel")) return rc;
   if (nnz_coarse > 0) {
-    hipLaunchKernelGGL(columns_kernel, dim3(blocks_for(nnz_coarse, 256)), dim3(256), 0, nullptr, unique_keys,
-                       nnz_coarse, nc, adj_out_d);
+    hipLaunchKernelGGL(columns_kernel, dim3(blocks_for(nnz_coarse, 256)), dim3(256), 0, nullptr, unique_keys, sums,
+                       nnz_coarse, nc, coarse.adj, coarse.mult);
     if (int rc = gosh::check_launch("columns_kernel")) return rc;
   }
   COARSE_HIP(hipDeviceSynchronize(), "coarse CSR");
-  if (int rc = download(xadj_out.data(), xadj_out_d, (static_cast<size_t>(n_coarse) + 1) * 8, threads, carry)) return rc;
-  if (int rc = download(adj_out.data(), adj_out_d, static_cast<size_t>(nnz_coarse) * 4, threads, carry)) return rc;
-  if (int rc = download(mult_out.data(), sums, static_cast<size_t>(nnz_coarse) * 8, threads, carry)) return rc;
-  buf.release(unique_keys);
-  if (nnz_coarse > 0) {
-    // hand the coarse graph to the next level: these three buffers now belong to carry
-    carry->n = n_coarse;
-    carry->nnz = nnz_coarse;
-    carry->xadj = xadj_out_d;
-    carry->adj = adj_out_d;
-    carry->mult = sums;
-    buf.forget(xadj_out_d);
-    buf.forget(adj_out_d);
-    buf.forget(sums);
-  }
   return GOSH_OK;
 }
 

@@ -59,22 +59,52 @@ struct NoInitAlloc {
 template <typename T>
 using RawVector = std::vector<T, NoInitAlloc<T>>;
 
-// State one coarsening run keeps on the device between levels: the coarse graph of the
-// last level (the next level reads it there instead of uploading it again) and pinned
-// staging for the downloads.
-struct DeviceCarry;
-DeviceCarry *device_carry_new();
-void device_carry_free(DeviceCarry *);
+// One graph of the hierarchy in device memory (all arrays exact-sized hipMalloc blocks on
+// `device`; null when absent).
+struct DeviceLevel {
+  int device = -1;
+  int64_t n = 0, nnz = 0;
+  int32_t xadj_is64 = 1;
+  void *xadj = nullptr;     // n + 1 offsets
+  int32_t *adj = nullptr;   // nnz neighbours
+  int64_t *mult = nullptr;  // nnz multiplicities (coarse levels only)
+  int32_t *map = nullptr;   // n cluster ids (every level but the last)
+  bool present() const { return xadj != nullptr; }
+};
+void device_level_free(DeviceLevel &level);
 
-// "Coarsen(G_i, map_i)" on the current device: the quotient graph of the host graph
-// `fine` under `map` (entry (a, b), a != b, for every fine entry (x, y) with map[x] = a,
-// map[y] = b; parallel entries merged and their multiplicities added; rows ascending).
-// mult_in may be null (every fine entry counts once).  Outputs are host vectors.  If
-// `carry` holds the graph this very call sequence produced last (same n and nnz as
-// `fine`), it is used in place of the host arrays.
-int build_coarse_on_device(const gosh_csr &fine, const int64_t *mult_in, const int32_t *map,
-                           int64_t n_coarse, int threads, DeviceCarry *carry,
-                           RawVector<int64_t> &xadj_out, RawVector<int32_t> &adj_out,
-                           RawVector<int64_t> &mult_out);
+// State of one coarsening run: device blocks recycled over the levels and pinned staging
+// for downloads.
+struct DeviceCoarsener;
+DeviceCoarsener *device_coarsener_new(int threads);
+void device_coarsener_free(DeviceCoarsener *);
+// Returns the recycled device blocks; the staging stays (later downloads use it).
+void device_coarsener_trim(DeviceCoarsener *);
+
+// Copies a host graph to the current device.
+int device_level_upload(const gosh_csr &host, DeviceLevel &out);
+// Replaces level.map with a copy of the host array (n entries).
+int device_level_set_map(DeviceLevel &level, const int32_t *map_host);
+// Drops level.map.
+void device_level_drop_map(DeviceLevel &level);
+
+// The marking sweep of Alg. 4 on the device: writes fine.map and *n_coarse and sets *done.
+// Chains of equal-degree vertices can make the parallel resolution take too many rounds;
+// then *done is false, nothing was written, and the caller marks on the host.
+// *order_ms receives the time of the degree sort.
+int device_mark(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *done, double *order_ms);
+
+// "Coarsen(G_i, map_i)" on the device: the quotient graph of `fine` under fine.map (entry
+// (a, b), a != b, for every fine entry (x, y) with map[x] = a, map[y] = b; parallel entries
+// merged and their multiplicities added; rows ascending).
+int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coarse, DeviceLevel &coarse);
+
+// Device -> pageable host copy through the run's pinned staging, emptied by all threads.
+int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t bytes);
+
+// What the multilevel driver needs of a hierarchy without forcing host copies: the shape
+// of G_i (n, nnz, xadj_is64; pointers null) and its device copy (null if there is none).
+int hierarchy_shape(const gosh_hierarchy *h, int32_t i, gosh_csr *shape);
+const DeviceLevel *hierarchy_device_level(const gosh_hierarchy *h, int32_t i);
 
 }  // namespace gosh

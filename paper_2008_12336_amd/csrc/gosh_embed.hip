@@ -13,6 +13,7 @@
 #include <cstring>
 #include <vector>
 
+#include "gosh_coarsen_internal.h"
 #include "gosh_common.h"
 
 namespace {
@@ -106,9 +107,17 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
   const int32_t d = pl.d;
   std::vector<int64_t> e_i(static_cast<size_t>(D));
   if (int rc = gosh_epoch_split(epochs, p, D, e_i.data())) return rc;
+  // shapes only: the arrays of a level are fetched where the level is trained (a hierarchy
+  // built on the device has no host copies until someone asks)
   std::vector<gosh_csr> G(static_cast<size_t>(D));
   for (int i = 0; i < D; ++i)
-    if (int rc = gosh_hierarchy_graph(h, i, &G[static_cast<size_t>(i)])) return rc;
+    if (int rc = gosh::hierarchy_shape(h, i, &G[static_cast<size_t>(i)])) return rc;
+  int current_device = -1;
+  GOSH_HIP(hipGetDevice(&current_device), "hipGetDevice");
+  auto resident = [&](int i) -> const gosh::DeviceLevel * {
+    const gosh::DeviceLevel *dl = gosh::hierarchy_device_level(h, i);
+    return dl != nullptr && dl->device == current_device ? dl : nullptr;
+  };
   auto fits = [&](int i) {
     return pl.budget == 0 || level_bytes(G[static_cast<size_t>(i)], d) <= pl.budget;
   };
@@ -135,7 +144,7 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
   float *cur_dev = nullptr, *cur_host = nullptr;
 
   for (int i = D - 1; i >= 0; --i) {
-    const gosh_csr &g = G[static_cast<size_t>(i)];
+    gosh_csr &g = G[static_cast<size_t>(i)];
     const size_t mat_bytes = static_cast<size_t>(g.n) * d * 4;
     gosh_level_stats ls{};
     ls.level = i;
@@ -177,19 +186,27 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
     if (cur_dev) {
       // CopyToDevice(G_i) + TrainInGPU
       auto t0 = std::chrono::steady_clock::now();
-      const size_t off_bytes = static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4);
-      const size_t adj_bytes = static_cast<size_t>(g.nnz) * 4;
       DeviceBuffer xadj_dev, adj_dev;
-      if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
-      if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
-      GOSH_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
-      if (adj_bytes)
-        GOSH_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
-      GOSH_HIP(hipStreamSynchronize(st), "upload graph");
-      ls.upload_ms = ms_since(t0);
       gosh_csr dev = g;
-      dev.xadj = xadj_dev.ptr;
-      dev.adj = static_cast<const int32_t *>(adj_dev.ptr);
+      if (const gosh::DeviceLevel *dl = resident(i)) {
+        dev.xadj = dl->xadj;
+        dev.adj = dl->adj;
+        dev.xadj_is64 = dl->xadj_is64;
+      } else {
+        if (int rc = gosh_hierarchy_graph(h, i, &g)) return rc;
+        const size_t off_bytes = static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4);
+        const size_t adj_bytes = static_cast<size_t>(g.nnz) * 4;
+        if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
+        if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
+        GOSH_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
+        if (adj_bytes)
+          GOSH_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
+        GOSH_HIP(hipStreamSynchronize(st), "upload graph");
+        dev = g;
+        dev.xadj = xadj_dev.ptr;
+        dev.adj = static_cast<const int32_t *>(adj_dev.ptr);
+      }
+      ls.upload_ms = ms_since(t0);
       GOSH_HIP(hipEventRecord(ev0, st), "hipEventRecord");
       for (int64_t j = 0; j < ls.epochs; ++j) {
         const float lr = gosh_lr(pl.lr0, j, ls.epochs);
@@ -203,7 +220,8 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
       GOSH_HIP(hipEventElapsedTime(&ms, ev0, ev1), "hipEventElapsedTime");
       ls.train_ms = ms;
     } else {
-      // LargeGraphGPU
+      // LargeGraphGPU (its sampler reads the graph on the host)
+      if (int rc = gosh_hierarchy_graph(h, i, &g)) return rc;
       gosh_parts_stats ps{};
       if (int rc = gosh_train_parts(&g, cur_host, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed,
                                     static_cast<uint32_t>(i), pl.budget, pl.P_gpu, pl.S_gpu, pl.B, 0,
@@ -216,10 +234,14 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
     if (i > 0) {
       // ExpandEmbedding(M_i, map_{i-1})
       auto t0 = std::chrono::steady_clock::now();
-      const gosh_csr &fine = G[static_cast<size_t>(i - 1)];
+      const int64_t n_fine = G[static_cast<size_t>(i - 1)].n;
+      const gosh::DeviceLevel *fine_dev = resident(i - 1);
+      const int32_t *map_dev_resident = fine_dev ? fine_dev->map : nullptr;
       const int32_t *map_host = nullptr;
-      int64_t n_fine = 0;
-      if (int rc = gosh_hierarchy_map(h, i - 1, &map_host, &n_fine)) return rc;
+      if (map_dev_resident == nullptr) {
+        int64_t len = 0;
+        if (int rc = gosh_hierarchy_map(h, i - 1, &map_host, &len)) return rc;
+      }
       const size_t fine_bytes = static_cast<size_t>(n_fine) * d * 4;
       const bool next_on_dev = fits(i - 1);
       float *next_dev = nullptr, *next_host = nullptr;
@@ -236,36 +258,57 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
           next_host = static_cast<float *>(host_next.ptr);
         }
       }
-      if (cur_dev && next_dev) {
+      // A coarse matrix that lives on the host only because its GRAPH did not fit may
+      // still visit the device for the projection, which needs no graph.
+      const float *src_dev = cur_dev;
+      DeviceBuffer src_visit;
+      if (src_dev == nullptr && next_host != nullptr) {
+        const size_t smallest_slice = 64 * (static_cast<size_t>(d) * 4 + 4);
+        if (pl.budget == 0 || mat_bytes + smallest_slice <= pl.budget) {
+          if (int rc = src_visit.alloc(mat_bytes, "coarse embedding (projection)")) return rc;
+          GOSH_HIP(hipMemcpyAsync(src_visit.ptr, cur_host, mat_bytes, hipMemcpyHostToDevice, st),
+                   "upload coarse embedding");
+          src_dev = static_cast<const float *>(src_visit.ptr);
+        }
+      }
+      if (src_dev && next_dev) {
         DeviceBuffer map_dev;
-        if (int rc = map_dev.alloc(static_cast<size_t>(n_fine) * 4, "map")) return rc;
-        GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host, static_cast<size_t>(n_fine) * 4,
-                                hipMemcpyHostToDevice, st), "copy map");
-        if (int rc = gosh_project(cur_dev, g.n, static_cast<const int32_t *>(map_dev.ptr), n_fine, d,
-                                  next_dev, st))
-          return rc;
+        const int32_t *map_on_device = map_dev_resident;
+        if (map_on_device == nullptr) {
+          if (int rc = map_dev.alloc(static_cast<size_t>(n_fine) * 4, "map")) return rc;
+          GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host, static_cast<size_t>(n_fine) * 4,
+                                  hipMemcpyHostToDevice, st), "copy map");
+          map_on_device = static_cast<const int32_t *>(map_dev.ptr);
+        }
+        if (int rc = gosh_project(src_dev, g.n, map_on_device, n_fine, d, next_dev, st)) return rc;
         GOSH_HIP(hipStreamSynchronize(st), "project");
-      } else if (cur_dev && next_host) {
+      } else if (src_dev && next_host) {
         // project slice by slice through a device staging buffer
         int64_t rows = 0;
         if (int rc = chunk_rows(pl.budget, mat_bytes, d, n_fine, &rows)) return rc;
         DeviceBuffer slice, map_dev;
         if (int rc = slice.alloc(static_cast<size_t>(rows) * d * 4, "projection slice")) return rc;
-        if (int rc = map_dev.alloc(static_cast<size_t>(rows) * 4, "map slice")) return rc;
+        if (map_dev_resident == nullptr)
+          if (int rc = map_dev.alloc(static_cast<size_t>(rows) * 4, "map slice")) return rc;
         for (int64_t lo = 0; lo < n_fine; lo += rows) {
           const int64_t cnt = std::min(rows, n_fine - lo);
-          GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host + lo, static_cast<size_t>(cnt) * 4,
-                                  hipMemcpyHostToDevice, st), "copy map slice");
-          if (int rc = gosh_project(cur_dev, g.n, static_cast<const int32_t *>(map_dev.ptr), cnt, d,
-                                    static_cast<float *>(slice.ptr), st))
+          const int32_t *map_slice = map_dev_resident ? map_dev_resident + lo : static_cast<const int32_t *>(map_dev.ptr);
+          if (map_dev_resident == nullptr)
+            GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host + lo, static_cast<size_t>(cnt) * 4,
+                                    hipMemcpyHostToDevice, st), "copy map slice");
+          if (int rc = gosh_project(src_dev, g.n, map_slice, cnt, d, static_cast<float *>(slice.ptr), st))
             return rc;
           GOSH_HIP(hipMemcpyAsync(next_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4,
                                   hipMemcpyDeviceToHost, st), "copy projected slice");
           GOSH_HIP(hipStreamSynchronize(st), "project slice");
         }
       } else {
-        // the coarse matrix is on the host: gather its rows there (both levels exceed the
-        // budget), then upload if the finer level happens to fit
+        // the coarse matrix is on the host and too large to visit the device: gather its
+        // rows there, then upload if the finer level happens to fit
+        if (map_host == nullptr) {
+          int64_t len = 0;
+          if (int rc = gosh_hierarchy_map(h, i - 1, &map_host, &len)) return rc;
+        }
         float *target = next_host;
         PinnedBuffer temp;
         if (next_dev) {
@@ -282,7 +325,6 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
         }
       }
       ls.project_ms = ms_since(t0);
-      (void)fine;
       dev_own.swap(dev_next);
       dev_next.reset();
       host_own.swap(host_next);

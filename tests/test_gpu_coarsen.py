@@ -1,5 +1,6 @@
-"""gosh_coarsen_device (coarse CSR rebuilt on the GPU) against the oracle's Alg. 4 and
-against gosh_coarsen: the hierarchy is unique, so everything is compared bit for bit."""
+"""gosh_coarsen_device (Alg. 4 on the GPU: degree sort, marking rounds, CSR rebuild) against
+the oracle and against gosh_coarsen: the hierarchy is unique, so everything is compared
+bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -7,7 +8,7 @@ import torch
 import graphgen
 import paper_2008_12336_amd as G
 from oracle import gosh_oracle as O
-from tests.test_coarsen import assert_same_hierarchy
+from tests.test_coarsen import _ring_lattice, assert_same_hierarchy
 from tests.util import csr_from_pairs
 
 pytestmark = pytest.mark.gpu
@@ -79,3 +80,76 @@ def test_device_large_matches_host():
             assert np.array_equal(hh.map(i), hd.map(i))
     hh.free()
     hd.free()
+
+
+@pytest.mark.parametrize("name", ["path", "ring3", "uniform", "mixed"])
+def test_device_marking_with_long_dependency_chains(name):
+    """Graphs whose marking is one long chain (the rounds stall and the host sweep takes
+    over) or many short ones (resolved by the rounds) still give the sequential result."""
+    if name == "path":
+        n = 30000
+        xadj, adj = csr_from_pairs(n, [(i, i + 1) for i in range(n - 1)])
+    elif name == "ring3":
+        n = 20000
+        xadj, adj = _ring_lattice(n, 3)
+    elif name == "uniform":
+        n = 60000
+        c = graphgen.to_csr(n, graphgen.er_gnm(n, 4 * n, 11))
+        xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    else:
+        n = 50000
+        path = [(i, i + 1) for i in range(30000)]
+        c = graphgen.chung_lu(n, 120000, 12)
+        xadj, adj = csr_from_pairs(n, path + [tuple(e) for e in c.tolist()])
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=n // 2, min_shrink=1.0, max_levels=2)
+    h = device_hierarchy(n, xadj, adj, False, threshold=n // 2, min_shrink=1.0, max_levels=2)
+    assert_same_hierarchy(h, graphs, maps, mults)
+    h.free()
+
+
+def test_device_isolated_vertices_and_no_progress():
+    # only isolated vertices: nothing merges, the hierarchy keeps the one level and no map
+    xadj, adj = csr_from_pairs(10, [])
+    h = device_hierarchy(10, xadj, adj, False, threshold=1)
+    assert h.levels == 1
+    h.free()
+    # a star plus isolated vertices: one merge level, then no progress
+    xadj, adj = csr_from_pairs(12, [(0, i) for i in range(1, 6)])
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=1, min_shrink=1.0)
+    h = device_hierarchy(12, xadj, adj, True, threshold=1, min_shrink=1.0)
+    assert_same_hierarchy(h, graphs, maps, mults)
+    h.free()
+
+
+def test_release_device_keeps_everything_readable():
+    n = 4096
+    c = graphgen.to_csr(n, graphgen.rmat(12, 1 << 15, 2))
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=100, min_shrink=1.0)
+    h = G.gosh_coarsen_device(n, c.xadj, c.adj, threshold=100, min_shrink=1.0)
+    h.release_device()
+    assert_same_hierarchy(h, graphs, maps, mults)
+    # training from the released (host) copies still works and agrees with the oracle's shapes
+    M0 = torch.zeros(n, 16, dtype=torch.float32, device="cuda:0")
+    stats = G.gosh_embed(h, M0, 3, 12, 0.3, 0.05, 1, flags=G.GOSH_FLAG_SEQUENTIAL)
+    torch.cuda.synchronize()
+    assert [s["n"] for s in stats] == [g[0].size - 1 for g in graphs]
+    assert bool(torch.isfinite(M0).all())
+    h.release_device()  # idempotent
+    h.free()
+
+
+def test_device_rejects_malformed_graphs():
+    xadj, adj = csr_from_pairs(300, [(i, i + 1) for i in range(299)])
+    bad_adj = adj.copy()
+    bad_adj[7] = 300  # neighbour id out of range
+    with pytest.raises(G.GoshError, match="neighbour"):
+        device_hierarchy(300, xadj, bad_adj, False, threshold=10)
+    bad_x = xadj.copy()
+    bad_x[5] = bad_x[6] + 1  # offsets decrease
+    with pytest.raises(G.GoshError, match="xadj"):
+        device_hierarchy(300, bad_x, adj, False, threshold=10)
+    # the device is still usable afterwards
+    h = device_hierarchy(300, xadj, adj, False, threshold=10)
+    assert h.levels >= 2
+    h.free()

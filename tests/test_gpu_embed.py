@@ -20,17 +20,21 @@ def say(msg):
     sys.stdout.flush()
 
 
-def test_sequential_vcycle_matches_oracle():
+COARSENERS = {"host": G.gosh_coarsen, "device": G.gosh_coarsen_device}
+
+
+@pytest.mark.parametrize("where", sorted(COARSENERS))
+def test_sequential_vcycle_matches_oracle(where):
     n = 1 << 11
     c = graphgen.to_csr(n, graphgen.rmat(11, 1 << 14, 3))
     xadj, adj = c.xadj.numpy(), c.adj.numpy()
     d, k, epochs, p, lr0, seed = 32, 3, 12, 0.3, 0.05, 5
     want, graphs, maps, e_i = O.embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100,
                                       min_shrink=0.8)
-    h = G.gosh_coarsen(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
+    h = COARSENERS[where](n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
     assert h.levels == len(graphs) >= 3
     M0 = torch.zeros(n, d, dtype=torch.float32, device=DEV)
-    say(f"[vcycle] D={h.levels} sizes={[g[0].size - 1 for g in graphs]} epochs={e_i.tolist()}")
+    say(f"[vcycle {where}] D={h.levels} sizes={[g[0].size - 1 for g in graphs]} epochs={e_i.tolist()}")
     stats = G.gosh_embed(h, M0, k, epochs, p, lr0, seed, flags=G.GOSH_FLAG_SEQUENTIAL)
     torch.cuda.synchronize()
     assert [s["epochs"] for s in stats] == e_i.tolist()
@@ -80,8 +84,9 @@ def test_hogwild_vcycle_aucroc():
     assert abs(hg - ho) <= 0.01 and abs(fg - fo) <= 0.01
 
 
+@pytest.mark.parametrize("where", sorted(COARSENERS))
 @pytest.mark.parametrize("budget_kib,expect_parts", [(0, 0), (4096, 0), (300, 1), (200, 2), (64, 4)])
-def test_budgeted_vcycle_on_host_matches_oracle(budget_kib, expect_parts):
+def test_budgeted_vcycle_on_host_matches_oracle(budget_kib, expect_parts, where):
     """Alg. 2 with levels above the device budget trained by the rotation: sequential mode
     against the oracle's composition of Alg. 3 / Alg. 5 levels."""
     n = 1 << 11
@@ -91,7 +96,7 @@ def test_budgeted_vcycle_on_host_matches_oracle(budget_kib, expect_parts):
     budget = budget_kib * 1024
     want, modes = O.embed_budget(xadj, adj, d, k, epochs, p, lr0, seed,
                                  budget if budget else 1 << 40, threshold=100, min_shrink=0.8)
-    h = G.gosh_coarsen(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
+    h = COARSENERS[where](n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
     M0 = torch.zeros(n, d, dtype=torch.float32).pin_memory()
     stats = G.gosh_embed_host(h, M0, k, epochs, p, lr0, seed, flags=G.GOSH_FLAG_SEQUENTIAL,
                               device_budget_bytes=budget)
