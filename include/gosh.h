@@ -57,6 +57,13 @@ typedef struct {
 #define GOSH_FLAG_ATOMIC_ADDS 4u  /* concurrent mode: apply every update as atomic adds of
                                      the step (no update is ever lost; about 2x the cost) */
 
+/* gosh_embed / gosh_embed_host only */
+#define GOSH_FLAG_EDGE_EPOCHS 8u  /* an epoch is |E_i| sampled sources, the definition of the
+                                     paper's experiments (Sec. 4.2), not the |V_i| of Alg. 3:
+                                     level i runs e_i * ceil(|E_i| / |V_i|) passes of Alg. 3,
+                                     |E_i| = nnz_i / 2, and the learning rate decays over all
+                                     of them */
+
 const char *gosh_last_error(void);
 
 /* ---- schedule helpers (host, pure) ------------------------------------------------ */
@@ -190,7 +197,8 @@ int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map
 typedef struct {
   int32_t level;     /* i */
   int64_t n, nnz;    /* size of G_i */
-  int64_t epochs;    /* e_i */
+  int64_t epochs;    /* passes of Alg. 3 run on G_i: e_i, times ceil(|E_i|/|V_i|) with
+                        GOSH_FLAG_EDGE_EPOCHS */
   double upload_ms;  /* host -> device copy of G_i (wall clock) */
   double train_ms;   /* the e_i epoch launches (HIP events on the stream) */
   double project_ms; /* map upload + projection to level i-1 (wall clock; 0 at level 0) */
@@ -205,7 +213,7 @@ typedef struct {
  * counter, then (i > 0) project to level i-1 with map_{i-1}.  The paper prints the loop
  * as "D-1 to 1"; the text trains until M_0 is obtained, which is what is done here.
  * h: hierarchy (host).  M0_dev: device matrix n_0 x d, receives the embedding of G_0.
- * flags: as for gosh_train_epoch.  device_budget_bytes: if non-zero and the graph plus
+ * flags: as for gosh_train_epoch, plus GOSH_FLAG_EDGE_EPOCHS.  device_budget_bytes: if non-zero and the graph plus
  * matrix of level 0 exceed it, the call is refused with GOSH_EBUDGET (use gosh_embed_host,
  * which keeps such levels on the host).  stats: NULL or host array of D entries, filled per level.
  * Blocking: returns after the last level finished; intermediate device buffers are

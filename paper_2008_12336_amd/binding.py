@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libgosh.so")
 GOSH_FLAG_SEQUENTIAL = 1
 GOSH_FLAG_PLAIN_STORES = 2
 GOSH_FLAG_ATOMIC_ADDS = 4
+GOSH_FLAG_EDGE_EPOCHS = 8
 GOSH_MAX_DIM = 512
 GOSH_MAX_NEG = 15
 

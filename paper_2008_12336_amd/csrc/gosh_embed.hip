@@ -95,7 +95,8 @@ struct Plan {
   int32_t d, k_neg;
   float lr0;
   uint64_t seed;
-  uint32_t flags;
+  uint32_t flags;  // for the training calls (without GOSH_FLAG_EDGE_EPOCHS)
+  bool edge_epochs;
   uint64_t budget;
   int32_t P_gpu, S_gpu, B;
 };
@@ -151,6 +152,11 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
     ls.n = g.n;
     ls.nnz = g.nnz;
     ls.epochs = e_i[static_cast<size_t>(i)];
+    if (pl.edge_epochs) {
+      // an epoch of the experiments samples |E_i| sources; one pass of Alg. 3 samples |V_i|
+      const int64_t edges = g.nnz / 2;
+      ls.epochs *= std::max<int64_t>(1, (edges + g.n - 1) / g.n);
+    }
 
     if (i == D - 1) {
       // "Randomly initialize M_{D-1}"
@@ -361,7 +367,8 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
   if (int rc = check_common(d, k_neg)) return rc;
   if (int rc = gosh::check_matrix(M0_dev, d, "M0")) return rc;
   // A level above level 0 can only exceed the budget if level 0 does too, which is refused.
-  const Plan pl{d, k_neg, lr0, seed, flags, device_budget_bytes, 3, 4, 5};
+  const Plan pl{d, k_neg, lr0, seed, flags & ~GOSH_FLAG_EDGE_EPOCHS, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
+                device_budget_bytes, 3, 4, 5};
   return embed_impl(h, pl, epochs, p, M0_dev, nullptr, stats, gosh::as_stream(hip_stream));
 }
 
@@ -373,7 +380,8 @@ int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t e
   if (int rc = gosh::check_matrix(M0_host, d, "M0")) return rc;
   if (P_gpu < 2 || S_gpu < 1 || B < 1)
     return gosh::fail(GOSH_EINVAL, "need P_gpu >= 2, S_gpu >= 1, B >= 1");
-  const Plan pl{d, k_neg, lr0, seed, flags, device_budget_bytes, P_gpu, S_gpu, B};
+  const Plan pl{d, k_neg, lr0, seed, flags & ~GOSH_FLAG_EDGE_EPOCHS, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
+                device_budget_bytes, P_gpu, S_gpu, B};
   return embed_impl(h, pl, epochs, p, nullptr, M0_host, stats, gosh::as_stream(hip_stream));
 }
 

@@ -44,6 +44,28 @@ def test_sequential_vcycle_matches_oracle(where):
     assert err <= 1e-5
 
 
+def test_edge_epochs_vcycle_matches_oracle():
+    """GOSH_FLAG_EDGE_EPOCHS: an epoch samples |E_i| sources (the experiments' definition),
+    i.e. ceil(|E_i| / |V_i|) passes of Alg. 3, with the learning rate decaying over all."""
+    n = 1 << 10
+    c = graphgen.to_csr(n, graphgen.rmat(10, 1 << 14, 8))
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    d, k, epochs, p, lr0, seed = 16, 2, 6, 0.3, 0.05, 3
+    want, graphs, maps, passes = O.embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100,
+                                         min_shrink=0.8, edge_epochs=True)
+    plain = O.epoch_split(epochs, p, len(graphs))
+    assert any(int(a) > int(b) for a, b in zip(passes, plain))  # the flag changes something here
+    h = G.gosh_coarsen_device(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
+    M0 = torch.zeros(n, d, dtype=torch.float32, device=DEV)
+    stats = G.gosh_embed(h, M0, k, epochs, p, lr0, seed,
+                         flags=G.GOSH_FLAG_SEQUENTIAL | G.GOSH_FLAG_EDGE_EPOCHS)
+    torch.cuda.synchronize()
+    assert [s["epochs"] for s in stats] == [int(e) for e in passes]
+    err = rel_err(M0.cpu().numpy(), want)
+    say(f"[edge epochs] passes per level {[int(e) for e in passes]} (plain {plain.tolist()}) err {err:.2e}")
+    assert err <= 1e-5
+
+
 def test_single_level_hierarchy_and_budget():
     n = 300
     c = graphgen.to_csr(n, graphgen.er_gnm(n, 1500, 2))

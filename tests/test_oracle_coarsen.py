@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 from hypothesis import given, settings, strategies as st
 
+import graphgen
 from oracle import gosh_oracle as O
 from tests.util import csr_from_pairs, dense_from_csr
 
@@ -160,3 +161,37 @@ def test_epoch_split():
     assert O.epoch_split(7, 0.3, 1).tolist() == [7]
     with pytest.raises(ValueError):
         O.epoch_split(3, 0.3, 5)
+
+
+def test_passes_per_epoch_closed_forms():
+    """Sec. 4.2: an experiment epoch samples |E| sources, a pass of Alg. 3 |V|."""
+    from tests.util import csr_from_pairs
+    # complete graph K_n: |E| = n(n-1)/2, so ceil((n-1)/2) passes
+    for n in (2, 3, 4, 7, 10, 11):
+        x, a = csr_from_pairs(n, [(i, j) for i in range(n) for j in range(i)])
+        assert O.passes_per_epoch(x, a) == max(1, -(-(n - 1) // 2))
+    # a path has fewer edges than vertices, a cycle exactly as many: one pass
+    x, a = csr_from_pairs(9, [(i, i + 1) for i in range(8)])
+    assert O.passes_per_epoch(x, a) == 1
+    x, a = csr_from_pairs(9, [(i, (i + 1) % 9) for i in range(9)])
+    assert O.passes_per_epoch(x, a) == 1
+    # no edges: still one pass
+    x, a = csr_from_pairs(5, [])
+    assert O.passes_per_epoch(x, a) == 1
+    # in general: the smallest count that reaches |E| samples
+    c = graphgen.to_csr(500, graphgen.er_gnm(500, 4321, 3))
+    x, a = c.xadj.numpy(), c.adj.numpy()
+    passes, edges = O.passes_per_epoch(x, a), a.size // 2
+    assert passes * 500 >= edges > (passes - 1) * 500
+
+
+def test_embed_with_edge_epochs_runs_enough_samples():
+    c = graphgen.to_csr(1024, graphgen.rmat(10, 6000, 4))
+    x, a = c.xadj.numpy(), c.adj.numpy()
+    _, graphs, _, passes = O.embed(x, a, 8, 2, 6, 0.3, 0.05, 1, threshold=50, min_shrink=0.8,
+                                   edge_epochs=True)
+    e_i = O.epoch_split(6, 0.3, len(graphs))
+    for (gx, ga), run, e in zip(graphs, passes, e_i):
+        n, edges = gx.size - 1, ga.size // 2
+        assert run % e == 0
+        assert run * n >= e * edges and (run // e - 1) * n < max(edges, 1)
