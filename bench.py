@@ -289,7 +289,7 @@ def main() -> int:
     achieved = row_bytes_per_launch / avg_kernel_s / 1e9
     traffic = None if scaled else read_traffic(args.workload)
 
-    cpu = None
+    cpu = cpu_hogwild = None
     if args.cpu_seconds > 0:
         from oracle import gosh_oracle as O  # cpu_baseline leg only
 
@@ -307,6 +307,17 @@ def main() -> int:
         cpu = {"value": count * (k + 1) / dt, "unit": "samples/s", "cores": 1, "kind": "oracle",
                "sample": f"sources {probe}..{probe + count - 1} of one sequential epoch on the same "
                          f"graph and matrix ({count * (k + 1)} updates, {dt:.1f} s)"}
+        # the paper's own CPU baseline is the same loop, lock-free on all cores (Sec. 4.5)
+        threads = min(os.cpu_count() or 1, 16)
+        hog_count = int(min(n - probe, count * threads // 2))
+        t1 = time.perf_counter()
+        O.train_sources_hogwild(xadj_h, adj_h, M_h, k, 0.01, args.seed, total_epochs, 0, probe, hog_count,
+                                threads)
+        dt = time.perf_counter() - t1
+        cpu_hogwild = {"value": hog_count * (k + 1) / dt, "unit": "samples/s", "cores": threads,
+                       "kind": "oracle loop under an OpenMP parallel-for (Hogwild)",
+                       "sample": f"sources {probe}..{probe + hog_count - 1} of one epoch "
+                                 f"({hog_count * (k + 1)} updates, {dt:.1f} s)"}
         del M_h, xadj_h, adj_h
 
     out = {
@@ -332,6 +343,7 @@ def main() -> int:
                      "kernel_ms_min": float(np.min(kernel_ms)),
                      "algorithmic_bytes_per_launch": row_bytes_per_launch},
         "cpu_baseline": cpu,
+        "cpu_baseline_hogwild": cpu_hogwild,
     }
     print(json.dumps(out))
     return 0

@@ -1,4 +1,5 @@
-"""Compile the oracle (plain C++17, single-threaded) into oracle/libgosh_oracle.so."""
+"""Compile the oracle (plain C++17; OpenMP only for the Hogwild timing slice) into
+oracle/libgosh_oracle.so."""
 from __future__ import annotations
 
 import os
@@ -12,7 +13,7 @@ LIB = os.path.join(HERE, "libgosh_oracle.so")
 def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
-    cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-ffp-contract=off",
+    cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-fopenmp",
            "-Wall", "-Wextra", "-o", LIB, SRC]
     subprocess.run(cmd, check=True)
     return LIB

@@ -27,6 +27,10 @@
 //   pair order/parts  pinned (closed form, coverage invariants); the host/device
 //                     overlap of the parts driver has no numeric oracle:
 //                     "parity unpinned" for scheduling, pinned for results.
+//   hogwild slice     the one multi-threaded function (orc_train_sources_hogwild): the
+//                     sequential loop under a parallel-for, for timing the paper's
+//                     multi-core CPU baseline; no expected value is ever taken from it
+//                     (pinned only at threads = 1, where it is the sequential slice).
 
 #include <algorithm>
 #include <cmath>
@@ -150,6 +154,31 @@ void orc_train_sources(int64_t n, const int64_t *xadj, const int32_t *adj, float
       int64_t v = smp[j];
       if (v < 0 || v == src) continue;
       orc_update(M + src * d, M + v * d, d, j == 0 ? 1 : 0, lr_epoch);
+    }
+  }
+}
+
+// The same slice with the sources spread over `threads` OpenMP threads, lock-free
+// (Hogwild), as the paper's multi-core CPU baseline does (Sec. 4.5, the 16-thread CPU
+// runs).  Rows are updated concurrently without synchronisation, so the result depends on
+// the interleaving: this function is for TIMING a CPU baseline and for quality checks,
+// never an expected value.  With threads = 1 it is orc_train_sources.
+void orc_train_sources_hogwild(int64_t n, const int64_t *xadj, const int32_t *adj, float *M,
+                               int32_t d, int32_t k, float lr_epoch, uint64_t seed,
+                               uint32_t epoch, uint32_t level, int64_t first, int64_t count,
+                               int32_t threads) {
+  const int64_t last = first + count < n ? first + count : n;
+#pragma omp parallel num_threads(threads)
+  {
+    std::vector<int32_t> smp((size_t)k + 1);
+#pragma omp for schedule(static)
+    for (int64_t src = first; src < last; ++src) {
+      orc_sample_source(n, xadj, adj, k, seed, epoch, level, src, smp.data());
+      for (int32_t j = 0; j <= k; ++j) {
+        int64_t v = smp[j];
+        if (v < 0 || v == src) continue;
+        orc_update(M + src * d, M + v * d, d, j == 0 ? 1 : 0, lr_epoch);
+      }
     }
   }
 }

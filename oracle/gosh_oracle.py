@@ -47,6 +47,10 @@ def lib():
                                         C.c_float, C.c_uint64, C.c_uint32, C.c_uint32,
                                         C.c_int64, C.c_int64]
         L.orc_train_sources.restype = None
+        L.orc_train_sources_hogwild.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
+                                                C.c_float, C.c_uint64, C.c_uint32, C.c_uint32,
+                                                C.c_int64, C.c_int64, C.c_int32]
+        L.orc_train_sources_hogwild.restype = None
         L.orc_init_rows.argtypes = [f32p, C.c_int64, C.c_int64, C.c_int32, C.c_uint64,
                                     C.c_uint32]
         L.orc_init_rows.restype = None
@@ -150,6 +154,16 @@ def train_sources(xadj, adj, M, k, lr_epoch, seed, epoch, level, first, count):
     n, d = M.shape
     lib().orc_train_sources(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
                             lr_epoch, seed, epoch, level, first, count)
+
+
+def train_sources_hogwild(xadj, adj, M, k, lr_epoch, seed, epoch, level, first, count, threads):
+    """The same slice spread lock-free over `threads` threads (the paper's multi-core CPU
+    baseline): for timing and quality checks only, its result depends on the interleaving."""
+    xadj, adj = _csr(xadj, adj)
+    assert M.dtype == np.float32 and M.flags.c_contiguous
+    n, d = M.shape
+    lib().orc_train_sources_hogwild(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d,
+                                    k, lr_epoch, seed, epoch, level, first, count, threads)
 
 
 def init_rows(first, count, d, seed, level):

@@ -5,6 +5,7 @@ import os
 import numpy as np
 import pytest
 
+import graphgen
 from oracle import gosh_oracle as O
 from tests.util import csr_from_pairs
 
@@ -197,3 +198,24 @@ def test_training_separates_two_cliques():
     intra = (G[:size, :size].sum() - np.trace(G[:size, :size])) / (size * (size - 1))
     inter = G[:size, size:].mean()
     assert intra > inter + 0.5, (intra, inter)
+
+
+def test_hogwild_slice_is_the_sequential_slice_on_one_thread_and_sane_on_many():
+    """The multi-threaded slice exists for timing the paper's multi-core CPU baseline: at
+    one thread it must be the sequential slice bit for bit; at several it must still
+    learn (two cliques separate) although its values depend on the interleaving."""
+    n, edges = 64, graphgen.two_cliques(32)
+    c = graphgen.to_csr(n, edges)
+    xadj, adj = c.xadj.numpy().astype(np.int64), c.adj.numpy()
+    a = O.init_embedding(n, 16, 3, 0)
+    b = a.copy()
+    O.train_sources(xadj, adj, a, 3, 0.05, 3, 0, 0, 5, 40)
+    O.train_sources_hogwild(xadj, adj, b, 3, 0.05, 3, 0, 0, 5, 40, 1)
+    assert np.array_equal(a, b)
+    M = O.init_embedding(n, 16, 3, 0)
+    for j in range(300):
+        O.train_sources_hogwild(xadj, adj, M, 3, float(O.lr(0.05, j, 300)), 3, j, 0, 0, n, 4)
+    assert np.isfinite(M).all()
+    inside = np.mean([M[i] @ M[j] for i in range(0, 32, 3) for j in range(1, 32, 5) if i != j])
+    across = np.mean([M[i] @ M[32 + j] for i in range(0, 32, 3) for j in range(1, 32, 5)])
+    assert inside > across + 0.5
