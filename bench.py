@@ -307,7 +307,7 @@ def main() -> int:
         cpu = {"value": count * (k + 1) / dt, "unit": "samples/s", "cores": 1, "kind": "oracle",
                "sample": f"sources {probe}..{probe + count - 1} of one sequential epoch on the same "
                          f"graph and matrix ({count * (k + 1)} updates, {dt:.1f} s)"}
-        # the paper's own CPU baseline is the same loop, lock-free on all cores (Sec. 4.5)
+        # the paper's own CPU baseline is the same loop, lock-free on all cores (Sec. 4.8)
         threads = min(os.cpu_count() or 1, 16)
         hog_count = int(min(n - probe, count * threads // 2))
         t1 = time.perf_counter()

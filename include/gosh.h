@@ -59,7 +59,7 @@ typedef struct {
 
 /* gosh_embed / gosh_embed_host only */
 #define GOSH_FLAG_EDGE_EPOCHS 8u  /* an epoch is |E_i| sampled sources, the definition of the
-                                     paper's experiments (Sec. 4.2), not the |V_i| of Alg. 3:
+                                     paper's experiments (Sec. 4.3), not the |V_i| of Alg. 3:
                                      level i runs e_i * ceil(|E_i| / |V_i|) passes of Alg. 3,
                                      |E_i| = nnz_i / 2, and the learning rate decays over all
                                      of them */

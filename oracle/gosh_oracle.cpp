@@ -159,7 +159,7 @@ void orc_train_sources(int64_t n, const int64_t *xadj, const int32_t *adj, float
 }
 
 // The same slice with the sources spread over `threads` OpenMP threads, lock-free
-// (Hogwild), as the paper's multi-core CPU baseline does (Sec. 4.5, the 16-thread CPU
+// (Hogwild), as the paper's multi-core CPU baseline does (Sec. 4.8, the 16-thread CPU
 // runs).  Rows are updated concurrently without synchronisation, so the result depends on
 // the interleaving: this function is for TIMING a CPU baseline and for quality checks,
 // never an expected value.  With threads = 1 it is orc_train_sources.

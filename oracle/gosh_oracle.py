@@ -254,7 +254,7 @@ def coarsen(xadj, adj, threshold=100, min_shrink=0.8, max_levels=64):
 
 
 def passes_per_epoch(xadj, adj):
-    """Sec. 4.2 (experimental setup): the experiments call |E| sampled sources one epoch,
+    """Sec. 4.3 (experimental setup): the experiments call |E| sampled sources one epoch,
     while one pass of Alg. 3 samples |V|.  READING: the smallest whole number of passes
     that samples at least |E| = nnz/2 sources (at least one)."""
     n = xadj.size - 1
@@ -270,7 +270,7 @@ def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, 
     """Alg. 2: coarsen, initialise M_{D-1}, then for i = D-1..0 train e_i epochs on G_i and
     (i > 0) project to G_{i-1}.  READING: the printed loop bound "D-1 to 1" would never
     train G_0; the text trains until M_0 is obtained.  With edge_epochs an epoch is the
-    experiments' (Sec. 4.2): level i runs e_i * passes_per_epoch(G_i) passes of Alg. 3.
+    experiments' (Sec. 4.3): level i runs e_i * passes_per_epoch(G_i) passes of Alg. 3.
     Returns (M_0, graphs, maps, passes run per level)."""
     graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink, max_levels)
     D = len(graphs)

@@ -164,7 +164,7 @@ def test_epoch_split():
 
 
 def test_passes_per_epoch_closed_forms():
-    """Sec. 4.2: an experiment epoch samples |E| sources, a pass of Alg. 3 |V|."""
+    """Sec. 4.3: an experiment epoch samples |E| sources, a pass of Alg. 3 |V|."""
     from tests.util import csr_from_pairs
     # complete graph K_n: |E| = n(n-1)/2, so ceil((n-1)/2) passes
     for n in (2, 3, 4, 7, 10, 11):
