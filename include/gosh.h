@@ -101,8 +101,9 @@ typedef struct gosh_hierarchy gosh_hierarchy;
  * Levels are built while |V_i| > threshold (the paper's default is 100); building stops
  * after a level with |V_{i+1}| > min_shrink*|V_i| (that level is kept), at a level that
  * merged nothing (|V_{i+1}| == |V_i|: it would repeat G_i and is dropped), or when
- * max_levels graphs exist.  min_shrink in (0, 1]; 1.0 keeps only the no-progress guard.  n_threads <= 0 uses every available core (the result does not
- * depend on the thread count).
+ * max_levels graphs exist.  min_shrink in (0, 1]; 1.0 keeps only the no-progress guard.
+ * n_threads <= 0 uses every available core (the result does not depend on the thread
+ * count).
  * g0_host: host CSR, borrowed for the lifetime of the hierarchy (level 0 is a view of
  * it, not a copy).  *out receives the hierarchy; on failure it is NULL. */
 int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
@@ -127,6 +128,12 @@ int gosh_coarsen_device(const gosh_csr *g0_host, int64_t threshold, double min_s
  * (no-op for a host-built one).  Accessors and training keep working, from the host
  * copies.  Blocking. */
 int gosh_hierarchy_release_device(gosh_hierarchy *h);
+
+/* Accessors.  The arrays they hand out are host memory owned by the hierarchy (level 0:
+ * by the caller) and stay valid until gosh_hierarchy_free.  For a device-built hierarchy
+ * the first request for an array downloads it (blocking; the building device must be
+ * current; GOSH_EHIP / GOSH_ENOMEM possible), so a hierarchy must not be used from two
+ * threads at once. */
 
 /* D, the number of graphs G_0..G_{D-1} (0 for NULL). */
 int gosh_hierarchy_levels(const gosh_hierarchy *h);
