@@ -125,3 +125,41 @@ def test_full_size_hogwild_epoch_rows(big):
     say(f"[full] rows off by more than 2% of their own step: {bad}/{len(rows)} "
         f"(worst agreeing row: {worst_ok:.2e} of its step)")
     assert frac_bad <= 0.03
+
+
+def test_full_size_coarsening(big):
+    """Alg. 4 at the benchmark's size: the first map against the oracle's marking sweep
+    (bit-exact, 2^24 entries), the whole device-built hierarchy against the host-built one
+    (every graph, map and multiplicity), and weight conservation from level to level."""
+    n, csr, xadj, adj = big
+    xh, ah = csr.xadj.cpu(), csr.adj.cpu()
+    say("[full] coarsening on the device")
+    t = time.time()
+    hd = G.gosh_coarsen_device(n, xh, ah, threshold=100, min_shrink=0.8)
+    say(f"[full] device hierarchy: {hd.levels} levels in {time.time() - t:.2f}s")
+    t = time.time()
+    want_map, n_coarse = O.coarsen_map(xadj, adj)
+    say(f"[full] oracle marking sweep in {time.time() - t:.1f}s: {n_coarse} clusters")
+    assert hd.graph(1)[0] == n_coarse
+    assert np.array_equal(hd.map(0), want_map)
+    del want_map
+    t = time.time()
+    hh = G.gosh_coarsen(n, xh, ah, threshold=100, min_shrink=0.8)
+    say(f"[full] host hierarchy in {time.time() - t:.1f}s")
+    assert hh.levels == hd.levels >= 4
+    total = adj.size
+    for i in range(hh.levels):
+        nh, xa, aa = hh.graph(i)
+        nd, xb, ab = hd.graph(i)
+        assert nh == nd and np.array_equal(xa, xb) and np.array_equal(aa, ab), f"graph {i}"
+        if i > 0:
+            mult = hd.mult(i)
+            assert np.array_equal(hh.mult(i), mult), f"multiplicities {i}"
+            # entries swallowed by clusters only ever reduce the total weight
+            assert 0 < int(mult.sum()) <= total
+            total = int(mult.sum())
+        if i + 1 < hh.levels:
+            assert np.array_equal(hh.map(i), hd.map(i)), f"map {i}"
+    say(f"[full] device hierarchy == host hierarchy, sizes {[hd.graph(i)[0] for i in range(hd.levels)]}")
+    hh.free()
+    hd.free()
