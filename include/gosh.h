@@ -254,6 +254,8 @@ typedef struct {
   uint64_t bytes_d2h;    /* parts copied back */
   double kernel_ms;      /* sum of the pair kernels' durations (HIP events) */
   double wall_ms;        /* whole call, host wall clock */
+  double sampler_ms;     /* time the host sampler spent drawing positives (its own clock) */
+  double sampler_wait_ms; /* time the driving thread waited for a pool of positives */
 } gosh_parts_stats;
 
 /* Visiting order of the part pairs in one rotation (Sec. 3.3.1): (0,0), (1,0), (1,1),

@@ -42,7 +42,8 @@ class gosh_level_stats(C.Structure):
 class gosh_parts_stats(C.Structure):
     _fields_ = [("K", C.c_int32), ("rotations", C.c_int64), ("pair_visits", C.c_int64),
                 ("updates", C.c_int64), ("device_bytes", C.c_uint64), ("bytes_h2d", C.c_uint64),
-                ("bytes_d2h", C.c_uint64), ("kernel_ms", C.c_double), ("wall_ms", C.c_double)]
+                ("bytes_d2h", C.c_uint64), ("kernel_ms", C.c_double), ("wall_ms", C.c_double),
+                ("sampler_ms", C.c_double), ("sampler_wait_ms", C.c_double)]
 
 
 EXPORTS = {

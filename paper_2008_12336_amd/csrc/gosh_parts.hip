@@ -311,7 +311,10 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   std::vector<int32_t *> staging(NS, nullptr);
   uint32_t *hot_bits_dev = nullptr;
   hipStream_t compute = nullptr, copy = nullptr, copy_out = nullptr;
-  std::vector<hipEvent_t> slot_flushed(P, nullptr);
+  // A part swap runs in kSwapChunks pieces: piece c of the new part goes up as soon as piece
+  // c of the old one is down, so both directions of the host link are busy at once.
+  constexpr int kSwapChunks = 16;
+  std::vector<hipEvent_t> chunk_flushed(static_cast<size_t>(P) * kSwapChunks, nullptr);
   std::vector<hipEvent_t> slot_ready(P, nullptr), slot_used(P, nullptr), pool_ready(S, nullptr),
       pool_used(S, nullptr), staging_done(NS, nullptr);
   std::vector<hipEvent_t> k_begin, k_end;
@@ -323,6 +326,7 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   int64_t filled = 0;    // pools produced so far (visit indices [0, filled))
   int64_t released = 0;  // staging buffers given back (visit indices [0, released))
   bool stop = false;
+  double sampler_busy_ms = 0;  // written by the sampler thread only, read after it joined
   std::thread sampler;
 
   auto visit_pair = [&](int64_t vi, int32_t &a, int32_t &b, uint32_t &rot, uint32_t &q) {
@@ -341,7 +345,9 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     PARTS_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * d * 4), "hipMalloc part slot");
     PARTS_HIP(hipEventCreateWithFlags(&slot_ready[s], hipEventDisableTiming), "hipEventCreate");
     PARTS_HIP(hipEventCreateWithFlags(&slot_used[s], hipEventDisableTiming), "hipEventCreate");
-    PARTS_HIP(hipEventCreateWithFlags(&slot_flushed[s], hipEventDisableTiming), "hipEventCreate");
+    for (int c = 0; c < kSwapChunks; ++c)
+      PARTS_HIP(hipEventCreateWithFlags(&chunk_flushed[static_cast<size_t>(s) * kSwapChunks + c],
+                                        hipEventDisableTiming), "hipEventCreate");
   }
   for (int s = 0; s < S; ++s) {
     PARTS_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
@@ -406,11 +412,13 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       visit_pair(vi, a, b, rot, q);
       int32_t *buf = staging[vi % NS];
       const uint32_t w3 = level_word(level, q);
+      const auto t_fill = std::chrono::steady_clock::now();
       fill_pool(csr, L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, B, per_round, key0, key1,
                 rot, w3, host_threads, buf);
       if (a != b)
         fill_pool(csr, L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, B, per_round, key0, key1,
                   rot, w3, host_threads, buf + static_cast<size_t>(L.part_rows) * B);
+      sampler_busy_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_fill).count();
       {
         std::lock_guard<std::mutex> lock(mu);
         filled = vi + 1;
@@ -448,25 +456,43 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         if (nu > farthest) { farthest = nu; victim = s; }
       }
       if (victim < 0) return -1;
+      const size_t new_bytes = static_cast<size_t>(L.size(p)) * d * 4;
+      float *new_host = M_host + static_cast<int64_t>(L.lo(p)) * d;
       if (slot_part[victim] >= 0) {
-        // write the old part back on the outbound stream, then let the inbound stream reuse
-        // the slot; a later upload of the same part must also see these host bytes, which
-        // the inbound stream's wait on slot_flushed guarantees (it is recorded in order)
+        // Write the old part back on the outbound stream and bring the new one in on the
+        // inbound stream, piece by piece: the upload of a piece waits only for the
+        // write-back of the same bytes of the slot.  A later upload of the old part must
+        // see its host bytes; it is queued on the inbound stream after these waits, the
+        // last of which covers the whole write-back.
         const int32_t old = slot_part[victim];
-        const size_t bytes = static_cast<size_t>(L.size(old)) * d * 4;
+        const size_t old_bytes = static_cast<size_t>(L.size(old)) * d * 4;
+        float *old_host = M_host + static_cast<int64_t>(L.lo(old)) * d;
+        const size_t longest = std::max(old_bytes, new_bytes);
+        size_t piece = (longest + kSwapChunks - 1) / kSwapChunks;
+        piece = std::max<size_t>((piece + 255) / 256 * 256, size_t(8) << 20);
         if (hipStreamWaitEvent(copy_out, slot_used[victim], 0) != hipSuccess) return -2;
-        if (hipMemcpyAsync(M_host + static_cast<int64_t>(L.lo(old)) * d, slot[victim], bytes,
-                           hipMemcpyDeviceToHost, copy_out) != hipSuccess) return -2;
-        if (hipEventRecord(slot_flushed[victim], copy_out) != hipSuccess) return -2;
-        if (hipStreamWaitEvent(copy, slot_flushed[victim], 0) != hipSuccess) return -2;
-        st.bytes_d2h += bytes;
-      } else if (hipStreamWaitEvent(copy, slot_used[victim], 0) != hipSuccess) {
-        return -2;
+        char *slot_bytes = reinterpret_cast<char *>(slot[victim]);
+        int c = 0;
+        for (size_t off = 0; off < longest; off += piece, ++c) {
+          hipEvent_t flushed = chunk_flushed[static_cast<size_t>(victim) * kSwapChunks + c];
+          if (off < old_bytes) {
+            if (hipMemcpyAsync(reinterpret_cast<char *>(old_host) + off, slot_bytes + off,
+                               std::min(piece, old_bytes - off), hipMemcpyDeviceToHost, copy_out) != hipSuccess)
+              return -2;
+            if (hipEventRecord(flushed, copy_out) != hipSuccess) return -2;
+            if (hipStreamWaitEvent(copy, flushed, 0) != hipSuccess) return -2;
+          }
+          if (off < new_bytes &&
+              hipMemcpyAsync(slot_bytes + off, reinterpret_cast<const char *>(new_host) + off,
+                             std::min(piece, new_bytes - off), hipMemcpyHostToDevice, copy) != hipSuccess)
+            return -2;
+        }
+        st.bytes_d2h += old_bytes;
+      } else {
+        if (hipStreamWaitEvent(copy, slot_used[victim], 0) != hipSuccess) return -2;
+        if (hipMemcpyAsync(slot[victim], new_host, new_bytes, hipMemcpyHostToDevice, copy) != hipSuccess) return -2;
       }
-      const size_t bytes = static_cast<size_t>(L.size(p)) * d * 4;
-      if (hipMemcpyAsync(slot[victim], M_host + static_cast<int64_t>(L.lo(p)) * d, bytes,
-                         hipMemcpyHostToDevice, copy) != hipSuccess) return -2;
-      st.bytes_h2d += bytes;
+      st.bytes_h2d += new_bytes;
       if (hipEventRecord(slot_ready[victim], copy) != hipSuccess) return -2;
       slot_part[victim] = p;
       return victim;
@@ -500,8 +526,10 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       if (sa < 0 || sb < 0) { rc = gosh::fail(GOSH_EHIP, "internal: part not resident"); break; }
       // 2. the pool of this visit: wait for the sampler, upload on the copy stream
       {
+        const auto t_wait = std::chrono::steady_clock::now();
         std::unique_lock<std::mutex> lock(mu);
         cv.wait(lock, [&] { return filled > vi; });
+        st.sampler_wait_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_wait).count();
       }
       const int ps = static_cast<int>(vi % S), hs = static_cast<int>(vi % NS);
       PARTS_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
@@ -589,10 +617,11 @@ done:
   }
   cv.notify_all();
   if (sampler.joinable()) sampler.join();
+  st.sampler_ms = sampler_busy_ms;
   if (compute) (void)hipStreamSynchronize(compute);
   if (copy) (void)hipStreamSynchronize(copy);
   if (copy_out) (void)hipStreamSynchronize(copy_out);
-  for (auto e : slot_flushed) if (e) (void)hipEventDestroy(e);
+  for (auto e : chunk_flushed) if (e) (void)hipEventDestroy(e);
   for (auto e : k_begin) if (e) (void)hipEventDestroy(e);
   for (auto e : k_end) if (e) (void)hipEventDestroy(e);
   for (auto e : slot_ready) if (e) (void)hipEventDestroy(e);
