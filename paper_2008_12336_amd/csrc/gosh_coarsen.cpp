@@ -466,7 +466,7 @@ static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_s
     const bool wants_levels = g0_host->n > threshold && max_levels > 1;
     if (on_device && wants_levels) {
       h->dc = gosh::device_coarsener_new(threads);
-      if (int rc = gosh::device_level_upload(*g0_host, h->levels[0].dev)) {
+      if (int rc = gosh::device_level_upload(h->dc, *g0_host, h->levels[0].dev)) {
         delete h;
         return rc;
       }

@@ -377,7 +377,7 @@ void device_level_drop_map(DeviceLevel &level) {
   level.map = nullptr;
 }
 
-int device_level_upload(const gosh_csr &host, DeviceLevel &out) {
+int device_level_upload(DeviceCoarsener *dc, const gosh_csr &host, DeviceLevel &out) {
   device_level_free(out);
   COARSE_HIP(hipGetDevice(&out.device), "hipGetDevice");
   out.n = host.n;
@@ -388,10 +388,8 @@ int device_level_upload(const gosh_csr &host, DeviceLevel &out) {
   if (int rc = persistent(&offsets, off_bytes, "offsets")) return rc;
   out.xadj = offsets;
   if (int rc = persistent(&out.adj, static_cast<size_t>(host.nnz), "adjacency")) return rc;
-  COARSE_HIP(hipMemcpy(out.xadj, host.xadj, off_bytes, hipMemcpyHostToDevice), "copy offsets");
-  if (host.nnz > 0)
-    COARSE_HIP(hipMemcpy(out.adj, host.adj, static_cast<size_t>(host.nnz) * 4, hipMemcpyHostToDevice),
-               "copy adjacency");
+  if (int rc = device_upload(dc, out.xadj, host.xadj, off_bytes)) return rc;
+  if (int rc = device_upload(dc, out.adj, host.adj, static_cast<size_t>(host.nnz) * 4)) return rc;
   // the kernels follow offsets and neighbour ids without further checks
   int32_t *bad_dev = nullptr;
   if (int rc = persistent(&bad_dev, 1, "check flag")) return rc;
@@ -428,55 +426,101 @@ int device_level_set_map(DeviceLevel &level, const int32_t *map_host) {
   return GOSH_OK;
 }
 
-// Large copies go through two pinned slots: while one slot receives the next piece by DMA,
-// all threads copy the previous one to its place (which also spreads the page faults of a
-// fresh destination over the threads).
-int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t bytes) {
-  if (bytes == 0) return GOSH_OK;
-  if (dc == nullptr || bytes < 4 * DeviceCoarsener::kSlotBytes) {
-    COARSE_HIP(hipMemcpy(dst, src_dev, bytes, hipMemcpyDeviceToHost), "download");
+namespace {
+
+// Copies between pageable host memory and the device through two pinned slots, so that the
+// DMA of one piece overlaps the host-side copy of the next, which all threads share (on a
+// download that also spreads the page faults of a fresh destination over the threads).
+// The copy stream lives only for the call.
+struct StagedCopy {
+  DeviceCoarsener *dc;
+  hipStream_t stream = nullptr;
+  hipEvent_t done[2] = {nullptr, nullptr};  // the DMA that last used slot i
+  explicit StagedCopy(DeviceCoarsener *d) : dc(d) {}
+  ~StagedCopy() {
+    for (int i = 0; i < 2; ++i)
+      if (done[i]) (void)hipEventDestroy(done[i]);
+    if (stream) (void)hipStreamDestroy(stream);
+  }
+  int open() {
+    for (int i = 0; i < 2; ++i)
+      if (dc->slot[i] == nullptr) {
+        void *p = nullptr;
+        COARSE_HIP(hipHostMalloc(&p, DeviceCoarsener::kSlotBytes, hipHostMallocDefault), "allocate pinned staging");
+        dc->slot[i] = static_cast<char *>(p);
+      }
+    COARSE_HIP(hipStreamCreate(&stream), "create copy stream");
+    for (int i = 0; i < 2; ++i)
+      COARSE_HIP(hipEventCreateWithFlags(&done[i], hipEventDisableTiming), "create copy event");
     return GOSH_OK;
   }
-  for (int i = 0; i < 2; ++i)
-    if (dc->slot[i] == nullptr) {
-      void *p = nullptr;
-      COARSE_HIP(hipHostMalloc(&p, DeviceCoarsener::kSlotBytes, hipHostMallocDefault), "allocate pinned staging");
-      dc->slot[i] = static_cast<char *>(p);
-    }
-  struct CopyQueue {
-    hipStream_t stream = nullptr;
-    hipEvent_t landed[2] = {nullptr, nullptr};
-    ~CopyQueue() {
-      for (int i = 0; i < 2; ++i)
-        if (landed[i]) (void)hipEventDestroy(landed[i]);
-      if (stream) (void)hipStreamDestroy(stream);
-    }
-  } q;
-  COARSE_HIP(hipStreamCreate(&q.stream), "create copy stream");
-  for (int i = 0; i < 2; ++i)
-    COARSE_HIP(hipEventCreateWithFlags(&q.landed[i], hipEventDisableTiming), "create copy event");
-  const size_t slot_bytes = DeviceCoarsener::kSlotBytes;
-  const size_t pieces = (bytes + slot_bytes - 1) / slot_bytes;
-  auto piece_bytes = [&](size_t c) { return std::min(slot_bytes, bytes - c * slot_bytes); };
-  auto start = [&](size_t c) -> hipError_t {
-    hipError_t e = hipMemcpyAsync(dc->slot[c & 1], static_cast<const char *>(src_dev) + c * slot_bytes,
-                                  piece_bytes(c), hipMemcpyDeviceToHost, q.stream);
-    return e != hipSuccess ? e : hipEventRecord(q.landed[c & 1], q.stream);
-  };
-  COARSE_HIP(start(0), "start download");
-  for (size_t c = 0; c < pieces; ++c) {
-    // slot (c + 1) & 1 was emptied in the previous iteration
-    if (c + 1 < pieces) COARSE_HIP(start(c + 1), "start download");
-    COARSE_HIP(hipEventSynchronize(q.landed[c & 1]), "wait for download");
-    char *to = static_cast<char *>(dst) + c * slot_bytes;
-    const char *from = dc->slot[c & 1];
-    const int64_t len = static_cast<int64_t>(piece_bytes(c));
+  void host_copy(char *to, const char *from, size_t bytes) const {
+    const int64_t len = static_cast<int64_t>(bytes);
     const int64_t grain = int64_t(1) << 20;
     const int64_t grains = (len + grain - 1) / grain;
 #pragma omp parallel for num_threads(dc->threads) schedule(static)
     for (int64_t g = 0; g < grains; ++g)
       memcpy(to + g * grain, from + g * grain, static_cast<size_t>(std::min(grain, len - g * grain)));
   }
+};
+
+bool is_pinned_host(const void *p) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+    (void)hipGetLastError();  // plain pageable memory is unknown to the runtime
+    return false;
+  }
+  return attr.type == hipMemoryTypeHost;
+}
+
+}  // namespace
+
+int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t bytes) {
+  if (bytes == 0) return GOSH_OK;
+  if (dc == nullptr || bytes < 4 * DeviceCoarsener::kSlotBytes) {
+    COARSE_HIP(hipMemcpy(dst, src_dev, bytes, hipMemcpyDeviceToHost), "download");
+    return GOSH_OK;
+  }
+  StagedCopy q(dc);
+  if (int rc = q.open()) return rc;
+  const size_t slot_bytes = DeviceCoarsener::kSlotBytes;
+  const size_t pieces = (bytes + slot_bytes - 1) / slot_bytes;
+  auto piece_bytes = [&](size_t c) { return std::min(slot_bytes, bytes - c * slot_bytes); };
+  auto start = [&](size_t c) -> hipError_t {
+    hipError_t e = hipMemcpyAsync(dc->slot[c & 1], static_cast<const char *>(src_dev) + c * slot_bytes,
+                                  piece_bytes(c), hipMemcpyDeviceToHost, q.stream);
+    return e != hipSuccess ? e : hipEventRecord(q.done[c & 1], q.stream);
+  };
+  COARSE_HIP(start(0), "start download");
+  for (size_t c = 0; c < pieces; ++c) {
+    // slot (c + 1) & 1 was emptied in the previous iteration
+    if (c + 1 < pieces) COARSE_HIP(start(c + 1), "start download");
+    COARSE_HIP(hipEventSynchronize(q.done[c & 1]), "wait for download");
+    q.host_copy(static_cast<char *>(dst) + c * slot_bytes, dc->slot[c & 1], piece_bytes(c));
+  }
+  return GOSH_OK;
+}
+
+int device_upload(DeviceCoarsener *dc, void *dst_dev, const void *src, size_t bytes) {
+  if (bytes == 0) return GOSH_OK;
+  if (dc == nullptr || bytes < 4 * DeviceCoarsener::kSlotBytes || is_pinned_host(src)) {
+    COARSE_HIP(hipMemcpy(dst_dev, src, bytes, hipMemcpyHostToDevice), "upload");
+    return GOSH_OK;
+  }
+  StagedCopy q(dc);
+  if (int rc = q.open()) return rc;
+  const size_t slot_bytes = DeviceCoarsener::kSlotBytes;
+  const size_t pieces = (bytes + slot_bytes - 1) / slot_bytes;
+  for (size_t c = 0; c < pieces; ++c) {
+    const size_t len = std::min(slot_bytes, bytes - c * slot_bytes);
+    // the DMA of piece c - 2 must have drained this slot
+    if (c >= 2) COARSE_HIP(hipEventSynchronize(q.done[c & 1]), "wait for upload");
+    q.host_copy(dc->slot[c & 1], static_cast<const char *>(src) + c * slot_bytes, len);
+    COARSE_HIP(hipMemcpyAsync(static_cast<char *>(dst_dev) + c * slot_bytes, dc->slot[c & 1], len,
+                              hipMemcpyHostToDevice, q.stream), "upload piece");
+    COARSE_HIP(hipEventRecord(q.done[c & 1], q.stream), "record upload");
+  }
+  COARSE_HIP(hipStreamSynchronize(q.stream), "finish upload");
   return GOSH_OK;
 }
 

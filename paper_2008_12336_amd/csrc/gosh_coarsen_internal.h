@@ -81,8 +81,8 @@ void device_coarsener_free(DeviceCoarsener *);
 // Returns the recycled device blocks; the staging stays (later downloads use it).
 void device_coarsener_trim(DeviceCoarsener *);
 
-// Copies a host graph to the current device.
-int device_level_upload(const gosh_csr &host, DeviceLevel &out);
+// Copies a host graph to the current device and range-checks it there.
+int device_level_upload(DeviceCoarsener *dc, const gosh_csr &host, DeviceLevel &out);
 // Replaces level.map with a copy of the host array (n entries).
 int device_level_set_map(DeviceLevel &level, const int32_t *map_host);
 // Drops level.map.
@@ -99,8 +99,10 @@ int device_mark(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool 
 // merged and their multiplicities added; rows ascending).
 int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coarse, DeviceLevel &coarse);
 
-// Device -> pageable host copy through the run's pinned staging, emptied by all threads.
+// Copies between pageable host memory and the device through the run's pinned staging,
+// the host side of every piece shared by all threads.
 int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t bytes);
+int device_upload(DeviceCoarsener *dc, void *dst_dev, const void *src, size_t bytes);
 
 // What the multilevel driver needs of a hierarchy without forcing host copies: the shape
 // of G_i (n, nnz, xadj_is64; pointers null) and its device copy (null if there is none).
