@@ -144,3 +144,24 @@ def test_marking_with_long_dependency_chains(name):
         h = product_hierarchy(n, xadj, adj, False, threshold=n // 2, min_shrink=1.0, max_levels=2,
                               n_threads=threads)
         assert_same_hierarchy(h, graphs, maps, mults)
+
+
+def test_release_device_is_a_noop_for_a_host_built_hierarchy():
+    c = graphgen.to_csr(1024, graphgen.er_gnm(1024, 8192, 1))
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=100, min_shrink=1.0)
+    h = product_hierarchy(1024, xadj, adj, False, threshold=100, min_shrink=1.0)
+    h.release_device()
+    assert_same_hierarchy(h, graphs, maps, mults)
+    h.free()
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="checks the failure without a device")
+def test_device_coarsening_fails_loudly_without_a_device():
+    c = graphgen.to_csr(1024, graphgen.er_gnm(1024, 8192, 1))
+    with pytest.raises(G.GoshError):
+        G.gosh_coarsen_device(1024, c.xadj, c.adj, threshold=100)
+    # at or below the threshold there is nothing to do on the device
+    h = G.gosh_coarsen_device(1024, c.xadj, c.adj, threshold=5000)
+    assert h.levels == 1
+    h.free()
