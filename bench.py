@@ -84,7 +84,10 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     import paper_2008_12336_amd as G
 
     d, k = w["d"], w["k"]
-    xadj_h, adj_h = csr.xadj.cpu(), csr.adj.cpu()
+    if args.graph == "device" and args.coarsen == "device":
+        xadj_h, adj_h = csr.xadj, csr.adj  # stays where the generator left it
+    else:
+        xadj_h, adj_h = csr.xadj.cpu(), csr.adj.cpu()
     del csr
     release_generator_memory(torch)
     t0 = time.perf_counter()
@@ -128,7 +131,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
            "config": {"workload": args.workload + "_levels", "desc": w["desc"], "n": n,
                       "device_budget_bytes": budget, "finite": bool(torch.isfinite(M0[::4097]).all()),
                       "undirected_edges": n_edges, "d": d, "k_neg": k, "total_epochs": args.epochs,
-                      "coarsen": args.coarsen, "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
+                      "coarsen": args.coarsen, "graph": args.graph, "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
                       "levels": levels}}
     print(json.dumps(out))
     return 0
@@ -194,6 +197,8 @@ def main() -> int:
                          "rotation of the part-pair scheme under a device budget")
     ap.add_argument("--coarsen", default="device", choices=["device", "host"],
                     help="--mode levels: where the coarse graphs are rebuilt")
+    ap.add_argument("--graph", default="host", choices=["host", "device"],
+                    help="--mode levels with --coarsen device: where G_0 is handed over")
     ap.add_argument("--epochs", type=int, default=40, help="total epochs of --mode levels")
     ap.add_argument("--p-gpu", type=int, default=3, help="--mode parts: device slots for parts")
     ap.add_argument("--s-gpu", type=int, default=4, help="--mode parts: device sample pools")

@@ -112,8 +112,11 @@ int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
 /* MultiEdgeCollapse on the current HIP device: the same hierarchy, bit for bit (Alg. 4 has
  * one result), with the degree order a device radix sort, the marking sweep resolved in
  * parallel rounds, and "Coarsen" (the rebuild of the CSR of G_{i+1}, Sec. 3.2.1) a sort
- * and a reduction of (cluster, cluster) keys.  g0_host is uploaded once (offsets and
- * neighbour ids are range-checked on the device: GOSH_EINVAL); every level then STAYS on
+ * and a reduction of (cluster, cluster) keys.  g0 may be a host graph, which is uploaded
+ * once, or a graph already in the current device's memory (detected from the pointers),
+ * which is used where it is: in both cases it is borrowed for the lifetime of the
+ * hierarchy, and its offsets and neighbour ids are range-checked on the device
+ * (GOSH_EINVAL).  Every level then STAYS on
  * that device, where gosh_embed / gosh_embed_host read it without another upload, and the
  * host arrays behind gosh_hierarchy_graph / _map / _mult are downloaded on first request.
  * A graph whose marking does not resolve in a bounded number of rounds (long chains of
@@ -121,7 +124,7 @@ int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
  * of G_0 while running, 12 bytes per entry of all levels afterwards (until
  * gosh_hierarchy_release_device or gosh_hierarchy_free, called with the same device
  * current).  GOSH_ENOMEM / GOSH_EHIP if the device cannot.  Blocking; null stream. */
-int gosh_coarsen_device(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
+int gosh_coarsen_device(const gosh_csr *g0, int64_t threshold, double min_shrink,
                         int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
 
 /* Brings every array of a device-built hierarchy to the host and frees its device copies
@@ -137,6 +140,8 @@ int gosh_hierarchy_release_device(gosh_hierarchy *h);
 
 /* D, the number of graphs G_0..G_{D-1} (0 for NULL). */
 int gosh_hierarchy_levels(const gosh_hierarchy *h);
+/* |V_i| and the length of G_i's adj; either pointer may be NULL.  Never downloads. */
+int gosh_hierarchy_shape(const gosh_hierarchy *h, int32_t i, int64_t *n, int64_t *nnz);
 /* Borrowed host view of G_i (coarse levels have 64-bit offsets). */
 int gosh_hierarchy_graph(const gosh_hierarchy *h, int32_t i, gosh_csr *view);
 /* map_i: one entry per vertex of G_i, its super vertex in G_{i+1}; 0 <= i < D-1. */

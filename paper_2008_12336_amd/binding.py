@@ -57,6 +57,8 @@ EXPORTS = {
                                       C.c_int32, C.POINTER(C.c_void_p)]),
     "gosh_hierarchy_release_device": (C.c_int, [C.c_void_p]),
     "gosh_hierarchy_levels": (C.c_int, [C.c_void_p]),
+    "gosh_hierarchy_shape": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64),
+                                       C.POINTER(C.c_int64)]),
     "gosh_hierarchy_graph": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(gosh_csr)]),
     "gosh_hierarchy_map": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
                                      C.POINTER(C.c_int64)]),
@@ -217,6 +219,12 @@ class Hierarchy:
     def levels(self) -> int:
         return int(lib().gosh_hierarchy_levels(self._h))
 
+    def shape(self, i: int):
+        """(n, nnz) of G_i; never triggers a download."""
+        n, nnz = C.c_int64(), C.c_int64()
+        _check(lib().gosh_hierarchy_shape(self._h, i, C.byref(n), C.byref(nnz)))
+        return int(n.value), int(nnz.value)
+
     def graph_view(self, i: int) -> gosh_csr:
         v = gosh_csr()
         _check(lib().gosh_hierarchy_graph(self._h, i, C.byref(v)))
@@ -260,9 +268,12 @@ class Hierarchy:
         return np.ctypeslib.as_array(ptr, shape=(n.value,))
 
 
-def _coarsen(fn, n, xadj, adj, threshold, min_shrink, max_levels, n_threads) -> Hierarchy:
-    if xadj.is_cuda or adj.is_cuda:
-        raise TypeError("coarsening takes host (CPU) tensors")
+def _coarsen(fn, n, xadj, adj, threshold, min_shrink, max_levels, n_threads,
+             device_ok=False) -> Hierarchy:
+    if xadj.is_cuda != adj.is_cuda:
+        raise TypeError("xadj and adj must live on the same side")
+    if xadj.is_cuda and not device_ok:
+        raise TypeError("gosh_coarsen takes host (CPU) tensors")
     g = csr_view(n, xadj, adj)
     out = C.c_void_p()
     _check(fn(C.byref(g), threshold, min_shrink, max_levels, n_threads, C.byref(out)))
@@ -278,13 +289,18 @@ def gosh_coarsen(n: int, xadj: torch.Tensor, adj: torch.Tensor, threshold: int =
 def gosh_coarsen_device(n: int, xadj: torch.Tensor, adj: torch.Tensor, threshold: int = 100,
                         min_shrink: float = 1.0, max_levels: int = 64,
                         n_threads: int = 0) -> Hierarchy:
-    """Same hierarchy, with the CSR rebuild of every level done on the current device."""
+    """Same hierarchy, built on the current device, where every level then stays.  The
+    graph may be given as CPU tensors (uploaded once) or as tensors on that device."""
     return _coarsen(lib().gosh_coarsen_device, n, xadj, adj, threshold, min_shrink, max_levels,
-                    n_threads)
+                    n_threads, device_ok=True)
 
 
 def gosh_hierarchy_levels(h: Hierarchy) -> int:
     return h.levels
+
+
+def gosh_hierarchy_shape(h: Hierarchy, i: int):
+    return h.shape(i)
 
 
 def gosh_hierarchy_graph(h: Hierarchy, i: int):
@@ -315,7 +331,7 @@ def gosh_embed(h: Hierarchy, M0: torch.Tensor, k_neg: int, epochs: int, p: float
                seed: int, flags: int = 0, device_budget_bytes: int = 0, stream=None):
     """Multilevel training into the device matrix M0 (n_0 x d); returns per-level stats."""
     ptr, n0, d = _matrix(M0, "M0")
-    if n0 != h.graph_view(0).n:
+    if n0 != h.shape(0)[0]:
         raise ValueError("M0 must have one row per vertex of G_0")
     D = h.levels
     stats = (gosh_level_stats * D)()
@@ -337,7 +353,7 @@ def gosh_embed_host(h: Hierarchy, M0_host: torch.Tensor, k_neg: int, epochs: int
     if M0_host.is_cuda:
         raise TypeError("M0_host must be a host tensor")
     ptr, n0, d = _matrix(M0_host, "M0_host")
-    if n0 != h.graph_view(0).n:
+    if n0 != h.shape(0)[0]:
         raise ValueError("M0_host must have one row per vertex of G_0")
     D = h.levels
     stats = (gosh_level_stats * D)()

@@ -25,6 +25,7 @@ struct gosh_hierarchy {
     int64_t n = 0, nnz = 0;
     gosh_csr view{};  // host view, valid once host_graph is set
     gosh::RawVector<int64_t> xadj;
+    gosh::RawVector<int32_t> xadj32;  // host copy of a device-resident G_0 with 32-bit offsets
     gosh::RawVector<int32_t> adj;
     gosh::RawVector<int64_t> mult;  // fine entries merged into each entry (none at level 0)
     std::vector<int32_t> map;       // this level -> next coarser level (none on the last)
@@ -353,15 +354,24 @@ int64_t coarsen_level(gosh_hierarchy &h, int threads) {
 int ensure_host_graph(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
   if (l.host_graph) return GOSH_OK;
   if (!l.dev.present()) return gosh::fail(GOSH_EINVAL, "level has neither a host nor a device copy");
-  l.xadj.resize(static_cast<size_t>(l.n) + 1);
+  void *offsets = nullptr;
+  if (l.dev.xadj_is64) {
+    l.xadj.resize(static_cast<size_t>(l.n) + 1);
+    offsets = l.xadj.data();
+  } else {
+    l.xadj32.resize(static_cast<size_t>(l.n) + 1);
+    offsets = l.xadj32.data();
+  }
   l.adj.resize(static_cast<size_t>(l.nnz));
-  if (int rc = gosh::device_download(h.dc, l.xadj.data(), l.dev.xadj, (static_cast<size_t>(l.n) + 1) * 8)) return rc;
+  if (int rc = gosh::device_download(h.dc, offsets, l.dev.xadj,
+                                     (static_cast<size_t>(l.n) + 1) * (l.dev.xadj_is64 ? 8 : 4)))
+    return rc;
   if (int rc = gosh::device_download(h.dc, l.adj.data(), l.dev.adj, static_cast<size_t>(l.nnz) * 4)) return rc;
   l.view.n = l.n;
   l.view.nnz = l.nnz;
-  l.view.xadj = l.xadj.data();
+  l.view.xadj = offsets;
   l.view.adj = l.adj.data();
-  l.view.xadj_is64 = 1;
+  l.view.xadj_is64 = l.dev.xadj_is64;
   l.host_graph = true;
   return GOSH_OK;
 }
@@ -461,14 +471,28 @@ static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_s
     h->levels.emplace_back();
     h->levels[0].n = g0_host->n;
     h->levels[0].nnz = g0_host->nnz;
-    h->levels[0].view = *g0_host;
-    h->levels[0].host_graph = true;
+    const bool g0_on_device = on_device && gosh::is_device_pointer(g0_host->xadj);
     const bool wants_levels = g0_host->n > threshold && max_levels > 1;
-    if (on_device && wants_levels) {
+    if (g0_on_device) {
+      // a device-resident G_0 is adopted as it is; its host copy is made if someone asks
+      if (g0_host->nnz > 0 && !gosh::is_device_pointer(g0_host->adj)) {
+        delete h;
+        return gosh::fail(GOSH_EINVAL, "xadj is device memory but adj is not");
+      }
       h->dc = gosh::device_coarsener_new(threads);
-      if (int rc = gosh::device_level_upload(h->dc, *g0_host, h->levels[0].dev)) {
+      if (int rc = gosh::device_level_borrow(*g0_host, h->levels[0].dev)) {
         delete h;
         return rc;
+      }
+    } else {
+      h->levels[0].view = *g0_host;
+      h->levels[0].host_graph = true;
+      if (on_device && wants_levels) {
+        h->dc = gosh::device_coarsener_new(threads);
+        if (int rc = gosh::device_level_upload(h->dc, *g0_host, h->levels[0].dev)) {
+          delete h;
+          return rc;
+        }
       }
     }
     while (h->levels.back().n > threshold && static_cast<int32_t>(h->levels.size()) < max_levels) {
@@ -514,6 +538,15 @@ int gosh_coarsen_device(const gosh_csr *g0_host, int64_t threshold, double min_s
 }
 
 int gosh_hierarchy_levels(const gosh_hierarchy *h) { return h ? static_cast<int>(h->levels.size()) : 0; }
+
+int gosh_hierarchy_shape(const gosh_hierarchy *h, int32_t i, int64_t *n, int64_t *nnz) {
+  if (h == nullptr) return gosh::fail(GOSH_EINVAL, "null argument");
+  if (i < 0 || i >= static_cast<int32_t>(h->levels.size()))
+    return gosh::fail(GOSH_EINVAL, "level %d out of range [0, %zu)", i, h->levels.size());
+  if (n) *n = h->levels[static_cast<size_t>(i)].n;
+  if (nnz) *nnz = h->levels[static_cast<size_t>(i)].nnz;
+  return GOSH_OK;
+}
 
 int gosh_hierarchy_graph(const gosh_hierarchy *h, int32_t i, gosh_csr *view) {
   if (h == nullptr || view == nullptr) return gosh::fail(GOSH_EINVAL, "null argument");

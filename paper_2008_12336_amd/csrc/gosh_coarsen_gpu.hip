@@ -365,8 +365,8 @@ void device_coarsener_trim(DeviceCoarsener *dc) {
 }
 
 void device_level_free(DeviceLevel &level) {
-  if (level.xadj) (void)hipFree(level.xadj);
-  if (level.adj) (void)hipFree(level.adj);
+  if (level.xadj && !level.borrowed_graph) (void)hipFree(level.xadj);
+  if (level.adj && !level.borrowed_graph) (void)hipFree(level.adj);
   if (level.mult) (void)hipFree(level.mult);
   if (level.map) (void)hipFree(level.map);
   level = DeviceLevel();
@@ -390,7 +390,33 @@ int device_level_upload(DeviceCoarsener *dc, const gosh_csr &host, DeviceLevel &
   if (int rc = persistent(&out.adj, static_cast<size_t>(host.nnz), "adjacency")) return rc;
   if (int rc = device_upload(dc, out.xadj, host.xadj, off_bytes)) return rc;
   if (int rc = device_upload(dc, out.adj, host.adj, static_cast<size_t>(host.nnz) * 4)) return rc;
-  // the kernels follow offsets and neighbour ids without further checks
+  return device_level_check(out);
+}
+
+int device_level_borrow(const gosh_csr &on_device, DeviceLevel &out) {
+  device_level_free(out);
+  COARSE_HIP(hipGetDevice(&out.device), "hipGetDevice");
+  out.n = on_device.n;
+  out.nnz = on_device.nnz;
+  out.xadj_is64 = on_device.xadj_is64 ? 1 : 0;
+  out.xadj = const_cast<void *>(on_device.xadj);
+  out.adj = const_cast<int32_t *>(on_device.adj);
+  out.borrowed_graph = true;
+  return device_level_check(out);
+}
+
+bool is_device_pointer(const void *p) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+    (void)hipGetLastError();  // plain pageable memory is unknown to the runtime
+    return false;
+  }
+  return attr.type == hipMemoryTypeDevice;
+}
+
+// The kernels follow offsets and neighbour ids without further checks: verify them once.
+int device_level_check(const DeviceLevel &out) {
+  const gosh_csr host{out.n, out.nnz, out.xadj, out.adj, out.xadj_is64};
   int32_t *bad_dev = nullptr;
   if (int rc = persistent(&bad_dev, 1, "check flag")) return rc;
   struct FlagGuard {

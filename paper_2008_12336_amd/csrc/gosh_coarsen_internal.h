@@ -69,6 +69,7 @@ struct DeviceLevel {
   int32_t *adj = nullptr;   // nnz neighbours
   int64_t *mult = nullptr;  // nnz multiplicities (coarse levels only)
   int32_t *map = nullptr;   // n cluster ids (every level but the last)
+  bool borrowed_graph = false;  // xadj and adj belong to the caller (a device-resident G_0)
   bool present() const { return xadj != nullptr; }
 };
 void device_level_free(DeviceLevel &level);
@@ -83,6 +84,13 @@ void device_coarsener_trim(DeviceCoarsener *);
 
 // Copies a host graph to the current device and range-checks it there.
 int device_level_upload(DeviceCoarsener *dc, const gosh_csr &host, DeviceLevel &out);
+// Adopts a graph that already lives on the current device (not freed with the level) and
+// range-checks it.
+int device_level_borrow(const gosh_csr &on_device, DeviceLevel &out);
+// Offsets run from 0 to nnz without decreasing, neighbour ids lie in [0, n): GOSH_EINVAL if not.
+int device_level_check(const DeviceLevel &level);
+// True for memory allocated on a device (hipMalloc); false for host memory of any kind.
+bool is_device_pointer(const void *p);
 // Replaces level.map with a copy of the host array (n entries).
 int device_level_set_map(DeviceLevel &level, const int32_t *map_host);
 // Drops level.map.

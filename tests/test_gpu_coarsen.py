@@ -153,3 +153,35 @@ def test_device_rejects_malformed_graphs():
     h = device_hierarchy(300, xadj, adj, False, threshold=10)
     assert h.levels >= 2
     h.free()
+
+
+@pytest.mark.parametrize("offsets64", [False, True])
+def test_device_resident_input_graph(offsets64):
+    """G_0 given as device tensors is used in place (no upload), gives the same hierarchy,
+    and its host copy appears on request."""
+    n = 4096
+    c = graphgen.to_csr(n, graphgen.rmat(12, 1 << 15, 2), offsets64=offsets64)
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=100, min_shrink=0.8)
+    xd, ad = c.xadj.to("cuda:0"), c.adj.to("cuda:0")
+    h = G.gosh_coarsen_device(n, xd, ad, threshold=100, min_shrink=0.8)
+    # train first (nothing has been downloaded yet), then read everything back
+    want, _, _, _ = O.embed(xadj, adj, 16, 3, 12, 0.3, 0.05, 4, threshold=100, min_shrink=0.8)
+    M0 = torch.zeros(n, 16, dtype=torch.float32, device="cuda:0")
+    assert h.shape(0) == (n, adj.size) and h.shape(1)[0] == graphs[1][0].size - 1
+    stats = G.gosh_embed(h, M0, 3, 12, 0.3, 0.05, 4, flags=G.GOSH_FLAG_SEQUENTIAL)
+    torch.cuda.synchronize()
+    assert all(s["upload_ms"] < 5.0 for s in stats)
+    err = np.abs(M0.cpu().numpy() - want).max() / np.abs(want).max()
+    assert err <= 1e-5
+    assert_same_hierarchy(h, graphs, maps, mults)
+    n0, x0, a0 = h.graph(0)
+    assert x0.dtype == (np.int64 if offsets64 else np.int32)
+    h.release_device()  # the caller's device tensors stay the caller's
+    assert_same_hierarchy(h, graphs, maps, mults)
+    h.free()
+    assert torch.equal(xd.cpu(), c.xadj) and torch.equal(ad.cpu(), c.adj)
+    with pytest.raises(TypeError):
+        G.gosh_coarsen_device(n, xd, c.adj, threshold=100)
+    with pytest.raises(TypeError):
+        G.gosh_coarsen(n, xd, ad, threshold=100)
