@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void make_keys_kernel(const OffT *__restrict__
     for (int64_t e = begin + lane; e < end; e += 64) {
       const uint64_t b = static_cast<uint64_t>(map[adj[e]]);
       keys[e] = a != b ? a * n_coarse + b : sentinel;
-      vals[e] = mult_in ? mult_in[e] : 1;
+      if (mult_in) vals[e] = mult_in[e];  // without multiplicities every entry counts once
     }
   }
 }
@@ -695,10 +695,14 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
   }
 
   Buffers buf(dc->pool);
+  // G_0 carries no multiplicities (every entry counts once): its keys are sorted alone and
+  // the reduction adds a constant 1 per key, which halves the bytes the sort moves.
+  const bool weighted = fine.mult != nullptr;
   uint64_t *keys = nullptr, *keys_sorted = nullptr;
   int64_t *vals = nullptr, *vals_sorted = nullptr;
   if (int rc = buf.alloc(&keys, static_cast<size_t>(nnz), "keys")) return rc;
-  if (int rc = buf.alloc(&vals, static_cast<size_t>(nnz), "values")) return rc;
+  if (weighted)
+    if (int rc = buf.alloc(&vals, static_cast<size_t>(nnz), "values")) return rc;
   const int key_blocks = blocks_for(n, 4);  // four wavefronts (rows) per block
   if (fine.xadj_is64)
     hipLaunchKernelGGL(make_keys_kernel<int64_t>, dim3(key_blocks), dim3(256), 0, nullptr,
@@ -711,44 +715,63 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
   if (int rc = gosh::check_launch("make_keys_kernel")) return rc;
 
   if (int rc = buf.alloc(&keys_sorted, static_cast<size_t>(nnz), "sorted keys")) return rc;
-  if (int rc = buf.alloc(&vals_sorted, static_cast<size_t>(nnz), "sorted values")) return rc;
+  if (weighted)
+    if (int rc = buf.alloc(&vals_sorted, static_cast<size_t>(nnz), "sorted values")) return rc;
   size_t temp_bytes = 0;
-  COARSE_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, vals, vals_sorted,
-                                       static_cast<size_t>(nnz), 0u, end_bit, nullptr),
-             "radix sort (size query)");
+  if (weighted)
+    COARSE_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, vals, vals_sorted,
+                                         static_cast<size_t>(nnz), 0u, end_bit, nullptr),
+               "radix sort (size query)");
+  else
+    COARSE_HIP(rocprim::radix_sort_keys(nullptr, temp_bytes, keys, keys_sorted, static_cast<size_t>(nnz), 0u,
+                                        end_bit, nullptr),
+               "radix sort (size query)");
   {
     char *temp = nullptr;
     if (int rc = buf.alloc(&temp, temp_bytes, "sort workspace")) return rc;
-    COARSE_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, vals, vals_sorted,
-                                         static_cast<size_t>(nnz), 0u, end_bit, nullptr),
-               "radix sort");
+    if (weighted)
+      COARSE_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, vals, vals_sorted,
+                                           static_cast<size_t>(nnz), 0u, end_bit, nullptr),
+                 "radix sort");
+    else
+      COARSE_HIP(rocprim::radix_sort_keys(temp, temp_bytes, keys, keys_sorted, static_cast<size_t>(nnz), 0u,
+                                          end_bit, nullptr),
+                 "radix sort");
     COARSE_HIP(hipDeviceSynchronize(), "radix sort");
     buf.release(temp);
   }
-  // distinct keys and their summed multiplicities go where the unsorted ones were (at most
-  // one distinct key per fine entry; the count is only known afterwards)
+  // distinct keys go where the unsorted ones were (at most one distinct key per fine entry;
+  // the count is only known afterwards), their summed multiplicities beside them
   uint64_t *unique_keys = keys;
   int64_t *sums = vals;
+  if (!weighted)
+    if (int rc = buf.alloc(&sums, static_cast<size_t>(nnz), "merged multiplicities")) return rc;
   unsigned long long *count_dev = nullptr;
   if (int rc = buf.alloc(&count_dev, 1, "distinct count")) return rc;
-  temp_bytes = 0;
-  COARSE_HIP(rocprim::reduce_by_key(nullptr, temp_bytes, keys_sorted, vals_sorted, static_cast<size_t>(nnz),
-                                    unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
-                                    rocprim::equal_to<uint64_t>(), nullptr),
-             "reduce by key (size query)");
   unsigned long long n_unique = 0;
-  {
+  auto reduce = [&](auto values_in) -> int {
+    size_t bytes = 0;
+    COARSE_HIP(rocprim::reduce_by_key(nullptr, bytes, keys_sorted, values_in, static_cast<size_t>(nnz),
+                                      unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
+                                      rocprim::equal_to<uint64_t>(), nullptr),
+               "reduce by key (size query)");
     char *temp = nullptr;
-    if (int rc = buf.alloc(&temp, temp_bytes, "reduce workspace")) return rc;
-    COARSE_HIP(rocprim::reduce_by_key(temp, temp_bytes, keys_sorted, vals_sorted, static_cast<size_t>(nnz),
+    if (int rc = buf.alloc(&temp, bytes, "reduce workspace")) return rc;
+    COARSE_HIP(rocprim::reduce_by_key(temp, bytes, keys_sorted, values_in, static_cast<size_t>(nnz),
                                       unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
                                       rocprim::equal_to<uint64_t>(), nullptr),
                "reduce by key");
     COARSE_HIP(hipMemcpy(&n_unique, count_dev, sizeof(n_unique), hipMemcpyDeviceToHost), "copy distinct count");
     buf.release(temp);
+    return GOSH_OK;
+  };
+  if (weighted) {
+    if (int rc = reduce(static_cast<const int64_t *>(vals_sorted))) return rc;
+  } else {
+    if (int rc = reduce(rocprim::constant_iterator<int64_t>(1))) return rc;
   }
   buf.release(keys_sorted);
-  buf.release(vals_sorted);
+  if (vals_sorted) buf.release(vals_sorted);
   // entries inside clusters collapse into one sentinel key, the largest: drop it
   if (n_unique > 0) {
     uint64_t last = 0;
