@@ -17,6 +17,8 @@
 // their multiplicities followed by a reduction of equal keys leaves exactly the distinct
 // coarse entries, in row-major ascending order, with the merged multiplicities -- the
 // same arrays the host implementation produces, since sorted distinct keys are unique.
+// The keys are made one thread per entry (the row of an entry is found by a search that a
+// block narrows to the few rows it spans), so hub rows are no long tail.
 //
 // Sort, scan and reduce-by-key are rocPRIM device primitives; the kernels around them
 // are here.  Everything runs on the null stream and the calls block.
@@ -194,24 +196,46 @@ __global__ __launch_bounds__(256) void check_neighbours_kernel(const int32_t *__
     if (adj[e] < 0 || adj[e] >= n) *bad = 1;
 }
 
-// One wavefront per fine row: lanes stride over the row's entries (coalesced reads).
+// Largest row r in [lo, hi] with xadj[r] <= e, i.e. the row that holds entry e (empty rows
+// share their offset with the next row and are skipped).
+template <typename OffT>
+__device__ inline int64_t row_of_entry(const OffT *__restrict__ xadj, int64_t lo, int64_t hi, int64_t e) {
+  while (lo < hi) {
+    const int64_t mid = lo + (hi - lo + 1) / 2;
+    if (static_cast<int64_t>(xadj[mid]) <= e) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+
+// One thread per fine entry, kKeysPerBlock consecutive entries per block: the block first
+// finds the rows of its first and last entry, then every thread searches only between
+// them (a handful of rows; none at all inside a hub's row), so hubs and short rows cost
+// the same per entry and all accesses to adj, keys and vals are coalesced.
+constexpr int kKeysPerBlock = 4096;
 template <typename OffT>
 __global__ __launch_bounds__(256) void make_keys_kernel(const OffT *__restrict__ xadj,
                                                         const int32_t *__restrict__ adj,
                                                         const int64_t *__restrict__ mult_in,
                                                         const int32_t *__restrict__ map, int64_t n,
-                                                        uint64_t n_coarse, uint64_t sentinel,
+                                                        int64_t nnz, uint64_t n_coarse, uint64_t sentinel,
                                                         uint64_t *__restrict__ keys,
                                                         int64_t *__restrict__ vals) {
-  const int lane = threadIdx.x & 63;
-  for (int64_t x = first_wave(); x < n; x += wave_count()) {
-    const uint64_t a = static_cast<uint64_t>(map[x]);
-    const int64_t begin = static_cast<int64_t>(xadj[x]), end = static_cast<int64_t>(xadj[x + 1]);
-    for (int64_t e = begin + lane; e < end; e += 64) {
+  __shared__ int64_t span[2];
+  for (int64_t e0 = static_cast<int64_t>(blockIdx.x) * kKeysPerBlock; e0 < nnz;
+       e0 += static_cast<int64_t>(gridDim.x) * kKeysPerBlock) {
+    const int64_t e_last = min(e0 + kKeysPerBlock, nnz) - 1;
+    if (threadIdx.x < 2) span[threadIdx.x] = row_of_entry(xadj, 0, n - 1, threadIdx.x == 0 ? e0 : e_last);
+    __syncthreads();
+    const int64_t row_lo = span[0], row_hi = span[1];
+    for (int64_t e = e0 + threadIdx.x; e <= e_last; e += 256) {
+      const int64_t x = row_of_entry(xadj, row_lo, row_hi, e);
+      const uint64_t a = static_cast<uint64_t>(map[x]);
       const uint64_t b = static_cast<uint64_t>(map[adj[e]]);
       keys[e] = a != b ? a * n_coarse + b : sentinel;
       if (mult_in) vals[e] = mult_in[e];  // without multiplicities every entry counts once
     }
+    __syncthreads();  // span is rewritten in the next round
   }
 }
 
@@ -703,15 +727,15 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
   if (int rc = buf.alloc(&keys, static_cast<size_t>(nnz), "keys")) return rc;
   if (weighted)
     if (int rc = buf.alloc(&vals, static_cast<size_t>(nnz), "values")) return rc;
-  const int key_blocks = blocks_for(n, 4);  // four wavefronts (rows) per block
+  const int key_blocks = blocks_for(nnz, kKeysPerBlock);
   if (fine.xadj_is64)
     hipLaunchKernelGGL(make_keys_kernel<int64_t>, dim3(key_blocks), dim3(256), 0, nullptr,
-                       static_cast<const int64_t *>(fine.xadj), fine.adj, fine.mult, fine.map, n, nc, sentinel,
-                       keys, vals);
+                       static_cast<const int64_t *>(fine.xadj), fine.adj, fine.mult, fine.map, n, nnz, nc,
+                       sentinel, keys, vals);
   else
     hipLaunchKernelGGL(make_keys_kernel<int32_t>, dim3(key_blocks), dim3(256), 0, nullptr,
-                       static_cast<const int32_t *>(fine.xadj), fine.adj, fine.mult, fine.map, n, nc, sentinel,
-                       keys, vals);
+                       static_cast<const int32_t *>(fine.xadj), fine.adj, fine.mult, fine.map, n, nnz, nc,
+                       sentinel, keys, vals);
   if (int rc = gosh::check_launch("make_keys_kernel")) return rc;
 
   if (int rc = buf.alloc(&keys_sorted, static_cast<size_t>(nnz), "sorted keys")) return rc;
