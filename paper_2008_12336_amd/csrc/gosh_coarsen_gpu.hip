@@ -282,9 +282,12 @@ struct Pool {
     blocks.clear();
   }
   void *take(size_t bytes) {
+    // best fit, but a small request never occupies a block that a large one will want
+    const size_t too_big = std::max<size_t>(bytes * 8, size_t(64) << 20);
     Block *best = nullptr;
     for (Block &b : blocks)
-      if (!b.busy && b.bytes >= bytes && (best == nullptr || b.bytes < best->bytes)) best = &b;
+      if (!b.busy && b.bytes >= bytes && b.bytes <= too_big && (best == nullptr || b.bytes < best->bytes))
+        best = &b;
     if (best != nullptr) {
       best->busy = true;
       return best->p;
