@@ -107,7 +107,7 @@ template <typename OffT>
 __global__ __launch_bounds__(256) void round_kernel(const OffT *__restrict__ xadj,
                                                     const int32_t *__restrict__ adj,
                                                     const uint32_t *__restrict__ rk,
-                                                    int32_t *__restrict__ status,
+                                                    int32_t *status,  // shared with other waves
                                                     const int32_t *__restrict__ pending, int64_t count,
                                                     int32_t *__restrict__ still,
                                                     unsigned long long *__restrict__ still_count) {
