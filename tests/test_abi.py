@@ -98,3 +98,18 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.gosh_project(ok_ptr, 0, 0x3000, 5, 32, ok_ptr * 2, None) == -1  # empty coarse level
     assert lib.gosh_project(ok_ptr, 5, 0, 10, 32, ok_ptr * 2, None) == -1
     assert lib.gosh_epoch_split(10, 0.5, 3, None) == -1
+
+
+def test_header_is_plain_c():
+    """include/gosh.h must compile as C99 on its own (the boundary is a C ABI)."""
+    import subprocess
+    import tempfile
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    with tempfile.TemporaryDirectory() as tmp:
+        src = os.path.join(tmp, "use_header.c")
+        with open(src, "w") as fh:
+            fh.write('#include "gosh.h"\nint main(void) { gosh_level_stats s; gosh_parts_stats p; '
+                     "gosh_csr g; (void)s; (void)p; (void)g; return gosh_hierarchy_levels(0); }\n")
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(root, "include"), src], check=True)
