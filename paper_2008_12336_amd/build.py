@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgosh.so")
 
-SOURCES = ["gosh_host.cpp", "gosh_coarsen.cpp", "gosh_coarsen_gpu.hip", "gosh_train.hip", "gosh_embed.hip", "gosh_parts.hip"]
+SOURCES = ["gosh_host.cpp", "gosh_coarsen.cpp", "gosh_sampler.cpp", "gosh_coarsen_gpu.hip", "gosh_train.hip", "gosh_embed.hip", "gosh_parts.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950",

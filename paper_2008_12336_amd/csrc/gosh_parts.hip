@@ -21,6 +21,7 @@
 #include <vector>
 
 #include "gosh_common.h"
+#include "gosh_sampler.h"
 #include "gosh_device.h"
 
 namespace {
@@ -94,34 +95,6 @@ struct HostCsr {
     return g->xadj_is64 ? static_cast<const int64_t *>(g->xadj)[v] : static_cast<const int32_t *>(g->xadj)[v];
   }
 };
-
-// Positives of the sources of part [lo, lo+cnt) against the partner range [olo, ohi): for
-// round r a uniform member of the source's neighbours inside the partner range, -1 if it
-// has none there (Sec. 3.3).  Neighbour lists are ascending, so the candidates are one
-// contiguous run found by two binary searches.
-void fill_pool(const HostCsr &csr, int32_t lo, int32_t cnt, int32_t olo, int32_t ohi, int side,
-               int32_t B, int32_t per_round, uint32_t key0, uint32_t key1, uint32_t rotation,
-               uint32_t word3, int threads, int32_t *pool) {
-  const int32_t *adj = csr.g->adj;
-#pragma omp parallel for num_threads(threads) schedule(dynamic, 1024)
-  for (int32_t local = 0; local < cnt; ++local) {
-    const int64_t src = static_cast<int64_t>(lo) + local;
-    const int32_t *row_begin = adj + csr.begin(src), *row_end = adj + csr.begin(src + 1);
-    const int32_t *first = std::lower_bound(row_begin, row_end, olo);
-    const int32_t *last = std::lower_bound(first, row_end, ohi);
-    const uint32_t candidates = static_cast<uint32_t>(last - first);
-    for (int32_t r = 0; r < B; ++r) {
-      int32_t pick = -1;
-      if (candidates > 0) {
-        const uint64_t draw = philox_draw(static_cast<uint32_t>(src),
-                                          static_cast<uint32_t>(side * B * per_round + r * per_round),
-                                          rotation, word3, key0, key1);
-        pick = first[scale_draw(draw, candidates)];
-      }
-      pool[static_cast<int64_t>(local) * B + r] = pick;
-    }
-  }
-}
 
 struct Layout {
   int64_t n;
@@ -224,7 +197,6 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
   if (B < 1 || B > 64 || k_neg < 0 || k_neg > GOSH_MAX_NEG || out_host == nullptr)
     return gosh::fail(GOSH_EINVAL, "bad B, k_neg or output pointer");
   const Layout L{g_host->n, K, (g_host->n + K - 1) / K};
-  const HostCsr csr{g_host};
   const int32_t per_round = k_neg + 1, samples = B * per_round;
   PairWork w{};
   w.a_lo = L.lo(pa); w.a_n = L.size(pa); w.b_lo = L.lo(pb); w.b_n = L.size(pb);
@@ -233,10 +205,10 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
   w.rotation = rotation; w.word3 = level_word(level, pair_index);
   std::vector<int32_t> pool_a(static_cast<size_t>(w.a_n) * B + 1), pool_b(static_cast<size_t>(w.b_n) * B + 1);
   const int threads = omp_get_max_threads();
-  fill_pool(csr, w.a_lo, w.a_n, w.b_lo, w.b_lo + w.b_n, 0, B, per_round, w.key0, w.key1, rotation,
+  gosh::fill_pool(*g_host, w.a_lo, w.a_n, w.b_lo, w.b_lo + w.b_n, 0, B, per_round, w.key0, w.key1, rotation,
             w.word3, threads, pool_a.data());
   if (!w.diagonal)
-    fill_pool(csr, w.b_lo, w.b_n, w.a_lo, w.a_lo + w.a_n, 1, B, per_round, w.key0, w.key1, rotation,
+    gosh::fill_pool(*g_host, w.b_lo, w.b_n, w.a_lo, w.a_lo + w.a_n, 1, B, per_round, w.key0, w.key1, rotation,
               w.word3, threads, pool_b.data());
   const int64_t total = w.count() * samples;
   int rc = GOSH_OK;
@@ -292,8 +264,8 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   pair_order(K, pa, pb);
   const int64_t npairs = static_cast<int64_t>(pa.size());
   const int64_t visits = rotations * npairs;
-  const HostCsr csr{g_host};
   const int host_threads = std::max(1, omp_get_max_threads());
+  const HostCsr csr{g_host};
   const size_t pool_ints = static_cast<size_t>(2) * L.part_rows * B;  // side 0 then side 1
 
   int rc = GOSH_OK;
@@ -413,10 +385,10 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       int32_t *buf = staging[vi % NS];
       const uint32_t w3 = level_word(level, q);
       const auto t_fill = std::chrono::steady_clock::now();
-      fill_pool(csr, L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, B, per_round, key0, key1,
+      gosh::fill_pool(*g_host, L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, B, per_round, key0, key1,
                 rot, w3, host_threads, buf);
       if (a != b)
-        fill_pool(csr, L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, B, per_round, key0, key1,
+        gosh::fill_pool(*g_host, L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, B, per_round, key0, key1,
                   rot, w3, host_threads, buf + static_cast<size_t>(L.part_rows) * B);
       sampler_busy_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_fill).count();
       {
