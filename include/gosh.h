@@ -64,6 +64,12 @@ typedef struct {
                                      |E_i| = nnz_i / 2, and the learning rate decays over all
                                      of them */
 
+/* gosh_train_parts / gosh_embed_host only */
+#define GOSH_FLAG_BLOCKED_ORDER 16u /* visit the part pairs in the blocked order of
+                                       gosh_pair_order_blocked (block = P_gpu - 2 parts, at
+                                       least 1) instead of the paper's: the same pairs once
+                                       per rotation, fewer parts over the host link */
+
 const char *gosh_last_error(void);
 
 /* ---- schedule helpers (host, pure) ------------------------------------------------ */
@@ -266,6 +272,14 @@ typedef struct {
 /* Visiting order of the part pairs in one rotation (Sec. 3.3.1): (0,0), (1,0), (1,1),
  * (2,0), ... -- K(K+1)/2 pairs written to a[] and b[] (host arrays), a[j] >= b[j]. */
 int gosh_pair_order(int32_t K, int32_t *a, int32_t *b);
+
+/* A visiting order that is not the paper's, for hardware whose host link bounds the
+ * rotation: the parts are cut into blocks of R consecutive parts; for every block in turn,
+ * first the pairs inside the block in the order of gosh_pair_order, then for each later
+ * part c the pairs (c, r) for every r of the block.  A device that keeps the block resident
+ * and streams the later parts through meets R pairs per part it loads.  Every pair (a, b),
+ * a >= b, occurs exactly once; R >= K gives gosh_pair_order.  GOSH_EINVAL if R < 1. */
+int gosh_pair_order_blocked(int32_t K, int32_t R, int32_t *a, int32_t *b);
 
 /* The part layout gosh_train_parts would use: the smallest K for which min(P_gpu, K) part
  * slots of ceil(n/K) rows, S_gpu sample pools of 2*ceil(n/K)*B ids and the hot-row bitmap

@@ -332,6 +332,32 @@ int64_t orc_pair_order(int32_t K, int32_t *a, int32_t *b) {
   return cnt;
 }
 
+// A second visiting order, NOT the paper's: "blocked".  The parts are cut into blocks of R
+// consecutive parts; for every block in turn, first the pairs inside the block in the
+// order above, then for each later part c the pairs (c, r) for every r of the block.  A
+// device that keeps one block resident and streams the later parts through meets R pairs
+// per part it loads, where the order above meets one.  Every pair (a, b), a >= b, still
+// occurs exactly once per rotation, and with R >= K the order is the one above.
+int64_t orc_pair_order_blocked(int32_t K, int32_t R, int32_t *a, int32_t *b) {
+  int64_t cnt = 0;
+  for (int32_t first = 0; first < K; first += R) {
+    int32_t end = first + R < K ? first + R : K;
+    for (int32_t m = first; m < end; ++m)
+      for (int32_t s = first; s <= m; ++s) {
+        a[cnt] = m;
+        b[cnt] = s;
+        ++cnt;
+      }
+    for (int32_t c = end; c < K; ++c)
+      for (int32_t r = first; r < end; ++r) {
+        a[cnt] = c;
+        b[cnt] = r;
+        ++cnt;
+      }
+  }
+  return cnt;
+}
+
 // READING (partition): parts are contiguous id ranges of ceil(n/K) vertices.
 static inline int64_t part_size(int64_t n, int32_t K) { return (n + K - 1) / K; }
 
@@ -400,13 +426,15 @@ int64_t orc_rotations(int64_t e_i, int32_t B, int32_t K) {
 
 // Alg. 5 executed sequentially on host memory with no device budget.
 // READING: the learning rate decays per rotation with the epoch formula.
+// block = 0: the paper's order; block = R > 0: the blocked order with blocks of R parts.
 void orc_train_parts(int64_t n, const int64_t *xadj, const int32_t *adj, float *M, int32_t d,
                      int32_t k, int64_t e_i, float lr0, uint64_t seed, uint32_t level, int32_t K,
-                     int32_t B) {
+                     int32_t B, int32_t block) {
   int64_t rotations = orc_rotations(e_i, B, K);
   int64_t npairs = (int64_t)K * (K + 1) / 2;
   std::vector<int32_t> a((size_t)npairs), b((size_t)npairs);
-  orc_pair_order(K, a.data(), b.data());
+  if (block > 0) orc_pair_order_blocked(K, block, a.data(), b.data());
+  else orc_pair_order(K, a.data(), b.data());
   for (int64_t r = 0; r < rotations; ++r) {
     float lr = orc_lr(lr0, r, rotations);
     for (int64_t q = 0; q < npairs; ++q)

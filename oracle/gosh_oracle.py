@@ -70,6 +70,8 @@ def lib():
         L.orc_coarsen_graph.restype = C.c_int64
         L.orc_pair_order.argtypes = [C.c_int32, i32p, i32p]
         L.orc_pair_order.restype = C.c_int64
+        L.orc_pair_order_blocked.argtypes = [C.c_int32, C.c_int32, i32p, i32p]
+        L.orc_pair_order_blocked.restype = C.c_int64
         L.orc_train_pair.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
                                      C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                      C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, i32p]
@@ -78,7 +80,7 @@ def lib():
         L.orc_rotations.restype = C.c_int64
         L.orc_train_parts.argtypes = [C.c_int64, i64p, i32p, f32p, C.c_int32, C.c_int32,
                                       C.c_int64, C.c_float, C.c_uint64, C.c_uint32, C.c_int32,
-                                      C.c_int32]
+                                      C.c_int32, C.c_int32]
         L.orc_train_parts.restype = None
         _lib = L
     return _lib
@@ -301,7 +303,7 @@ def parts_split(n, d, budget, P_gpu, S_gpu, B):
 
 
 def embed_budget(xadj, adj, d, k, epochs, p, lr0, seed, budget, P_gpu=3, S_gpu=4, B=5,
-                 threshold=100, min_shrink=1.0, offsets64=False):
+                 threshold=100, min_shrink=1.0, offsets64=False, blocked=False):
     """Alg. 2 with its "fits into GPU" test: a level whose graph (offsets + adj) and matrix
     exceed `budget` bytes is trained with the rotation of Alg. 5, the others with Alg. 3.
     Coarse levels have 64-bit offsets; level 0 as given.  Returns (M_0, modes) where
@@ -321,7 +323,8 @@ def embed_budget(xadj, adj, d, k, epochs, p, lr0, seed, budget, P_gpu=3, S_gpu=4
         else:
             K = parts_split(n, d, budget, P_gpu, S_gpu, B)
             modes[i] = K
-            train_parts(x, a, M, k, int(e_i[i]), lr0, seed, i, K, B)
+            train_parts(x, a, M, k, int(e_i[i]), lr0, seed, i, K, B,
+                        block=blocked_block_size(P_gpu, K) if blocked else 0)
         if i > 0:
             M = project(M, maps[i - 1])
     return M, modes
@@ -332,6 +335,21 @@ def pair_order(K):
     a = np.zeros(npairs, dtype=np.int32)
     b = np.zeros(npairs, dtype=np.int32)
     cnt = lib().orc_pair_order(K, _p(a, C.c_int32), _p(b, C.c_int32))
+    assert cnt == npairs
+    return list(zip(a.tolist(), b.tolist()))
+
+
+def blocked_block_size(P_gpu, K):
+    """Block size of the blocked order for a device with P_gpu part slots: all slots but two
+    (the two take turns receiving the streamed parts), at least one."""
+    return max(1, min(P_gpu, K) - 2)
+
+
+def pair_order_blocked(K, R):
+    npairs = K * (K + 1) // 2
+    a = np.zeros(npairs, dtype=np.int32)
+    b = np.zeros(npairs, dtype=np.int32)
+    cnt = lib().orc_pair_order_blocked(K, R, _p(a, C.c_int32), _p(b, C.c_int32))
     assert cnt == npairs
     return list(zip(a.tolist(), b.tolist()))
 
@@ -358,8 +376,10 @@ def train_pair(xadj, adj, M, k, B, K, pa, pb, lr_, seed, rotation, level, pair_i
     return stream
 
 
-def train_parts(xadj, adj, M, k, e_i, lr0, seed, level, K, B):
+def train_parts(xadj, adj, M, k, e_i, lr0, seed, level, K, B, block=0):
+    """Alg. 5, sequentially.  block = 0: the paper's visiting order; block = R > 0: the
+    blocked order with blocks of R parts."""
     xadj, adj = _csr(xadj, adj)
     n, d = M.shape
     lib().orc_train_parts(n, _p(xadj, C.c_int64), _p(adj, C.c_int32), _p(M, C.c_float), d, k,
-                          e_i, lr0, seed, level, K, B)
+                          e_i, lr0, seed, level, K, B, block)

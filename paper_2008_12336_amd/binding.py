@@ -18,6 +18,7 @@ GOSH_FLAG_SEQUENTIAL = 1
 GOSH_FLAG_PLAIN_STORES = 2
 GOSH_FLAG_ATOMIC_ADDS = 4
 GOSH_FLAG_EDGE_EPOCHS = 8
+GOSH_FLAG_BLOCKED_ORDER = 16
 GOSH_MAX_DIM = 512
 GOSH_MAX_NEG = 15
 
@@ -77,6 +78,8 @@ EXPORTS = {
                              C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p,
                              C.POINTER(gosh_level_stats), C.c_void_p]),
     "gosh_pair_order": (C.c_int, [C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "gosh_pair_order_blocked": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                          C.POINTER(C.c_int32)]),
     "gosh_parts_plan": (C.c_int, [C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_int32, C.c_int32,
                                   C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_uint64)]),
@@ -368,6 +371,15 @@ def gosh_pair_order(K: int):
     a = (C.c_int32 * npairs)()
     b = (C.c_int32 * npairs)()
     _check(lib().gosh_pair_order(K, a, b))
+    return list(zip(list(a), list(b)))
+
+
+def gosh_pair_order_blocked(K: int, R: int):
+    """The blocked visiting order with blocks of R parts (not the paper's order)."""
+    npairs = K * (K + 1) // 2 if K > 0 else 1
+    a = (C.c_int32 * npairs)()
+    b = (C.c_int32 * npairs)()
+    _check(lib().gosh_pair_order_blocked(K, R, a, b))
     return list(zip(list(a), list(b)))
 
 

@@ -95,7 +95,8 @@ struct Plan {
   int32_t d, k_neg;
   float lr0;
   uint64_t seed;
-  uint32_t flags;  // for the training calls (without GOSH_FLAG_EDGE_EPOCHS)
+  uint32_t flags;  // for the epoch kernel calls
+  uint32_t parts_flags;  // for the rotation calls: the same plus GOSH_FLAG_BLOCKED_ORDER if asked
   bool edge_epochs;
   uint64_t budget;
   int32_t P_gpu, S_gpu, B;
@@ -231,7 +232,7 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
       gosh_parts_stats ps{};
       if (int rc = gosh_train_parts(&g, cur_host, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed,
                                     static_cast<uint32_t>(i), pl.budget, pl.P_gpu, pl.S_gpu, pl.B, 0,
-                                    pl.flags, &ps))
+                                    pl.parts_flags, &ps))
         return rc;
       ls.parts_K = ps.K;
       ls.train_ms = ps.wall_ms;
@@ -367,7 +368,8 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
   if (int rc = check_common(d, k_neg)) return rc;
   if (int rc = gosh::check_matrix(M0_dev, d, "M0")) return rc;
   // A level above level 0 can only exceed the budget if level 0 does too, which is refused.
-  const Plan pl{d, k_neg, lr0, seed, flags & ~GOSH_FLAG_EDGE_EPOCHS, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
+  const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
+  const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
                 device_budget_bytes, 3, 4, 5};
   return embed_impl(h, pl, epochs, p, M0_dev, nullptr, stats, gosh::as_stream(hip_stream));
 }
@@ -380,8 +382,9 @@ int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t e
   if (int rc = gosh::check_matrix(M0_host, d, "M0")) return rc;
   if (P_gpu < 2 || S_gpu < 1 || B < 1)
     return gosh::fail(GOSH_EINVAL, "need P_gpu >= 2, S_gpu >= 1, B >= 1");
-  const Plan pl{d, k_neg, lr0, seed, flags & ~GOSH_FLAG_EDGE_EPOCHS, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
-                device_budget_bytes, P_gpu, S_gpu, B};
+  const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
+  const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags | (flags & GOSH_FLAG_BLOCKED_ORDER),
+                (flags & GOSH_FLAG_EDGE_EPOCHS) != 0, device_budget_bytes, P_gpu, S_gpu, B};
   return embed_impl(h, pl, epochs, p, nullptr, M0_host, stats, gosh::as_stream(hip_stream));
 }
 

@@ -116,6 +116,30 @@ void pair_order(int32_t K, std::vector<int32_t> &a, std::vector<int32_t> &b) {
     }
 }
 
+// A visiting order for hardware whose host link, not its kernels, bounds the rotation (it
+// is not the paper's): the parts are cut into blocks of R consecutive parts; for every
+// block in turn, first the pairs inside the block in the order above, then for each later
+// part c the pairs (c, r) for every r of the block.  With the block resident and the later
+// parts streamed through, a loaded part meets R partners instead of one.  Every pair
+// (a, b), a >= b, still occurs exactly once; R >= K gives the order above.
+void pair_order_blocked(int32_t K, int32_t R, std::vector<int32_t> &a, std::vector<int32_t> &b) {
+  a.clear();
+  b.clear();
+  for (int32_t first = 0; first < K; first += R) {
+    const int32_t end = std::min(first + R, K);
+    for (int32_t m = first; m < end; ++m)
+      for (int32_t s = first; s <= m; ++s) {
+        a.push_back(m);
+        b.push_back(s);
+      }
+    for (int32_t c = end; c < K; ++c)
+      for (int32_t r = first; r < end; ++r) {
+        a.push_back(c);
+        b.push_back(r);
+      }
+  }
+}
+
 #define PARTS_HIP(call, what)                                                          \
   do {                                                                                 \
     hipError_t e_ = (call);                                                            \
@@ -140,7 +164,7 @@ int check_parts_args(const gosh_csr *g, const float *M, int32_t d, int32_t k_neg
   if (P < 2 || P > 64) return gosh::fail(GOSH_EINVAL, "P_gpu = %d: must be in [2, 64]", P);
   if (S < 1 || S > 64) return gosh::fail(GOSH_EINVAL, "S_gpu = %d: must be in [1, 64]", S);
   if (B < 1 || B > 64) return gosh::fail(GOSH_EINVAL, "B = %d: must be in [1, 64]", B);
-  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS))
+  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS | GOSH_FLAG_BLOCKED_ORDER))
     return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
   if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
     return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
@@ -158,6 +182,17 @@ int gosh_pair_order(int32_t K, int32_t *a, int32_t *b) {
   if (a == nullptr || b == nullptr) return gosh::fail(GOSH_EINVAL, "output array is null");
   std::vector<int32_t> va, vb;
   pair_order(K, va, vb);
+  std::copy(va.begin(), va.end(), a);
+  std::copy(vb.begin(), vb.end(), b);
+  return GOSH_OK;
+}
+
+int gosh_pair_order_blocked(int32_t K, int32_t R, int32_t *a, int32_t *b) {
+  if (K < 1 || K > kMaxParts) return gosh::fail(GOSH_EINVAL, "K = %d: must be in [1, %d]", K, kMaxParts);
+  if (R < 1) return gosh::fail(GOSH_EINVAL, "R = %d: must be >= 1", R);
+  if (a == nullptr || b == nullptr) return gosh::fail(GOSH_EINVAL, "output array is null");
+  std::vector<int32_t> va, vb;
+  pair_order_blocked(K, R, va, vb);
   std::copy(va.begin(), va.end(), a);
   std::copy(vb.begin(), vb.end(), b);
   return GOSH_OK;
@@ -261,7 +296,10 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   const bool seq = (flags & GOSH_FLAG_SEQUENTIAL) != 0;
   const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
   std::vector<int32_t> pa, pb;
-  pair_order(K, pa, pb);
+  // the blocked order keeps all slots but two for a block; the two take turns receiving
+  // the streamed parts
+  if (flags & GOSH_FLAG_BLOCKED_ORDER) pair_order_blocked(K, std::max(1, P - 2), pa, pb);
+  else pair_order(K, pa, pb);
   const int64_t npairs = static_cast<int64_t>(pa.size());
   const int64_t visits = rotations * npairs;
   const int host_threads = std::max(1, omp_get_max_threads());
@@ -417,13 +455,13 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     // other slots an empty one is taken, else the part whose next use is farthest is
     // written back and replaced.  Everything is queued on the copy stream behind the last
     // kernel that used the slot.  Returns the slot, -1 if every slot is kept, -2 on error.
-    auto load_part = [&](int32_t p, const int32_t (&keep)[3], int64_t now) -> int {
+    auto load_part = [&](int32_t p, const std::vector<int32_t> &keep, int64_t now) -> int {
       int victim = -1;
       int64_t farthest = -1;
       for (int s = 0; s < P; ++s) {
         const int32_t sp = slot_part[s];
         if (sp == -1) { victim = s; break; }
-        if (sp == keep[0] || sp == keep[1] || sp == keep[2]) continue;
+        if (std::find(keep.begin(), keep.end(), sp) != keep.end()) continue;
         const int64_t nu = next_use(sp, now);
         if (nu > farthest) { farthest = nu; victim = s; }
       }
@@ -442,7 +480,10 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         const size_t longest = std::max(old_bytes, new_bytes);
         size_t piece = (longest + kSwapChunks - 1) / kSwapChunks;
         piece = std::max<size_t>((piece + 255) / 256 * 256, size_t(8) << 20);
+        // after the last kernel that used the slot, and after the upload that filled it (a
+        // part brought in ahead of time may leave again before any kernel has used it)
         if (hipStreamWaitEvent(copy_out, slot_used[victim], 0) != hipSuccess) return -2;
+        if (hipStreamWaitEvent(copy_out, slot_ready[victim], 0) != hipSuccess) return -2;
         char *slot_bytes = reinterpret_cast<char *>(slot[victim]);
         int c = 0;
         for (size_t off = 0; off < longest; off += piece, ++c) {
@@ -469,23 +510,25 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       slot_part[victim] = p;
       return victim;
     };
-    // Makes the parts of visit vi resident as far as slots allow, never evicting the
-    // parts of the visit whose kernel may still be running (run_a, run_b; -1 = none).
-    auto ensure_parts = [&](int64_t vi, int32_t run_a, int32_t run_b) -> int {
-      if (vi >= visits) return 0;
+    // Makes the parts of visit vi resident as far as slots allow, never evicting a part
+    // in `keep` (the parts of the running visit and of the visits before vi).  Returns 1 if
+    // a needed part could not be placed, -2 on error, else 0; the parts of vi join `keep`.
+    auto ensure_parts = [&](int64_t vi, std::vector<int32_t> &keep) -> int {
+      if (vi >= visits) return 1;
       const int64_t q = vi % npairs;
+      keep.push_back(pa[q]);
+      keep.push_back(pb[q]);
       const int32_t need[2] = {pa[q], pb[q]};
       for (int t = 0; t < 2; ++t) {
         if (t == 1 && need[1] == need[0]) break;
         if (slot_of(need[t]) >= 0) continue;
-        // keep the running pair; keep the partner too unless it IS part of the running
-        // pair (already covered) -- with three slots at most two distinct parts are kept
-        // whenever a load is possible at all
-        const int32_t keep[3] = {run_a, run_b, need[1 - t]};
-        if (load_part(need[t], keep, vi) == -2) return -2;
+        const int got = load_part(need[t], keep, vi);
+        if (got == -2) return -2;
+        if (got == -1) return 1;
       }
       return 0;
     };
+    std::vector<int32_t> keep;
 
     for (int64_t vi = 0; vi < visits && rc == GOSH_OK; ++vi) {
       int32_t a, b;
@@ -493,7 +536,8 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       visit_pair(vi, a, b, rot, q);
       // 1. the two parts of this visit (nothing is running that they could disturb: the
       //    copy stream waits for the last kernel of any slot it overwrites)
-      if (ensure_parts(vi, -1, -1) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
+      keep.clear();
+      if (ensure_parts(vi, keep) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
       const int sa = slot_of(a), sb = slot_of(b);
       if (sa < 0 || sb < 0) { rc = gosh::fail(GOSH_EHIP, "internal: part not resident"); break; }
       // 2. the pool of this visit: wait for the sampler, upload on the copy stream
@@ -549,8 +593,14 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       PARTS_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
       PARTS_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
       PARTS_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
-      // 4. while that kernel runs: bring in what the next visit needs, if a slot is spare
-      if (ensure_parts(vi + 1, a, b) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
+      // 4. while that kernel runs: bring in what the next visits need, as far ahead as
+      //    slots that none of the visits in between uses can be found
+      {
+        keep.assign({a, b});
+        int got = 0;
+        for (int64_t ahead = 1; ahead <= P && got == 0; ++ahead) got = ensure_parts(vi + ahead, keep);
+        if (got == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
+      }
       // 5. hand the staging buffer back to the sampler once its upload is done
       PARTS_HIP(hipEventSynchronize(staging_done[hs]), "hipEventSynchronize");
       {

@@ -128,3 +128,25 @@ def test_budgeted_vcycle_on_host_matches_oracle(budget_kib, expect_parts, where)
     assert got_modes == modes
     assert sum(1 for m in modes if m) == expect_parts
     assert err <= 1e-5
+
+
+def test_budgeted_vcycle_with_blocked_order_matches_oracle():
+    """gosh_embed_host passes GOSH_FLAG_BLOCKED_ORDER on to the levels it trains by rotation."""
+    n = 1 << 11
+    c = graphgen.to_csr(n, graphgen.rmat(11, 1 << 14, 3))
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    d, k, epochs, p, lr0, seed, P = 32, 3, 40, 0.3, 0.05, 5, 5
+    budget = 200 * 1024
+    want, modes = O.embed_budget(xadj, adj, d, k, epochs, p, lr0, seed, budget, P_gpu=P, threshold=100,
+                                 min_shrink=0.8, blocked=True)
+    plain, _ = O.embed_budget(xadj, adj, d, k, epochs, p, lr0, seed, budget, P_gpu=P, threshold=100,
+                              min_shrink=0.8)
+    h = G.gosh_coarsen_device(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
+    M0 = torch.zeros(n, d, dtype=torch.float32).pin_memory()
+    stats = G.gosh_embed_host(h, M0, k, epochs, p, lr0, seed, device_budget_bytes=budget, P_gpu=P,
+                              flags=G.GOSH_FLAG_SEQUENTIAL | G.GOSH_FLAG_BLOCKED_ORDER)
+    assert [s["parts_K"] for s in stats] == modes and max(modes) >= 5
+    err = rel_err(M0.numpy(), want)
+    say(f"[budget blocked] modes {modes} err {err:.2e}")
+    assert err <= 1e-5
+    assert rel_err(plain, want) > 1e-4

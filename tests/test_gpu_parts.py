@@ -98,6 +98,46 @@ def test_unpinned_host_matrix_and_forced_split():
         G.gosh_train_parts(n, c.xadj, c.adj, M, k, 20, 0.05, 3, force_K=4, P_gpu=1)
 
 
+@pytest.mark.parametrize("n,d,K,P,S,B,k,epochs", [
+    (600, 32, 3, 3, 4, 5, 3, 30),    # blocks of one part: column order
+    (1200, 32, 9, 4, 4, 2, 3, 40),   # blocks of two
+    (1300, 16, 13, 5, 3, 2, 2, 60),  # blocks of three, last block short
+    (1100, 32, 7, 6, 2, 3, 3, 50),   # blocks of four
+    (500, 8, 2, 4, 2, 2, 3, 10),     # fewer parts than slots: one block, the paper's order
+    (9, 8, 4, 4, 2, 2, 3, 16),       # an empty last part
+])
+def test_sequential_blocked_rotation_matches_oracle(n, d, K, P, S, B, k, epochs):
+    """GOSH_FLAG_BLOCKED_ORDER: the rotation visits the pairs in the blocked order (blocks of
+    min(P, K) - 2 parts) with parts fetched several visits ahead; sequential mode against the
+    oracle's rotation in the same order, and fewer bytes over the link than the paper's."""
+    say(f"[parts-blocked] n={n} d={d} K={K} P={P} S={S} B={B} k={k} epochs={epochs}")
+    c = graph(n, 5 * n, 8, "cl")
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    M0 = (O.init_embedding(n, d, 3, 0).astype(np.float64) * d * 0.8).astype(np.float32)
+    want = M0.copy()
+    block = O.blocked_block_size(P, K)
+    O.train_parts(xadj, adj, want, k, epochs, 0.1, 7, 2, K, B, block=block)
+    budget = budget_for(n, d, K, P, S, B)
+    runs = {}
+    for name, flags in (("blocked", G.GOSH_FLAG_BLOCKED_ORDER), ("paper", 0)):
+        M = torch.from_numpy(M0.copy()).pin_memory()
+        st = G.gosh_train_parts(n, c.xadj, c.adj, M, k, epochs, 0.1, 7, level=2, device_budget_bytes=budget,
+                                P_gpu=P, S_gpu=S, B=B, force_K=K, flags=G.GOSH_FLAG_SEQUENTIAL | flags)
+        runs[name] = (M.numpy().copy(), st)
+    got, st = runs["blocked"]
+    err = rel_err(got, want)
+    say(f"            block={block} visits={st['pair_visits']} err={err:.2e} h2d blocked {st['bytes_h2d']} "
+        f"paper {runs['paper'][1]['bytes_h2d']}")
+    assert st["K"] == K and st["pair_visits"] == st["rotations"] * K * (K + 1) // 2
+    assert err <= 1e-5
+    if block >= K:
+        assert np.array_equal(got, runs["paper"][0])  # one block: the paper's order itself
+    elif K >= 3:
+        assert rel_err(runs["paper"][0], want) > 1e-4  # the other order gives another result
+    if block > 1 and K >= 2 * P:
+        assert st["bytes_h2d"] < 0.85 * runs["paper"][1]["bytes_h2d"]
+
+
 @pytest.mark.parametrize("flags", [0, G.GOSH_FLAG_PLAIN_STORES])
 def test_concurrent_rotation_with_zero_lr_moves_nothing(flags):
     n, d, k = 3000, 128, 3

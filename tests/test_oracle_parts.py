@@ -91,3 +91,67 @@ def test_parts_training_separates_two_cliques():
     intra = (G[:size, :size].sum() - np.trace(G[:size, :size])) / (size * (size - 1))
     inter = G[:size, size:].mean()
     assert intra > inter + 0.5, (intra, inter)
+
+
+def _loads_with_optimal_cache(order, slots):
+    """Part loads a cache of `slots` parts needs for the visiting order `order` when it
+    evicts the part whose next use is farthest (brute force, independent of the library)."""
+    resident, loads = set(), 0
+    for t, pair in enumerate(order):
+        for p in set(pair):
+            if p in resident:
+                continue
+            loads += 1
+            if len(resident) >= slots:
+                def next_use(q):
+                    for u in range(t, len(order)):
+                        if q in order[u]:
+                            return u
+                    return len(order)
+                victims = [q for q in resident if q not in pair]
+                resident.remove(max(victims, key=next_use))
+            resident.add(p)
+    return loads
+
+
+def test_blocked_pair_order():
+    """The blocked order (not the paper's): every pair once, the paper's order when one block
+    holds all parts, the hand-written sequence for K = 5, R = 2, and fewer part loads than
+    the paper's order on a device with R + 2 slots."""
+    assert O.pair_order_blocked(5, 2) == [(0, 0), (1, 0), (1, 1), (2, 0), (2, 1), (3, 0), (3, 1), (4, 0),
+                                          (4, 1), (2, 2), (3, 2), (3, 3), (4, 2), (4, 3), (4, 4)]
+    assert O.pair_order_blocked(4, 1) == [(0, 0), (1, 0), (2, 0), (3, 0), (1, 1), (2, 1), (3, 1), (2, 2),
+                                          (3, 2), (3, 3)]
+    for K in range(1, 12):
+        assert O.pair_order_blocked(K, K) == O.pair_order(K) == O.pair_order_blocked(K, K + 3)
+        for R in range(1, K + 1):
+            order = O.pair_order_blocked(K, R)
+            assert sorted(order) == sorted((a, b) for a in range(K) for b in range(a + 1))
+            assert all(a >= b for a, b in order)
+    for K, R in [(13, 2), (17, 2), (21, 3), (9, 1)]:
+        blocked, paper = O.pair_order_blocked(K, R), O.pair_order(K)
+        starts = range(0, K, R)
+        closed_form = sum(min(R, K - s) + max(0, K - (s + R)) for s in starts)
+        # the closed form is what "keep the block, stream the rest" needs; an optimal cache can
+        # also carry a few parts over from one block to the next
+        loads = _loads_with_optimal_cache(blocked, R + 2)
+        assert K <= loads <= closed_form
+        if R > 1:
+            assert loads < 0.75 * _loads_with_optimal_cache(paper, R + 2)
+    assert O.blocked_block_size(3, 13) == 1 and O.blocked_block_size(5, 21) == 3
+    assert O.blocked_block_size(4, 2) == 1
+
+
+def test_blocked_rotation_differs_only_in_order():
+    """With one block the blocked rotation is the paper's, bit for bit; with small blocks it
+    applies the same multiset of updates in another order (same sample ids per pair)."""
+    n = 60
+    c = graphgen.to_csr(n, graphgen.er_gnm(n, 300, 5))
+    xadj, adj = c.xadj.numpy().astype(np.int64), c.adj.numpy()
+    a = O.init_embedding(n, 8, 2, 0)
+    b, c2 = a.copy(), a.copy()
+    O.train_parts(xadj, adj, a, 2, 40, 0.05, 2, 0, 4, 5)
+    O.train_parts(xadj, adj, b, 2, 40, 0.05, 2, 0, 4, 5, block=4)
+    O.train_parts(xadj, adj, c2, 2, 40, 0.05, 2, 0, 4, 5, block=2)
+    assert np.array_equal(a, b)
+    assert not np.array_equal(a, c2) and np.isfinite(c2).all()

@@ -12,6 +12,14 @@ def test_pair_order_matches_oracle():
         G.gosh_pair_order(0)
 
 
+def test_blocked_pair_order_matches_oracle():
+    for K in (1, 2, 3, 7, 13, 20):
+        for R in (1, 2, 3, 5, K, K + 2):
+            assert G.gosh_pair_order_blocked(K, R) == O.pair_order_blocked(K, R)
+    with pytest.raises(G.GoshError):
+        G.gosh_pair_order_blocked(5, 0)
+
+
 def test_plan_is_the_smallest_split_that_fits():
     n, d, B, P, S = 1_000_000, 128, 5, 3, 4
 
