@@ -144,7 +144,10 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     import paper_2008_12336_amd as G
 
     d, k, B = w["d"], w["k"], 5
-    xadj_h, adj_h = csr.xadj.cpu(), csr.adj.cpu()
+    if args.graph == "device":
+        xadj_h, adj_h = csr.xadj, csr.adj  # sampled where the generator left it
+    else:
+        xadj_h, adj_h = csr.xadj.cpu(), csr.adj.cpu()
     del csr
     release_generator_memory(torch)
     M_dev = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
@@ -169,7 +172,7 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
            "steps": 1, "warmup": 0, "ms_per_step": st["wall_ms"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": args.workload + "_parts", "desc": w["desc"], "n": n,
-                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "P_gpu": args.p_gpu,
+                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "graph": args.graph, "flags": args.flags, "P_gpu": args.p_gpu,
                       "S_gpu": args.s_gpu, "device_budget_bytes": budget, "matrix_bytes": n * d * 4,
                       "graph_build_s": t_graph, "finite": bool(torch.isfinite(M_host[::4097]).all()),
                       **st,
@@ -198,7 +201,7 @@ def main() -> int:
     ap.add_argument("--coarsen", default="device", choices=["device", "host"],
                     help="--mode levels: where the coarse graphs are rebuilt")
     ap.add_argument("--graph", default="host", choices=["host", "device"],
-                    help="--mode levels with --coarsen device: where G_0 is handed over")
+                    help="--mode levels with --coarsen device, --mode parts: where G_0 is handed over")
     ap.add_argument("--epochs", type=int, default=40, help="total epochs of --mode levels")
     ap.add_argument("--p-gpu", type=int, default=3, help="--mode parts: device slots for parts")
     ap.add_argument("--s-gpu", type=int, default=4, help="--mode parts: device sample pools")

@@ -309,11 +309,17 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
  * update (a neighbour inside b, drawn on the host into a pool that is shipped to the
  * device) and k_neg negative updates (drawn on the device, uniform over b), and vice versa;
  * a vertex without a neighbour in the partner part gets no positive update there.
- * g_host: host CSR.  M_host: host matrix n x d, updated in place; pinned memory makes the
+ * g_host: host CSR, or a CSR in the current device's memory (detected from the pointers;
+ * what gosh_embed_host passes for a level of a device-built hierarchy): the pools of
+ * positives are then filled by a kernel on the device, with the same values, and no host
+ * sampler runs -- on this hardware the graph usually fits the device where the matrix
+ * does not.  The graph is outside device_budget_bytes either way.
+ * M_host: host matrix n x d, updated in place; pinned memory makes the
  * transfers asynchronous.  device_budget_bytes: cap for slots + pools + bitmap (0 only
  * together with force_K > 0).  P_gpu >= 2 (paper: 3), S_gpu >= 1 (paper: 4), B >= 1
  * (paper: 5).  force_K > 0 overrides the part count.  flags as for gosh_train_epoch
- * (GOSH_FLAG_SEQUENTIAL: every pair kernel runs on one wavefront, sources in order).
+ * (GOSH_FLAG_SEQUENTIAL: every pair kernel runs on one wavefront, sources in order), plus
+ * GOSH_FLAG_BLOCKED_ORDER.
  * The library owns its streams, device buffers and sampler thread for the duration of
  * the call, which blocks until the matrix is back on the host.  stats_out may be NULL. */
 int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k_neg,

@@ -227,8 +227,15 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
       GOSH_HIP(hipEventElapsedTime(&ms, ev0, ev1), "hipEventElapsedTime");
       ls.train_ms = ms;
     } else {
-      // LargeGraphGPU (its sampler reads the graph on the host)
-      if (int rc = gosh_hierarchy_graph(h, i, &g)) return rc;
+      // LargeGraphGPU.  A graph that already lives on the device is sampled there; otherwise
+      // the host copy is used (and made, if the hierarchy has none yet).
+      if (const gosh::DeviceLevel *dl = resident(i)) {
+        g.xadj = dl->xadj;
+        g.adj = dl->adj;
+        g.xadj_is64 = dl->xadj_is64;
+      } else if (int rc = gosh_hierarchy_graph(h, i, &g)) {
+        return rc;
+      }
       gosh_parts_stats ps{};
       if (int rc = gosh_train_parts(&g, cur_host, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed,
                                     static_cast<uint32_t>(i), pl.budget, pl.P_gpu, pl.S_gpu, pl.B, 0,

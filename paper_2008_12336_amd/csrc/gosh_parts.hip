@@ -20,6 +20,7 @@
 #include <thread>
 #include <vector>
 
+#include "gosh_coarsen_internal.h"
 #include "gosh_common.h"
 #include "gosh_sampler.h"
 #include "gosh_device.h"
@@ -86,6 +87,61 @@ __global__ __launch_bounds__(256) void pair_stream_kernel(PairWork w, int32_t sa
     const int64_t i = x / samples;
     const int32_t t = static_cast<int32_t>(x % samples);
     out[x] = w.sample(i, w.source_id(i), t, true, t % w.per_round == 0);
+  }
+}
+
+// The positives of one side of a pair, drawn on the device from a graph that lives there:
+// the same runs (two binary searches in the ascending row) and the same draws as the host
+// sampler, one thread per source.
+template <typename OffT>
+__global__ __launch_bounds__(256) void fill_pool_kernel(const OffT *__restrict__ xadj,
+                                                        const int32_t *__restrict__ adj, int32_t lo, int32_t cnt,
+                                                        int32_t olo, int32_t ohi, int32_t side, int32_t B,
+                                                        int32_t per_round, uint32_t key0, uint32_t key1,
+                                                        uint32_t rotation, uint32_t word3,
+                                                        int32_t *__restrict__ pool) {
+  for (int64_t local = blockIdx.x * 256LL + threadIdx.x; local < cnt; local += gridDim.x * 256LL) {
+    const int64_t src = static_cast<int64_t>(lo) + local;
+    const int64_t end = static_cast<int64_t>(xadj[src + 1]);
+    int64_t first = static_cast<int64_t>(xadj[src]), hi = end;
+    while (first < hi) {  // first entry >= olo
+      const int64_t mid = first + (hi - first) / 2;
+      if (adj[mid] < olo) first = mid + 1;
+      else hi = mid;
+    }
+    int64_t last = first;
+    hi = end;
+    while (last < hi) {  // first entry >= ohi
+      const int64_t mid = last + (hi - last) / 2;
+      if (adj[mid] < ohi) last = mid + 1;
+      else hi = mid;
+    }
+    const uint32_t candidates = static_cast<uint32_t>(last - first);
+    for (int32_t r = 0; r < B; ++r) {
+      int32_t pick = -1;
+      if (candidates > 0) {
+        const uint64_t draw = philox_draw(static_cast<uint32_t>(src),
+                                          static_cast<uint32_t>(side * B * per_round + r * per_round), rotation,
+                                          word3, key0, key1);
+        pick = adj[first + scale_draw(draw, candidates)];
+      }
+      pool[local * B + r] = pick;
+    }
+  }
+}
+
+// Bit v of the hot-row bitmap: deg(v) >= min_degree (one thread per 64 vertices).
+template <typename OffT>
+__global__ __launch_bounds__(256) void degree_bitmap_kernel(const OffT *__restrict__ xadj, int64_t n,
+                                                            int64_t min_degree, uint64_t *__restrict__ bits) {
+  const int64_t words = (n + 63) / 64;
+  for (int64_t w = blockIdx.x * 256LL + threadIdx.x; w < words; w += gridDim.x * 256LL) {
+    uint64_t word = 0;
+    for (int bit = 0; bit < 64; ++bit) {
+      const int64_t v = w * 64 + bit;
+      if (v < n && static_cast<int64_t>(xadj[v + 1] - xadj[v]) >= min_degree) word |= uint64_t{1} << bit;
+    }
+    bits[w] = word;
   }
 }
 
@@ -303,6 +359,8 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   const int64_t npairs = static_cast<int64_t>(pa.size());
   const int64_t visits = rotations * npairs;
   const int host_threads = std::max(1, omp_get_max_threads());
+  // A graph in device memory is sampled there (no sampler thread, no pool uploads).
+  const bool graph_on_device = gosh::is_device_pointer(g_host->xadj);
   const HostCsr csr{g_host};
   const size_t pool_ints = static_cast<size_t>(2) * L.part_rows * B;  // side 0 then side 1
 
@@ -323,10 +381,11 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   hipStream_t compute = nullptr, copy = nullptr, copy_out = nullptr;
   // A part swap runs in kSwapChunks pieces: piece c of the new part goes up as soon as piece
   // c of the old one is down, so both directions of the host link are busy at once.
-  constexpr int kSwapChunks = 16;
+  constexpr int kSwapChunks = 8;
   std::vector<hipEvent_t> chunk_flushed(static_cast<size_t>(P) * kSwapChunks, nullptr);
   std::vector<hipEvent_t> slot_ready(P, nullptr), slot_used(P, nullptr), pool_ready(S, nullptr),
       pool_used(S, nullptr), staging_done(NS, nullptr);
+  hipEvent_t arrived = nullptr;  // device-sampled path: the parts of the current visit are in
   std::vector<hipEvent_t> k_begin, k_end;
   std::vector<int32_t> slot_part(P, -1);
 
@@ -364,11 +423,12 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     PARTS_HIP(hipEventCreateWithFlags(&pool_ready[s], hipEventDisableTiming), "hipEventCreate");
     PARTS_HIP(hipEventCreateWithFlags(&pool_used[s], hipEventDisableTiming), "hipEventCreate");
   }
-  for (int s = 0; s < NS; ++s) {
+  for (int s = 0; s < NS && !graph_on_device; ++s) {
     PARTS_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
               "hipHostMalloc staging");
     PARTS_HIP(hipEventCreateWithFlags(&staging_done[s], hipEventDisableTiming), "hipEventCreate");
   }
+  PARTS_HIP(hipEventCreateWithFlags(&arrived, hipEventDisableTiming), "hipEventCreate");
   k_begin.assign(static_cast<size_t>(visits), nullptr);
   k_end.assign(static_cast<size_t>(visits), nullptr);
 
@@ -386,7 +446,23 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     if (flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
     if (mode == gosh::kHotBitmap) {
       const int64_t min_degree = g_host->nnz / (gosh::tuning().hot_inv_eps * in_flight * B) + 1;
-      std::vector<uint64_t> bits(static_cast<size_t>((n + 63) / 64), 0);
+      if (graph_on_device) {
+        const int64_t words = (n + 63) / 64;
+        PARTS_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
+        const int blocks = static_cast<int>(std::min<int64_t>((words + 255) / 256, 65536));
+        if (g_host->xadj_is64)
+          hipLaunchKernelGGL(degree_bitmap_kernel<int64_t>, dim3(blocks), dim3(256), 0, nullptr,
+                             static_cast<const int64_t *>(g_host->xadj), n, min_degree,
+                             reinterpret_cast<uint64_t *>(hot_bits_dev));
+        else
+          hipLaunchKernelGGL(degree_bitmap_kernel<int32_t>, dim3(blocks), dim3(256), 0, nullptr,
+                             static_cast<const int32_t *>(g_host->xadj), n, min_degree,
+                             reinterpret_cast<uint64_t *>(hot_bits_dev));
+        if ((rc = gosh::check_launch("degree_bitmap_kernel"))) goto done;
+        PARTS_HIP(hipDeviceSynchronize(), "hot bitmap");
+        hot.bits = hot_bits_dev;
+      }
+      std::vector<uint64_t> bits(graph_on_device ? 0 : static_cast<size_t>((n + 63) / 64), 0);
 #pragma omp parallel for num_threads(host_threads) schedule(static)
       for (int64_t w64 = 0; w64 < static_cast<int64_t>(bits.size()); ++w64) {
         uint64_t word = 0;
@@ -396,9 +472,11 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         }
         bits[static_cast<size_t>(w64)] = word;
       }
-      PARTS_HIP(hipMalloc(&hot_bits_dev, bits.size() * 8), "hipMalloc hot bitmap");
-      PARTS_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
-      hot.bits = hot_bits_dev;
+      if (!graph_on_device) {
+        PARTS_HIP(hipMalloc(&hot_bits_dev, bits.size() * 8), "hipMalloc hot bitmap");
+        PARTS_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
+        hot.bits = hot_bits_dev;
+      }
     }
     hot.mode = mode;
   }
@@ -410,7 +488,8 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   }
 
   // ---- sampler thread: pools of positives, at most NS visits ahead of their release ------
-  sampler = std::thread([&] {
+  // (only for a host graph; a device-resident graph is sampled by fill_pool_kernel)
+  if (!graph_on_device) sampler = std::thread([&] {
     for (int64_t vi = 0; vi < visits; ++vi) {
       {
         std::unique_lock<std::mutex> lock(mu);
@@ -541,6 +620,31 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       if (ensure_parts(vi, keep) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
       const int sa = slot_of(a), sb = slot_of(b);
       if (sa < 0 || sb < 0) { rc = gosh::fail(GOSH_EHIP, "internal: part not resident"); break; }
+      const int ps = static_cast<int>(vi % S), hs = static_cast<int>(vi % NS);
+      if (graph_on_device) {
+        // 2. the pool of this visit, drawn on the device right before the kernel that reads
+        //    it (same stream: the pool's previous reader is done, its next reader waits)
+        const uint32_t w3 = level_word(level, q);
+        auto fill = [&](int32_t lo, int32_t cnt, int32_t olo, int32_t ohi, int32_t side, int32_t *pool) {
+          if (cnt <= 0) return;
+          const int blocks = static_cast<int>(std::min<int64_t>((static_cast<int64_t>(cnt) + 255) / 256, 65536));
+          if (g_host->xadj_is64)
+            hipLaunchKernelGGL(fill_pool_kernel<int64_t>, dim3(blocks), dim3(256), 0, compute,
+                               static_cast<const int64_t *>(g_host->xadj), g_host->adj, lo, cnt, olo, ohi, side, B,
+                               per_round, key0, key1, rot, w3, pool);
+          else
+            hipLaunchKernelGGL(fill_pool_kernel<int32_t>, dim3(blocks), dim3(256), 0, compute,
+                               static_cast<const int32_t *>(g_host->xadj), g_host->adj, lo, cnt, olo, ohi, side, B,
+                               per_round, key0, key1, rot, w3, pool);
+        };
+        fill(L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, dpool[ps]);
+        if (a != b)
+          fill(L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, dpool[ps] + static_cast<size_t>(L.part_rows) * B);
+        if ((rc = gosh::check_launch("fill_pool_kernel"))) break;
+        PARTS_HIP(hipEventRecord(pool_ready[ps], compute), "hipEventRecord");
+        // marks, on the inbound stream, the point up to which this visit's parts are in
+        PARTS_HIP(hipEventRecord(arrived, copy), "hipEventRecord");
+      } else {
       // 2. the pool of this visit: wait for the sampler, upload on the copy stream
       {
         const auto t_wait = std::chrono::steady_clock::now();
@@ -548,7 +652,6 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         cv.wait(lock, [&] { return filled > vi; });
         st.sampler_wait_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_wait).count();
       }
-      const int ps = static_cast<int>(vi % S), hs = static_cast<int>(vi % NS);
       PARTS_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
       {
         const size_t side0 = static_cast<size_t>(L.size(a)) * B * 4;
@@ -564,6 +667,7 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       }
       PARTS_HIP(hipEventRecord(pool_ready[ps], copy), "hipEventRecord");
       PARTS_HIP(hipEventRecord(staging_done[hs], copy), "hipEventRecord");
+      }
       // 3. the pair kernel
       PARTS_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
       PARTS_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
@@ -605,13 +709,20 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         for (int64_t ahead = 1; ahead <= max_ahead && got == 0; ++ahead) got = ensure_parts(vi + ahead, keep);
         if (got == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
       }
-      // 5. hand the staging buffer back to the sampler once its upload is done
-      PARTS_HIP(hipEventSynchronize(staging_done[hs]), "hipEventSynchronize");
-      {
-        std::lock_guard<std::mutex> lock(mu);
-        released = vi + 1;
+      if (graph_on_device) {
+        // 5. nothing to hand back; only keep the host from running ahead: it continues once
+        //    the parts of this visit have arrived, as it does with a host sampler (with
+        //    several swaps queued at once the copies of a swap took four times as long)
+        PARTS_HIP(hipEventSynchronize(arrived), "hipEventSynchronize");
+      } else {
+        // 5. hand the staging buffer back to the sampler once its upload is done
+        PARTS_HIP(hipEventSynchronize(staging_done[hs]), "hipEventSynchronize");
+        {
+          std::lock_guard<std::mutex> lock(mu);
+          released = vi + 1;
+        }
+        cv.notify_all();
       }
-      cv.notify_all();
     }
     if (rc == GOSH_OK) {
       // write every resident part back
@@ -647,6 +758,7 @@ done:
   if (compute) (void)hipStreamSynchronize(compute);
   if (copy) (void)hipStreamSynchronize(copy);
   if (copy_out) (void)hipStreamSynchronize(copy_out);
+  if (arrived) (void)hipEventDestroy(arrived);
   for (auto e : chunk_flushed) if (e) (void)hipEventDestroy(e);
   for (auto e : k_begin) if (e) (void)hipEventDestroy(e);
   for (auto e : k_end) if (e) (void)hipEventDestroy(e);

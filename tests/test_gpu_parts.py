@@ -12,6 +12,7 @@ from tests.linkpred import aucroc, make_eval_sets
 from tests.util import rel_err
 
 pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
 
 
 def say(msg):
@@ -136,6 +137,36 @@ def test_sequential_blocked_rotation_matches_oracle(n, d, K, P, S, B, k, epochs)
         assert rel_err(runs["paper"][0], want) > 1e-4  # the other order gives another result
     if block > 1 and K >= 2 * P:
         assert st["bytes_h2d"] < 0.85 * runs["paper"][1]["bytes_h2d"]
+
+
+@pytest.mark.parametrize("offsets64", [False, True])
+@pytest.mark.parametrize("order_flag", [0, G.GOSH_FLAG_BLOCKED_ORDER])
+def test_device_resident_graph_gives_the_same_rotation(offsets64, order_flag):
+    """A graph in device memory is sampled on the device (no host sampler, no pool uploads):
+    the positives, hence the whole sequential rotation, must be bit for bit what the host
+    sampler gives, and the oracle's within the usual bar."""
+    n, d, K, P, S, B, k, epochs = 1300, 32, 7, 4, 2, 3, 3, 45
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 5 * n, 8), offsets64=offsets64)
+    M0 = (O.init_embedding(n, d, 3, 0).astype(np.float64) * d * 0.8).astype(np.float32)
+    want = M0.copy()
+    O.train_parts(c.xadj.numpy(), c.adj.numpy(), want, k, epochs, 0.1, 7, 1, K, B,
+                  block=O.blocked_block_size(P, K) if order_flag else 0)
+    got = {}
+    for where in ("host", "device"):
+        xadj = c.xadj if where == "host" else c.xadj.to(DEV)
+        adj = c.adj if where == "host" else c.adj.to(DEV)
+        M = torch.from_numpy(M0.copy()).pin_memory()
+        st = G.gosh_train_parts(n, xadj, adj, M, k, epochs, 0.1, 7, level=1, P_gpu=P, S_gpu=S, B=B,
+                                force_K=K, flags=G.GOSH_FLAG_SEQUENTIAL | order_flag)
+        got[where] = (M.numpy().copy(), st)
+    assert np.array_equal(got["host"][0], got["device"][0])
+    assert got["device"][1]["sampler_ms"] == 0 and got["host"][1]["sampler_ms"] > 0
+    assert got["device"][1]["bytes_h2d"] < got["host"][1]["bytes_h2d"]  # no pools go up
+    assert rel_err(got["device"][0], want) <= 1e-5
+    # concurrent mode with the hot-row bitmap built on the device: nothing moves at lr = 0
+    M = torch.from_numpy(M0.copy()).pin_memory()
+    G.gosh_train_parts(n, c.xadj.to(DEV), c.adj.to(DEV), M, k, epochs, 0.0, 7, force_K=K, flags=order_flag)
+    assert np.array_equal(M.numpy(), M0)
 
 
 @pytest.mark.parametrize("flags", [0, G.GOSH_FLAG_PLAIN_STORES])
