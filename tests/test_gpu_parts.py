@@ -106,6 +106,8 @@ def test_unpinned_host_matrix_and_forced_split():
     (1100, 32, 7, 6, 2, 3, 3, 50),   # blocks of four
     (500, 8, 2, 4, 2, 2, 3, 10),     # fewer parts than slots: one block, the paper's order
     (9, 8, 4, 4, 2, 2, 3, 16),       # an empty last part
+    (700, 16, 5, 2, 1, 1, 2, 10),    # two slots only: nothing can be fetched ahead
+    (800, 16, 11, 8, 1, 1, 0, 22),   # more slots than a block can use up; no negatives
 ])
 def test_sequential_blocked_rotation_matches_oracle(n, d, K, P, S, B, k, epochs):
     """GOSH_FLAG_BLOCKED_ORDER: the rotation visits the pairs in the blocked order (blocks of
