@@ -450,6 +450,8 @@ extern "C" {
 
 int gosh_csr_validate(const gosh_csr *g_host) {
   if (int rc = gosh::check_csr(g_host)) return rc;
+  if (gosh::is_device_pointer(g_host->xadj) || gosh::is_device_pointer(g_host->adj))
+    return gosh::fail(GOSH_EINVAL, "gosh_csr_validate takes a host graph");
   return g_host->xadj_is64 ? validate<int64_t>(g_host) : validate<int32_t>(g_host);
 }
 
@@ -471,7 +473,11 @@ static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_s
     h->levels.emplace_back();
     h->levels[0].n = g0_host->n;
     h->levels[0].nnz = g0_host->nnz;
-    const bool g0_on_device = on_device && gosh::is_device_pointer(g0_host->xadj);
+    const bool g0_on_device = gosh::is_device_pointer(g0_host->xadj);
+    if (g0_on_device && !on_device) {
+      delete h;
+      return gosh::fail(GOSH_EINVAL, "gosh_coarsen takes a host graph (gosh_coarsen_device takes either)");
+    }
     const bool wants_levels = g0_host->n > threshold && max_levels > 1;
     if (g0_on_device) {
       // a device-resident G_0 is adopted as it is; its host copy is made if someone asks

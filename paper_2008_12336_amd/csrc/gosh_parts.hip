@@ -283,6 +283,8 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
                            int32_t k_neg, uint64_t seed, uint32_t rotation, uint32_t level,
                            uint32_t pair_index, int32_t *out_host) {
   if (int rc = gosh::check_csr(g_host)) return rc;
+  if (gosh::is_device_pointer(g_host->xadj) || gosh::is_device_pointer(g_host->adj))
+    return gosh::fail(GOSH_EINVAL, "gosh_parts_sample_pair takes a host graph");
   if (K < 1 || K > kMaxParts || pa < 0 || pb < 0 || pa >= K || pb >= K || pb > pa)
     return gosh::fail(GOSH_EINVAL, "need 0 <= pb <= pa < K <= %d", kMaxParts);
   if (B < 1 || B > 64 || k_neg < 0 || k_neg > GOSH_MAX_NEG || out_host == nullptr)

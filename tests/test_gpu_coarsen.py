@@ -1,6 +1,8 @@
 """gosh_coarsen_device (Alg. 4 on the GPU: degree sort, marking rounds, CSR rebuild) against
 the oracle and against gosh_coarsen: the hierarchy is unique, so everything is compared
 bit for bit."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -185,3 +187,9 @@ def test_device_resident_input_graph(offsets64):
         G.gosh_coarsen_device(n, xd, c.adj, threshold=100)
     with pytest.raises(TypeError):
         G.gosh_coarsen(n, xd, ad, threshold=100)
+    # the C entry points that read the graph on the host refuse device memory themselves
+    gd = G.csr_view(n, xd, ad)
+    out = C.c_void_p()
+    assert G.lib().gosh_coarsen(C.byref(gd), 100, 1.0, 64, 0, C.byref(out)) == -1
+    assert "host graph" in G.gosh_last_error()
+    assert G.lib().gosh_csr_validate(C.byref(gd)) == -1
