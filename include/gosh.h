@@ -164,6 +164,10 @@ int gosh_hierarchy_times(const gosh_hierarchy *h, int32_t i, double *ms3);
 void gosh_hierarchy_free(gosh_hierarchy *h);
 
 /* ---- device entry points ---------------------------------------------------------- */
+/* Every array these take must be memory a kernel can reach -- a device allocation, or
+ * pinned host memory -- and must hold the documented number of elements inside the
+ * allocation it starts in; both are checked before anything is launched (GOSH_EINVAL), so
+ * that a wrong pointer or size becomes an error and not a memory fault on the device. */
 
 /* "Randomly initialize M" (Alg. 2, second line).  Fills the device matrix M (n x d)
  * with values uniform in [-0.5/d, 0.5/d): entry (v, c) is word c%4 of

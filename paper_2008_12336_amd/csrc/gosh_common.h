@@ -18,6 +18,11 @@ int fail(int code, const char *fmt, ...);
 int check_dim(int32_t d);
 int check_matrix(const float *M, int32_t d, const char *what);
 int check_csr(const gosh_csr *g);
+// The span [p, p + bytes) must be memory a kernel can reach: a device allocation that holds
+// all of it, or pinned host memory.  GOSH_EINVAL otherwise (pageable host memory, a span
+// running past its allocation) -- a kernel would fault on it.
+int check_device_span(const void *p, size_t bytes, const char *what);
+int check_device_csr(const gosh_csr *g);  // both arrays of a device-resident graph
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 

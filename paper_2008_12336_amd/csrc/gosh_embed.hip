@@ -374,6 +374,11 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
                gosh_level_stats *stats, void *hip_stream) {
   if (int rc = check_common(d, k_neg)) return rc;
   if (int rc = gosh::check_matrix(M0_dev, d, "M0")) return rc;
+  {
+    gosh_csr g0{};
+    if (int rc = gosh::hierarchy_shape(h, 0, &g0)) return rc;
+    if (int rc = gosh::check_device_span(M0_dev, static_cast<size_t>(g0.n) * d * 4, "M0")) return rc;
+  }
   // A level above level 0 can only exceed the budget if level 0 does too, which is refused.
   const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
   const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,

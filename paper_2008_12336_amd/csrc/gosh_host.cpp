@@ -43,6 +43,35 @@ int check_csr(const gosh_csr *g) {
   return GOSH_OK;
 }
 
+int check_device_span(const void *p, size_t bytes, const char *what) {
+  // The runtime answers for every address: memory it does not know (pageable host memory,
+  // a stale or made-up pointer) comes back as "unregistered", not as an error.
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(GOSH_EINVAL, "%s is not memory a kernel can reach (device or pinned host memory is needed)", what);
+  }
+  if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeManaged)
+    return fail(GOSH_EINVAL, "%s is not memory a kernel can reach (device or pinned host memory is needed)", what);
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange(&base, &size, const_cast<void *>(p)) == hipSuccess) {
+    const char *end = static_cast<const char *>(p) + bytes;
+    if (end > static_cast<const char *>(base) + size)
+      return fail(GOSH_EINVAL, "%s: %zu bytes do not fit the allocation they start in", what, bytes);
+  } else {
+    (void)hipGetLastError();
+  }
+  return GOSH_OK;
+}
+
+int check_device_csr(const gosh_csr *g) {
+  if (int rc = check_device_span(g->xadj, static_cast<size_t>(g->n + 1) * (g->xadj_is64 ? 8 : 4), "xadj")) return rc;
+  if (g->nnz > 0)
+    if (int rc = check_device_span(g->adj, static_cast<size_t>(g->nnz) * 4, "adj")) return rc;
+  return GOSH_OK;
+}
+
 int check_launch(const char *kernel) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(GOSH_EHIP, "%s: %s", kernel, hipGetErrorString(e));

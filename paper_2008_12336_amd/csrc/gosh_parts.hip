@@ -363,6 +363,8 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   const int host_threads = std::max(1, omp_get_max_threads());
   // A graph in device memory is sampled there (no sampler thread, no pool uploads).
   const bool graph_on_device = gosh::is_device_pointer(g_host->xadj);
+  if (graph_on_device)
+    if (int rc0 = gosh::check_device_csr(g_host)) return rc0;
   const HostCsr csr{g_host};
   const size_t pool_ints = static_cast<size_t>(2) * L.part_rows * B;  // side 0 then side 1
 

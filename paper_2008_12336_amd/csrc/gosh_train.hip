@@ -232,6 +232,7 @@ int gosh_init_embedding(float *M_dev, int64_t n, int32_t d, uint64_t seed, uint3
                         void *hip_stream) {
   if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
   if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
+  if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(n) * d * 4, "M")) return rc;
   return gosh::init_rows(M_dev, 0, n, d, seed, level, gosh::as_stream(hip_stream));
 }
 
@@ -241,6 +242,8 @@ int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint3
   if (k_neg < 0 || k_neg > GOSH_MAX_NEG)
     return gosh::fail(GOSH_EINVAL, "k_neg = %d: must be in [0, %d]", k_neg, GOSH_MAX_NEG);
   if (out_dev == nullptr) return gosh::fail(GOSH_EINVAL, "out is null");
+  if (int rc = gosh::check_device_csr(g_dev)) return rc;
+  if (int rc = gosh::check_device_span(out_dev, static_cast<size_t>(g_dev->n) * (k_neg + 1) * 4, "out")) return rc;
   const SamplerArgs s = sampler_args(g_dev, seed, epoch, level);
   const int blocks = grid_for(g_dev->n * (k_neg + 1), 256, 1 << 16);
   if (g_dev->xadj_is64)
@@ -264,6 +267,8 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
   if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
     return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
   if (!(lr_epoch == lr_epoch)) return gosh::fail(GOSH_EINVAL, "lr is NaN");
+  if (int rc = gosh::check_device_csr(g_dev)) return rc;
+  if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(g_dev->n) * d * 4, "M")) return rc;
 
   hipStream_t st = gosh::as_stream(hip_stream);
   if (g_dev->xadj_is64)
@@ -279,6 +284,9 @@ int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map
   if (n_coarse < 1 || n_fine < 1)
     return gosh::fail(GOSH_EINVAL, "need n_coarse (%lld) >= 1 and n_fine (%lld) >= 1",
                       (long long)n_coarse, (long long)n_fine);
+  if (int rc = gosh::check_device_span(M_coarse_dev, static_cast<size_t>(n_coarse) * d * 4, "M_coarse")) return rc;
+  if (int rc = gosh::check_device_span(M_fine_dev, static_cast<size_t>(n_fine) * d * 4, "M_fine")) return rc;
+  if (int rc = gosh::check_device_span(map_dev, static_cast<size_t>(n_fine) * 4, "map")) return rc;
   const int64_t total4 = n_fine * (d / 4);
   hipLaunchKernelGGL(project_kernel, dim3(grid_for(total4, 256, 1 << 16)), dim3(256), 0,
                      gosh::as_stream(hip_stream), reinterpret_cast<const float4 *>(M_coarse_dev),

@@ -267,3 +267,33 @@ def test_project_bit_exact(nc, nf, d):
     G.gosh_project(torch.from_numpy(Mc).to(DEV), torch.from_numpy(m).to(DEV), out)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), O.project(Mc, m))
+
+
+def test_operands_a_kernel_cannot_reach_are_refused():
+    """Pageable host memory, or a span that runs past its device allocation, would make a
+    kernel fault: the entry points check where their operands live and refuse with
+    GOSH_EINVAL instead of launching."""
+    import ctypes as C
+
+    n, d, k = 1000, 32, 3
+    c = graphgen.to_csr(n, graphgen.er_gnm(n, 4000, 1))
+    dev = c.to(DEV)
+    lib = G.lib()
+    M_host = torch.zeros(n, d, dtype=torch.float32)
+    M_dev = torch.zeros(n, d, dtype=torch.float32, device=DEV)
+    g_dev = G.csr_view(n, dev.xadj, dev.adj)
+    g_host = G.csr_view(n, c.xadj, c.adj)
+    # the matrix in pageable host memory
+    assert lib.gosh_train_epoch(C.byref(g_dev), M_host.data_ptr(), d, k, 0.1, 1, 0, 0, 0, None) == -1
+    assert "reach" in G.gosh_last_error()
+    # the graph in pageable host memory
+    assert lib.gosh_train_epoch(C.byref(g_host), M_dev.data_ptr(), d, k, 0.1, 1, 0, 0, 0, None) == -1
+    assert lib.gosh_sample_epoch(C.byref(g_host), k, 1, 0, 0, M_dev.data_ptr(), None) == -1
+    assert lib.gosh_init_embedding(M_host.data_ptr(), n, d, 1, 0, None) == -1
+    # a matrix far smaller than n x d: its own allocation of 64 rows, asked to hold 2^22
+    small = torch.empty(1 << 22, dtype=torch.uint8, device=DEV)  # a 4 MiB block of its own
+    assert lib.gosh_init_embedding(small.data_ptr(), 1 << 22, d, 1, 0, None) == -1
+    assert "do not fit" in G.gosh_last_error()
+    # and the device still works
+    G.gosh_train_epoch(g_dev, M_dev, k, 0.1, 1, 0, 0, G.GOSH_FLAG_SEQUENTIAL)
+    torch.cuda.synchronize()
