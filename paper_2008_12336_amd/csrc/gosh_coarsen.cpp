@@ -351,7 +351,30 @@ int64_t coarsen_level(gosh_hierarchy &h, int threads) {
 }
 
 // Host copies of a device-built level, made on first request.
+int ensure_host_graph_impl(gosh_hierarchy &h, gosh_hierarchy::Level &l);
+int ensure_host_map_impl(gosh_hierarchy &h, gosh_hierarchy::Level &l);
+int ensure_host_mult_impl(gosh_hierarchy &h, gosh_hierarchy::Level &l);
+
+// The accessors that call these are C entry points: an allocation failure becomes a status.
+template <typename F>
+int no_throw(F &&f) {
+  try {
+    return f();
+  } catch (const std::bad_alloc &) {
+    return gosh::fail(GOSH_ENOMEM, "out of host memory while copying a level to the host");
+  }
+}
 int ensure_host_graph(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+  return no_throw([&] { return ensure_host_graph_impl(h, l); });
+}
+int ensure_host_map(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+  return no_throw([&] { return ensure_host_map_impl(h, l); });
+}
+int ensure_host_mult(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+  return no_throw([&] { return ensure_host_mult_impl(h, l); });
+}
+
+int ensure_host_graph_impl(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
   if (l.host_graph) return GOSH_OK;
   if (!l.dev.present()) return gosh::fail(GOSH_EINVAL, "level has neither a host nor a device copy");
   void *offsets = nullptr;
@@ -376,7 +399,7 @@ int ensure_host_graph(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
   return GOSH_OK;
 }
 
-int ensure_host_map(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+int ensure_host_map_impl(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
   if (l.host_map || !l.has_map) return GOSH_OK;
   if (l.dev.map == nullptr) return gosh::fail(GOSH_EINVAL, "map has neither a host nor a device copy");
   l.map.resize(static_cast<size_t>(l.n));
@@ -385,7 +408,7 @@ int ensure_host_map(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
   return GOSH_OK;
 }
 
-int ensure_host_mult(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
+int ensure_host_mult_impl(gosh_hierarchy &h, gosh_hierarchy::Level &l) {
   if (l.host_mult || !l.has_mult) return GOSH_OK;
   if (l.dev.mult == nullptr) return gosh::fail(GOSH_EINVAL, "multiplicities have neither a host nor a device copy");
   l.mult.resize(static_cast<size_t>(l.nnz));
