@@ -127,11 +127,18 @@ int gosh_coarsen(const gosh_csr *g0_host, int64_t threshold, double min_shrink,
  * host arrays behind gosh_hierarchy_graph / _map / _mult are downloaded on first request.
  * A graph whose marking does not resolve in a bounded number of rounds (long chains of
  * equal degrees) is marked on the host instead.  Device memory: about 36 bytes per entry
- * of G_0 while running, 12 bytes per entry of all levels afterwards (until
- * gosh_hierarchy_release_device or gosh_hierarchy_free, called with the same device
- * current).  GOSH_ENOMEM / GOSH_EHIP if the device cannot.  Blocking; null stream. */
+ * of G_0 while running; afterwards 12 bytes per entry of all levels, and the run's scratch
+ * blocks (about 32 bytes per entry of G_0), which stay allocated until
+ * gosh_hierarchy_trim_scratch, gosh_hierarchy_release_device or gosh_hierarchy_free
+ * (called with the same device current) because freeing them at once would slow the host
+ * link down for whatever follows (the driver clears freed memory in the background).
+ * GOSH_ENOMEM / GOSH_EHIP if the device cannot.  Blocking; null stream. */
 int gosh_coarsen_device(const gosh_csr *g0, int64_t threshold, double min_shrink,
                         int32_t max_levels, int32_t n_threads, gosh_hierarchy **out);
+
+/* Returns the scratch blocks a device-built hierarchy still holds from its construction
+ * (no-op otherwise).  The levels stay where they are. */
+int gosh_hierarchy_trim_scratch(gosh_hierarchy *h);
 
 /* Brings every array of a device-built hierarchy to the host and frees its device copies
  * (no-op for a host-built one).  Accessors and training keep working, from the host

@@ -57,6 +57,7 @@ EXPORTS = {
     "gosh_coarsen_device": (C.c_int, [C.POINTER(gosh_csr), C.c_int64, C.c_double, C.c_int32,
                                       C.c_int32, C.POINTER(C.c_void_p)]),
     "gosh_hierarchy_release_device": (C.c_int, [C.c_void_p]),
+    "gosh_hierarchy_trim_scratch": (C.c_int, [C.c_void_p]),
     "gosh_hierarchy_levels": (C.c_int, [C.c_void_p]),
     "gosh_hierarchy_shape": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64),
                                        C.POINTER(C.c_int64)]),
@@ -210,6 +211,10 @@ class Hierarchy:
             lib().gosh_hierarchy_free(self._h)
             self._h = None
 
+    def trim_scratch(self) -> None:
+        """Return the device scratch blocks kept from the construction of the hierarchy."""
+        _check(lib().gosh_hierarchy_trim_scratch(self._h))
+
     def release_device(self) -> None:
         """Bring a device-built hierarchy to the host and free its device copies."""
         _check(lib().gosh_hierarchy_release_device(self._h))
@@ -320,6 +325,10 @@ def gosh_hierarchy_mult(h: Hierarchy, i: int):
 
 def gosh_hierarchy_times(h: Hierarchy, i: int):
     return h.times(i)
+
+
+def gosh_hierarchy_trim_scratch(h: Hierarchy) -> None:
+    h.trim_scratch()
 
 
 def gosh_hierarchy_release_device(h: Hierarchy) -> None:

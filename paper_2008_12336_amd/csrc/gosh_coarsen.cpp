@@ -547,7 +547,10 @@ static int coarsen_impl(const gosh_csr *g0_host, int64_t threshold, double min_s
       }
       if (static_cast<double>(n_coarse) > min_shrink * static_cast<double>(n_fine)) break;
     }
-    gosh::device_coarsener_trim(h->dc);
+    // The scratch blocks of the run stay with the hierarchy (gosh_hierarchy_trim_scratch or
+    // freeing it returns them): the driver clears freed device memory in the background for
+    // seconds, and host<->device copies that run meanwhile -- those of a rotation that
+    // follows the coarsening at once -- make half their rate.
     *out = h;
     return GOSH_OK;
   } catch (const std::bad_alloc &) {
@@ -610,8 +613,14 @@ int gosh_hierarchy_mult(const gosh_hierarchy *h, int32_t i, const int64_t **mult
   return GOSH_OK;
 }
 
+int gosh_hierarchy_trim_scratch(gosh_hierarchy *h) {
+  if (h != nullptr) gosh::device_coarsener_trim(h->dc);
+  return GOSH_OK;
+}
+
 int gosh_hierarchy_release_device(gosh_hierarchy *h) {
   if (h == nullptr) return GOSH_OK;
+  gosh::device_coarsener_trim(h->dc);
   for (gosh_hierarchy::Level &l : h->levels) {
     if (int rc = ensure_host_graph(*h, l)) return rc;
     if (int rc = ensure_host_map(*h, l)) return rc;

@@ -129,6 +129,9 @@ def test_release_device_keeps_everything_readable():
     xadj, adj = c.xadj.numpy(), c.adj.numpy()
     graphs, maps, mults = O.coarsen(xadj, adj, threshold=100, min_shrink=1.0)
     h = G.gosh_coarsen_device(n, c.xadj, c.adj, threshold=100, min_shrink=1.0)
+    h.trim_scratch()  # the levels stay on the device
+    h.trim_scratch()
+    assert np.array_equal(h.map(0), maps[0])
     h.release_device()
     assert_same_hierarchy(h, graphs, maps, mults)
     # training from the released (host) copies still works and agrees with the oracle's shapes
