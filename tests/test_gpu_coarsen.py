@@ -196,3 +196,21 @@ def test_device_resident_input_graph(offsets64):
     assert G.lib().gosh_coarsen(C.byref(gd), 100, 1.0, 64, 0, C.byref(out)) == -1
     assert "host graph" in G.gosh_last_error()
     assert G.lib().gosh_csr_validate(C.byref(gd)) == -1
+
+
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+_graphs = st.integers(min_value=2, max_value=90).flatmap(
+    lambda n: st.tuples(st.just(n), st.lists(
+        st.tuples(st.integers(0, n - 1), st.integers(0, n - 1)), min_size=0, max_size=6 * n)))
+
+
+@settings(max_examples=60, deadline=None)
+@given(_graphs, st.booleans())
+def test_device_random_tiny_graphs_match_oracle(g, offsets64):
+    n, pairs = g
+    xadj, adj = csr_from_pairs(n, pairs)
+    graphs, maps, mults = O.coarsen(xadj, adj, threshold=1, min_shrink=1.0)
+    h = device_hierarchy(n, xadj, adj, offsets64, threshold=1, min_shrink=1.0)
+    assert_same_hierarchy(h, graphs, maps, mults)
+    h.free()
