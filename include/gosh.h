@@ -8,7 +8,10 @@
  *   - Graphs are CSR (Sec. 3.2.1 of the paper): adj holds the neighbour lists back to
  *     back, xadj holds n+1 offsets into it, xadj[n] == nnz.  Rows must be sorted
  *     ascending, without duplicates or self loops (gosh_csr_validate checks a host
- *     copy; the device entry points trust the caller).
+ *     copy).  The training entry points do not verify this, but no array content can
+ *     take their kernels outside the operands: a row whose offsets leave adj counts
+ *     as empty, an entry that names no vertex (or, in the part-pair rotation, no vertex
+ *     of the partner part) is no sample.  What such a graph trains is unspecified.
  *   - The embedding matrix M is n x d, row-major fp32, 16-byte aligned, d a multiple
  *     of 4 with 4 <= d <= 512.
  *   - Every function returns GOSH_OK (0) or a negative gosh_status; the message of the
@@ -215,9 +218,9 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
 
 /* "ExpandEmbedding" (Alg. 2; Sec. 3: the row of a vertex of G_{i-1} is the row of its
  * super vertex in G_i): M_fine[v,:] = M_coarse[map[v],:] for v < n_fine.  All pointers
- * are device memory; map holds n_fine ids in [0, n_coarse) (trusted).  M_fine and
- * M_coarse must not overlap.  A slice of the fine level can be projected by passing the
- * matching slice of map and of M_fine. */
+ * are device memory; map holds n_fine ids in [0, n_coarse); an entry outside that range
+ * gives a row of zeros.  M_fine and M_coarse must not overlap.  A slice of the fine level
+ * can be projected by passing the matching slice of map and of M_fine. */
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev,
                  int64_t n_fine, int32_t d, float *M_fine_dev, void *hip_stream);
 

@@ -63,8 +63,11 @@ struct PairWork {
     const int side = i >= a_n;
     const int64_t local = side ? i - a_n : i;
     const int32_t *pool = side ? pool_b : pool_a;
-    const int32_t from_pool = pool[(want && positive) ? local * B + t / per_round : 0];
     const int32_t other_lo = side ? a_lo : b_lo, other_n = side ? a_n : b_n;
+    // a pool entry outside the partner part (the rows of a malformed graph can yield one)
+    // is no sample: the kernel never leaves the two slots
+    int32_t from_pool = pool[(want && positive) ? local * B + t / per_round : 0];
+    if (static_cast<uint32_t>(from_pool - other_lo) >= static_cast<uint32_t>(other_n)) from_pool = -1;
     const uint64_t r = philox_draw(static_cast<uint32_t>(src),
                                    static_cast<uint32_t>(side * B * per_round + t), rotation, word3,
                                    key0, key1);
@@ -95,15 +98,17 @@ __global__ __launch_bounds__(256) void pair_stream_kernel(PairWork w, int32_t sa
 // sampler, one thread per source.
 template <typename OffT>
 __global__ __launch_bounds__(256) void fill_pool_kernel(const OffT *__restrict__ xadj,
-                                                        const int32_t *__restrict__ adj, int32_t lo, int32_t cnt,
-                                                        int32_t olo, int32_t ohi, int32_t side, int32_t B,
+                                                        const int32_t *__restrict__ adj, int64_t nnz,
+                                                        int32_t lo, int32_t cnt, int32_t olo, int32_t ohi,
+                                                        int32_t side, int32_t B,
                                                         int32_t per_round, uint32_t key0, uint32_t key1,
                                                         uint32_t rotation, uint32_t word3,
                                                         int32_t *__restrict__ pool) {
   for (int64_t local = blockIdx.x * 256LL + threadIdx.x; local < cnt; local += gridDim.x * 256LL) {
     const int64_t src = static_cast<int64_t>(lo) + local;
-    const int64_t end = static_cast<int64_t>(xadj[src + 1]);
-    int64_t first = static_cast<int64_t>(xadj[src]), hi = end;
+    int64_t first = static_cast<int64_t>(xadj[src]), end = static_cast<int64_t>(xadj[src + 1]);
+    if (first < 0 || first > end || end > nnz) first = end = 0;  // offsets that leave adj: an empty row
+    int64_t hi = end;
     while (first < hi) {  // first entry >= olo
       const int64_t mid = first + (hi - first) / 2;
       if (adj[mid] < olo) first = mid + 1;
@@ -139,7 +144,8 @@ __global__ __launch_bounds__(256) void degree_bitmap_kernel(const OffT *__restri
     uint64_t word = 0;
     for (int bit = 0; bit < 64; ++bit) {
       const int64_t v = w * 64 + bit;
-      if (v < n && static_cast<int64_t>(xadj[v + 1] - xadj[v]) >= min_degree) word |= uint64_t{1} << bit;
+      if (v < n && static_cast<int64_t>(xadj[v + 1]) - static_cast<int64_t>(xadj[v]) >= min_degree)
+        word |= uint64_t{1} << bit;
     }
     bits[w] = word;
   }
@@ -634,11 +640,11 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
           const int blocks = static_cast<int>(std::min<int64_t>((static_cast<int64_t>(cnt) + 255) / 256, 65536));
           if (g_host->xadj_is64)
             hipLaunchKernelGGL(fill_pool_kernel<int64_t>, dim3(blocks), dim3(256), 0, compute,
-                               static_cast<const int64_t *>(g_host->xadj), g_host->adj, lo, cnt, olo, ohi, side, B,
+                               static_cast<const int64_t *>(g_host->xadj), g_host->adj, g_host->nnz, lo, cnt, olo, ohi, side, B,
                                per_round, key0, key1, rot, w3, pool);
           else
             hipLaunchKernelGGL(fill_pool_kernel<int32_t>, dim3(blocks), dim3(256), 0, compute,
-                               static_cast<const int32_t *>(g_host->xadj), g_host->adj, lo, cnt, olo, ohi, side, B,
+                               static_cast<const int32_t *>(g_host->xadj), g_host->adj, g_host->nnz, lo, cnt, olo, ohi, side, B,
                                per_round, key0, key1, rot, w3, pool);
         };
         fill(L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, dpool[ps]);

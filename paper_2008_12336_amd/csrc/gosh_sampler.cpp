@@ -101,7 +101,9 @@ void fill_pool(const gosh_csr &g, int32_t lo, int32_t cnt, int32_t olo, int32_t 
     for (int l = 0; l < kLanes; ++l) {
       // lanes beyond the part repeat its last source; their draws are discarded
       const int64_t v = static_cast<int64_t>(lo) + local0 + std::min(l, lanes - 1);
-      const int32_t *begin = adj + row_begin(g, v), *end = adj + row_begin(g, v + 1);
+      int64_t row_lo = row_begin(g, v), row_hi = row_begin(g, v + 1);
+      if (row_lo < 0 || row_lo > row_hi || row_hi > g.nnz) row_lo = row_hi = 0;  // offsets that leave adj
+      const int32_t *begin = adj + row_lo, *end = adj + row_hi;
       first[l] = std::lower_bound(begin, end, olo);
       candidates[l] = static_cast<uint32_t>(std::lower_bound(first[l], end, ohi) - first[l]);
       src[l] = static_cast<uint32_t>(v);

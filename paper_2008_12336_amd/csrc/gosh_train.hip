@@ -24,10 +24,20 @@ using gosh::scale_draw;
 struct SamplerArgs {
   const void *xadj;
   const int32_t *adj;
+  int64_t nnz;
   uint32_t n;
   uint32_t key0, key1;
   uint32_t epoch, level;
 };
+
+// Number of entries of the row [begin, end) that may be read.  The kernels stay inside
+// their operands whatever the graph arrays hold: a row that the offsets place outside adj
+// counts as empty, and an entry that names no vertex is no sample.
+template <typename OffT>
+__device__ __forceinline__ uint32_t row_entries(OffT begin, OffT end, int64_t nnz) {
+  const bool inside = begin >= 0 && begin <= end && static_cast<int64_t>(end) <= nnz;
+  return inside ? static_cast<uint32_t>(end - begin) : 0u;
+}
 
 // Sample j of source src: j = 0 positive (uniform neighbour, -1 if none), j >= 1
 // negative (uniform vertex).
@@ -37,9 +47,10 @@ __device__ __forceinline__ int32_t draw_sample(const SamplerArgs &a, uint32_t sr
   if (j != 0) return static_cast<int32_t>(scale_draw(r, a.n));
   const OffT *xadj = static_cast<const OffT *>(a.xadj);
   const OffT begin = xadj[src];
-  const uint32_t deg = static_cast<uint32_t>(xadj[src + 1] - begin);
+  const uint32_t deg = row_entries(begin, xadj[src + 1], a.nnz);
   if (deg == 0) return -1;
-  return a.adj[begin + static_cast<OffT>(scale_draw(r, deg))];
+  const int32_t neighbour = a.adj[begin + static_cast<OffT>(scale_draw(r, deg))];
+  return static_cast<uint32_t>(neighbour) < a.n ? neighbour : -1;
 }
 
 template <typename OffT>
@@ -72,13 +83,14 @@ struct EpochWork {
                                    s.level, s.key0, s.key1);
     const OffT *xadj = static_cast<const OffT *>(s.xadj);
     const OffT begin = xadj[src];
-    const uint32_t deg = static_cast<uint32_t>(xadj[src + 1] - begin);
+    const uint32_t deg = row_entries(begin, xadj[src + 1], s.nnz);
     const bool read_adj = want && positive && deg != 0;
     const int32_t *entry = read_adj ? s.adj + (begin + static_cast<OffT>(scale_draw(r, deg)))
                                     : reinterpret_cast<const int32_t *>(xadj);
     const int32_t neighbour = *entry;
     const int32_t uniform = static_cast<int32_t>(scale_draw(r, s.n));
-    const int32_t id = positive ? (read_adj ? neighbour : -1) : uniform;
+    const bool is_vertex = static_cast<uint32_t>(neighbour) < s.n;
+    const int32_t id = positive ? (read_adj && is_vertex ? neighbour : -1) : uniform;
     return want ? id : -1;
   }
   __device__ __forceinline__ float *sample_row(int64_t, int32_t v) const {
@@ -98,7 +110,7 @@ __global__ __launch_bounds__(256) void mark_hot_kernel(const OffT *__restrict__ 
   for (int64_t w = wave0; w < words; w += nwaves) {
     const int64_t v = w * 64 + lane;
     bool hot = false;
-    if (v < n) hot = static_cast<int64_t>(xadj[v + 1] - xadj[v]) >= min_degree;
+    if (v < n) hot = static_cast<int64_t>(xadj[v + 1]) - static_cast<int64_t>(xadj[v]) >= min_degree;
     const unsigned long long mask = __ballot(hot);
     if (lane == 0) bits[w] = mask;
   }
@@ -127,14 +139,16 @@ __global__ __launch_bounds__(256) void init_embedding_kernel(float4 *__restrict_
   }
 }
 
+// A map entry that names no coarse vertex gives a row of zeros.
 __global__ __launch_bounds__(256) void project_kernel(const float4 *__restrict__ coarse,
                                                       const int32_t *__restrict__ map,
                                                       float4 *__restrict__ fine, int64_t total4,
-                                                      int32_t d4) {
+                                                      int32_t d4, uint32_t n_coarse) {
   for (int64_t i = blockIdx.x * 256LL + threadIdx.x; i < total4; i += gridDim.x * 256LL) {
     const int64_t v = i / d4;
     const int32_t c4 = static_cast<int32_t>(i % d4);
-    fine[i] = coarse[static_cast<int64_t>(map[v]) * d4 + c4];
+    const uint32_t c = static_cast<uint32_t>(map[v]);
+    fine[i] = c < n_coarse ? coarse[static_cast<int64_t>(c) * d4 + c4] : float4{0.f, 0.f, 0.f, 0.f};
   }
 }
 
@@ -149,6 +163,7 @@ SamplerArgs sampler_args(const gosh_csr *g, uint64_t seed, uint32_t epoch, uint3
   SamplerArgs s;
   s.xadj = g->xadj;
   s.adj = g->adj;
+  s.nnz = g->nnz;
   s.n = static_cast<uint32_t>(g->n);
   s.key0 = static_cast<uint32_t>(seed);
   s.key1 = static_cast<uint32_t>(seed >> 32);
@@ -290,7 +305,8 @@ int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map
   const int64_t total4 = n_fine * (d / 4);
   hipLaunchKernelGGL(project_kernel, dim3(grid_for(total4, 256, 1 << 16)), dim3(256), 0,
                      gosh::as_stream(hip_stream), reinterpret_cast<const float4 *>(M_coarse_dev),
-                     map_dev, reinterpret_cast<float4 *>(M_fine_dev), total4, d / 4);
+                     map_dev, reinterpret_cast<float4 *>(M_fine_dev), total4, d / 4,
+                     static_cast<uint32_t>(std::min<int64_t>(n_coarse, 2147483647LL)));
   return gosh::check_launch("project_kernel");
 }
 

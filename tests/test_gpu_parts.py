@@ -208,3 +208,32 @@ def test_concurrent_rotation_aucroc():
     assert K >= 4 and st["device_bytes"] <= budget
     assert hg > 0.7
     assert abs(hg - ho) <= 0.01 and abs(fg - fo) <= 0.01
+
+
+@pytest.mark.parametrize("offsets64", [False, True])
+def test_malformed_graph_keeps_the_rotation_inside_its_slots(offsets64):
+    """Offsets that leave adj, entries that name no vertex and rows that are not ascending:
+    the samplers (host and device) treat such rows as empty or draw what is there, the pair
+    kernel drops every pool entry outside the partner part.  Both samplers make the same
+    probes, so the sequential rotation is the same bit for bit, and finite."""
+    from tests.util import corrupt
+
+    n, d, K, P, S, B, k, epochs = 1300, 32, 5, 3, 2, 3, 3, 30
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 5 * n, 8))
+    xadj, adj, _ = corrupt(c, offsets64, 2, stray=300)
+    M0 = (O.init_embedding(n, d, 3, 0).astype(np.float64) * d * 0.8).astype(np.float32)
+    got = {}
+    for where in ("host", "device"):
+        x, a = torch.from_numpy(xadj), torch.from_numpy(adj)
+        if where == "device":
+            x, a = x.to(DEV), a.to(DEV)
+        for flags in (G.GOSH_FLAG_SEQUENTIAL, 0):
+            print(f"malformed graph on the {where}, offsets64={offsets64}, flags {flags}", flush=True)
+            M = torch.from_numpy(M0.copy()).pin_memory()
+            G.gosh_train_parts(n, x, a, M, k, epochs, 0.1, 7, level=1, P_gpu=P, S_gpu=S, B=B, force_K=K,
+                               flags=flags)
+            assert np.isfinite(M.numpy()).all()
+            if flags:
+                got[where] = M.numpy().copy()
+    assert np.array_equal(got["host"], got["device"])
+    assert not np.array_equal(got["host"], M0)

@@ -14,7 +14,7 @@ import graphgen
 import paper_2008_12336_amd as G
 from oracle import gosh_oracle as O
 from tests.linkpred import aucroc, make_eval_sets
-from tests.util import csr_from_pairs, rel_err
+from tests.util import corrupt, csr_from_pairs, rel_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -297,3 +297,61 @@ def test_operands_a_kernel_cannot_reach_are_refused():
     # and the device still works
     G.gosh_train_epoch(g_dev, M_dev, k, 0.1, 1, 0, 0, G.GOSH_FLAG_SEQUENTIAL)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("offsets64", [False, True])
+def test_malformed_graph_keeps_the_kernels_inside_their_operands(offsets64):
+    """The training kernels trust no graph content: a row whose offsets leave adj counts as
+    empty, an entry that names no vertex is no sample.  Every other source draws what the
+    oracle draws on the intact graph, and training leaves a finite matrix."""
+    n, d, k = 3000, 32, 3
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 24000, 5))
+    good_xadj, good_adj = c.xadj.numpy().astype(np.int64), c.adj.numpy()
+    xadj, adj, touched = corrupt(c, offsets64, 1)
+    nnz = adj.size
+    # what the guards must decide, row by row, computed here on the host
+    lo, hi = xadj[:-1].astype(np.int64), xadj[1:].astype(np.int64)
+    row_ok = (lo >= 0) & (lo <= hi) & (hi <= nnz)
+    assert (~row_ok).sum() >= 12 and all(not row_ok[v] for v in touched)
+    want = O.sample_epoch(good_xadj, good_adj, k, 9, 2, 1)
+    # the intact rows: the same entry index is drawn; the entry itself may have been replaced
+    for v in range(n):
+        if v in touched or want[v, 0] < 0:
+            continue
+        j = good_xadj[v] + np.searchsorted(good_adj[good_xadj[v]:good_xadj[v + 1]], want[v, 0])
+        want[v, 0] = adj[j] if 0 <= adj[j] < n else -1
+    xadj_dev, adj_dev = torch.from_numpy(xadj).to(DEV), torch.from_numpy(adj).to(DEV)
+    g = G.csr_view(n, xadj_dev, adj_dev)
+    assert g.nnz == nnz
+    out = torch.empty(n, k + 1, dtype=torch.int32, device=DEV)
+    say(f"malformed graph, offsets64={offsets64}: sample stream")
+    G.gosh_sample_epoch(g, k, 9, 2, 1, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    rows = np.array([v not in touched for v in range(n)])
+    assert np.array_equal(got[rows], want[rows])
+    assert np.array_equal(got[:, 1:], want[:, 1:])
+    assert np.all(got[~rows, 0] == -1)
+    for flags in (G.GOSH_FLAG_SEQUENTIAL, 0):
+        say(f"malformed graph, offsets64={offsets64}: epoch with flags {flags}")
+        M = torch.from_numpy(O.init_embedding(n, d, 1, 0)).to(DEV)
+        G.gosh_train_epoch(g, M, k, 0.05, 9, 2, 1, flags)
+        torch.cuda.synchronize()
+        assert torch.isfinite(M).all()
+
+
+def test_projection_through_a_map_with_invalid_entries():
+    """A map entry that names no coarse vertex gives a row of zeros; the others are copied."""
+    n_fine, n_coarse, d = 500, 40, 16
+    rng = np.random.default_rng(3)
+    m = rng.integers(0, n_coarse, size=n_fine, dtype=np.int32)
+    bad = rng.choice(n_fine, size=20, replace=False)
+    m[bad] = np.resize(np.array([n_coarse, -1, 2**31 - 1, -2**31], dtype=np.int32), 20)
+    Mc = rng.standard_normal((n_coarse, d)).astype(np.float32)
+    out = torch.full((n_fine, d), 7.0, dtype=torch.float32, device=DEV)
+    G.gosh_project(torch.from_numpy(Mc).to(DEV), torch.from_numpy(m).to(DEV), out)
+    torch.cuda.synchronize()
+    want = np.zeros((n_fine, d), dtype=np.float32)
+    valid = (m >= 0) & (m < n_coarse)
+    want[valid] = Mc[m[valid]]
+    assert np.array_equal(out.cpu().numpy(), want)

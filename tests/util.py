@@ -48,3 +48,25 @@ def rel_err(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-30))
+
+
+def corrupt(c, offsets64, seed, stray=0):
+    """A copy of the CSR arrays with offsets that leave adj, entries that name no vertex and
+    `stray` entries replaced by arbitrary vertices (their rows are no longer ascending).
+    Returns (xadj, adj, rows whose offsets were touched)."""
+    rng = np.random.default_rng(seed)
+    n = c.xadj.numel() - 1
+    xadj = c.xadj.numpy().astype(np.int64 if offsets64 else np.int32).copy()
+    adj = c.adj.numpy().copy()
+    nnz = adj.size
+    where = rng.choice(np.arange(2, n - 2, 4), size=12, replace=False)  # no two touch one row
+    huge = (1 << 40) if offsets64 else 2**31 - 1
+    for v, bad in zip(where, [nnz + 7, -3, huge, -huge, nnz + 1, -1] * 2):
+        xadj[v] = bad
+    touched = set(int(v) for v in where) | set(int(v) - 1 for v in where)
+    entries = rng.choice(nnz, size=40, replace=False)
+    for j, bad in zip(entries, [n, -1, 2**31 - 1, -2**31, n + 100] * 8):
+        adj[j] = bad
+    for j in rng.choice(nnz, size=stray, replace=False):
+        adj[j] = rng.integers(0, n)
+    return xadj, adj, touched
