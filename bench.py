@@ -97,6 +97,8 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     t_coarsen = time.perf_counter() - t0
     coarsen_stages = [dict(level=i, **h.times(i)) for i in range(h.levels - 1)]
     budget = int(w.get("budget", 0)) if args.log2n is None else 0
+    if args.budget_gb is not None:
+        budget = int(args.budget_gb * (1 << 30))
     print(f"[bench] hierarchy of {h.levels} levels in {t_coarsen:.1f}s; budget {budget}",
           file=sys.stderr, flush=True)
     if budget:
@@ -207,6 +209,9 @@ def main() -> int:
     ap.add_argument("--s-gpu", type=int, default=4, help="--mode parts: device sample pools")
     ap.add_argument("--budget-ratio", type=float, default=4.2,
                     help="--mode parts: matrix bytes / device budget")
+    ap.add_argument("--budget-gb", type=float, default=None,
+                    help="--mode levels: device budget in GiB instead of the workload's "
+                         "(0 = none: every level resident)")
     ap.add_argument("--flags", type=int, default=0,
                     help="gosh_train_epoch flags (0 = default mix of plain stores and atomic adds)")
     ap.add_argument("--copy-calibration", action="store_true",

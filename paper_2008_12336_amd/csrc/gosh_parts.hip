@@ -442,7 +442,7 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   k_begin.assign(static_cast<size_t>(visits), nullptr);
   k_end.assign(static_cast<size_t>(visits), nullptr);
 
-  // ---- hot rows: degree rule evaluated on the host, bitmap uploaded once -----------------
+  // ---- hot rows: degree rule evaluated once, where the graph lives -----------------------
   if (!seq) {
     const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(d);
     const int64_t pair_sources = 2 * L.part_rows;
@@ -456,9 +456,9 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     if (flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
     if (mode == gosh::kHotBitmap) {
       const int64_t min_degree = g_host->nnz / (gosh::tuning().hot_inv_eps * in_flight * B) + 1;
+      const int64_t words = (n + 63) / 64;
+      PARTS_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
       if (graph_on_device) {
-        const int64_t words = (n + 63) / 64;
-        PARTS_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
         const int blocks = static_cast<int>(std::min<int64_t>((words + 255) / 256, 65536));
         if (g_host->xadj_is64)
           hipLaunchKernelGGL(degree_bitmap_kernel<int64_t>, dim3(blocks), dim3(256), 0, nullptr,
@@ -470,23 +470,20 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
                              reinterpret_cast<uint64_t *>(hot_bits_dev));
         if ((rc = gosh::check_launch("degree_bitmap_kernel"))) goto done;
         PARTS_HIP(hipDeviceSynchronize(), "hot bitmap");
-        hot.bits = hot_bits_dev;
-      }
-      std::vector<uint64_t> bits(graph_on_device ? 0 : static_cast<size_t>((n + 63) / 64), 0);
+      } else {
+        std::vector<uint64_t> bits(static_cast<size_t>(words), 0);
 #pragma omp parallel for num_threads(host_threads) schedule(static)
-      for (int64_t w64 = 0; w64 < static_cast<int64_t>(bits.size()); ++w64) {
-        uint64_t word = 0;
-        for (int bit = 0; bit < 64; ++bit) {
-          const int64_t v = w64 * 64 + bit;
-          if (v < n && csr.begin(v + 1) - csr.begin(v) >= min_degree) word |= uint64_t{1} << bit;
+        for (int64_t w64 = 0; w64 < words; ++w64) {
+          uint64_t word = 0;
+          for (int bit = 0; bit < 64; ++bit) {
+            const int64_t v = w64 * 64 + bit;
+            if (v < n && csr.begin(v + 1) - csr.begin(v) >= min_degree) word |= uint64_t{1} << bit;
+          }
+          bits[static_cast<size_t>(w64)] = word;
         }
-        bits[static_cast<size_t>(w64)] = word;
-      }
-      if (!graph_on_device) {
-        PARTS_HIP(hipMalloc(&hot_bits_dev, bits.size() * 8), "hipMalloc hot bitmap");
         PARTS_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
-        hot.bits = hot_bits_dev;
       }
+      hot.bits = hot_bits_dev;
     }
     hot.mode = mode;
   }
