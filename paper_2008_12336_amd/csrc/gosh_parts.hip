@@ -396,7 +396,13 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   std::vector<hipEvent_t> slot_ready(P, nullptr), slot_used(P, nullptr), pool_ready(S, nullptr),
       pool_used(S, nullptr), staging_done(NS, nullptr);
   hipEvent_t arrived = nullptr;  // device-sampled path: the parts of the current visit are in
-  std::vector<hipEvent_t> k_begin, k_end;
+  // Kernel timing: a ring of event pairs, read when a pair is used again and at the end.
+  // The host is normally a few visits ahead of the kernels, so that read does not wait;
+  // when nothing else paces it (every part resident, graph on the device) the ring does,
+  // at kTimers visits.
+  constexpr int kTimers = 64;
+  std::vector<hipEvent_t> k_begin(kTimers, nullptr), k_end(kTimers, nullptr);
+  std::vector<char> k_pending(kTimers, 0);
   std::vector<int32_t> slot_part(P, -1);
 
   // ---- sampler thread state -------------------------------------------------------------
@@ -439,8 +445,10 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     PARTS_HIP(hipEventCreateWithFlags(&staging_done[s], hipEventDisableTiming), "hipEventCreate");
   }
   PARTS_HIP(hipEventCreateWithFlags(&arrived, hipEventDisableTiming), "hipEventCreate");
-  k_begin.assign(static_cast<size_t>(visits), nullptr);
-  k_end.assign(static_cast<size_t>(visits), nullptr);
+  for (int t = 0; t < kTimers; ++t) {
+    PARTS_HIP(hipEventCreate(&k_begin[t]), "hipEventCreate");
+    PARTS_HIP(hipEventCreate(&k_end[t]), "hipEventCreate");
+  }
 
   // ---- hot rows: degree rule evaluated once, where the graph lives -----------------------
   if (!seq) {
@@ -693,13 +701,20 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
         args.k_neg = k_neg;
         args.samples = samples;
         args.lr = gosh_lr(lr0, rot, rotations);
-        PARTS_HIP(hipEventCreate(&k_begin[vi]), "hipEventCreate");
-        PARTS_HIP(hipEventCreate(&k_end[vi]), "hipEventCreate");
-        PARTS_HIP(hipEventRecord(k_begin[vi], compute), "hipEventRecord");
+        const int timer = static_cast<int>(vi % kTimers);
+        if (k_pending[timer]) {
+          float ms = 0.f;
+          PARTS_HIP(hipEventSynchronize(k_end[timer]), "hipEventSynchronize");
+          PARTS_HIP(hipEventElapsedTime(&ms, k_begin[timer], k_end[timer]), "hipEventElapsedTime");
+          st.kernel_ms += ms;
+          k_pending[timer] = 0;
+        }
+        PARTS_HIP(hipEventRecord(k_begin[timer], compute), "hipEventRecord");
         gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, gosh::tuning().row_policy == 0,
                                             gosh::tuning().max_waves, compute);
         if ((rc = gosh::check_launch("sgd_kernel (pair)"))) break;
-        PARTS_HIP(hipEventRecord(k_end[vi], compute), "hipEventRecord");
+        PARTS_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
+        k_pending[timer] = 1;
         st.updates += w.count() * samples;
       }
       PARTS_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
@@ -745,10 +760,9 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
       PARTS_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
       PARTS_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
       PARTS_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
-      for (int64_t vi = 0; vi < visits; ++vi) {
+      for (int t = 0; t < kTimers; ++t) {
         float ms = 0.f;
-        if (k_begin[vi] && k_end[vi] && hipEventElapsedTime(&ms, k_begin[vi], k_end[vi]) == hipSuccess)
-          st.kernel_ms += ms;
+        if (k_pending[t] && hipEventElapsedTime(&ms, k_begin[t], k_end[t]) == hipSuccess) st.kernel_ms += ms;
       }
     }
   }
