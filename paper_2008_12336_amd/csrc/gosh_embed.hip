@@ -128,16 +128,16 @@ int embed_impl(const gosh_hierarchy *h, const Plan &pl, int64_t epochs, double p
                       "level 0 needs %zu bytes on the device, budget is %llu: use gosh_embed_host",
                       level_bytes(G[0], d), (unsigned long long)pl.budget);
 
-  hipEvent_t ev0, ev1;
-  GOSH_HIP(hipEventCreate(&ev0), "hipEventCreate");
-  GOSH_HIP(hipEventCreate(&ev1), "hipEventCreate");
-  struct EventGuard {
-    hipEvent_t a, b;
-    ~EventGuard() {
-      (void)hipEventDestroy(a);
-      (void)hipEventDestroy(b);
+  struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    ~EventPair() {
+      if (a) (void)hipEventDestroy(a);
+      if (b) (void)hipEventDestroy(b);
     }
-  } guard{ev0, ev1};
+  } timer;
+  GOSH_HIP(hipEventCreate(&timer.a), "hipEventCreate");
+  GOSH_HIP(hipEventCreate(&timer.b), "hipEventCreate");
+  const hipEvent_t ev0 = timer.a, ev1 = timer.b;
 
   // The matrix of the current level lives either on the device (cur_dev) or on the host
   // (cur_host); the buffers own it unless it is the caller's output array.

@@ -235,6 +235,516 @@ int check_parts_args(const gosh_csr *g, const float *M, int32_t d, int32_t k_neg
 
 constexpr int32_t kMaxParts = 4096;
 
+#define ROT_HIP(call, what)                                                                         \
+  do {                                                                                              \
+    hipError_t e_ = (call);                                                                         \
+    if (e_ != hipSuccess) return gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_));      \
+  } while (0)
+
+// What a call of gosh_train_parts is asked to do, after planning.
+struct RotationPlan {
+  const gosh_csr *g;  // host or device arrays
+  float *M_host;
+  int32_t d, k_neg, B;
+  float lr0;
+  uint64_t seed;
+  uint32_t level, flags;
+  int32_t K, P, S;
+  int64_t rotations;
+};
+
+// One call of gosh_train_parts: owns the device slots and pools, the three streams, the
+// events that order them and the sampler thread; the destructor waits for everything that
+// is queued, stops the thread and frees it all, on every path.
+class Rotation {
+ public:
+  explicit Rotation(const RotationPlan &plan)
+      : pl(plan), L{plan.g->n, plan.K, (plan.g->n + plan.K - 1) / plan.K}, P(plan.P), S(plan.S), NS(plan.S + 1),
+        per_round(plan.k_neg + 1), samples(plan.B * (plan.k_neg + 1)),
+        seq((plan.flags & GOSH_FLAG_SEQUENTIAL) != 0), key0(static_cast<uint32_t>(plan.seed)),
+        key1(static_cast<uint32_t>(plan.seed >> 32)), host_threads(std::max(1, omp_get_max_threads())),
+        graph_on_device(gosh::is_device_pointer(plan.g->xadj)),
+        pool_ints(static_cast<size_t>(2) * L.part_rows * plan.B) {
+    // the blocked order keeps all slots but two for a block; the two take turns receiving
+    // the streamed parts
+    if (pl.flags & GOSH_FLAG_BLOCKED_ORDER) pair_order_blocked(pl.K, std::max(1, P - 2), pa, pb);
+    else pair_order(pl.K, pa, pb);
+    npairs = static_cast<int64_t>(pa.size());
+    visits = pl.rotations * npairs;
+    st.K = pl.K;
+    st.rotations = pl.rotations;
+    st.pair_visits = visits;
+  }
+  Rotation(const Rotation &) = delete;
+  Rotation &operator=(const Rotation &) = delete;
+
+  // Stops the sampler thread and waits for everything that is queued; the statistics are
+  // complete after this.
+  void finish() {
+    {
+      std::lock_guard<std::mutex> lock(mu);
+      stop = true;
+    }
+    cv.notify_all();
+    if (sampler.joinable()) sampler.join();
+    st.sampler_ms = sampler_busy_ms;
+    for (hipStream_t s : {compute, copy, copy_out})
+      if (s) (void)hipStreamSynchronize(s);
+  }
+
+  ~Rotation() {
+    finish();
+    for (auto *events : {&chunk_flushed, &k_begin, &k_end, &slot_ready, &slot_used, &pool_ready, &pool_used,
+                         &staging_done})
+      for (hipEvent_t e : *events)
+        if (e) (void)hipEventDestroy(e);
+    if (arrived) (void)hipEventDestroy(arrived);
+    for (auto p : slot) if (p) (void)hipFree(p);
+    for (auto p : dpool) if (p) (void)hipFree(p);
+    for (auto p : staging) if (p) (void)hipHostFree(p);
+    if (hot_bits_dev) (void)hipFree(hot_bits_dev);
+    for (hipStream_t s : {compute, copy, copy_out})
+      if (s) (void)hipStreamDestroy(s);
+  }
+
+  // Streams, slots, pools, events, the hot-row set, the sampler thread.
+  int prepare() {
+    if (graph_on_device)
+      if (int rc = gosh::check_device_csr(pl.g)) return rc;
+    slot.assign(P, nullptr);
+    dpool.assign(S, nullptr);
+    staging.assign(NS, nullptr);
+    slot_part.assign(P, -1);
+    chunk_flushed.assign(static_cast<size_t>(P) * kSwapChunks, nullptr);
+    slot_ready.assign(P, nullptr);
+    slot_used.assign(P, nullptr);
+    pool_ready.assign(S, nullptr);
+    pool_used.assign(S, nullptr);
+    staging_done.assign(NS, nullptr);
+    k_begin.assign(kTimers, nullptr);
+    k_end.assign(kTimers, nullptr);
+    k_pending.assign(kTimers, 0);
+    ROT_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
+    ROT_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
+    ROT_HIP(hipStreamCreateWithFlags(&copy_out, hipStreamNonBlocking), "hipStreamCreate");
+    for (int s = 0; s < P; ++s)
+      ROT_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * pl.d * 4), "hipMalloc part slot");
+    for (int s = 0; s < S; ++s) ROT_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
+    for (int s = 0; s < NS && !graph_on_device; ++s)
+      ROT_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
+              "hipHostMalloc staging");
+    for (auto *events : {&chunk_flushed, &slot_ready, &slot_used, &pool_ready, &pool_used, &staging_done})
+      for (hipEvent_t &e : *events) ROT_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+    ROT_HIP(hipEventCreateWithFlags(&arrived, hipEventDisableTiming), "hipEventCreate");
+    for (int t = 0; t < kTimers; ++t) {
+      ROT_HIP(hipEventCreate(&k_begin[t]), "hipEventCreate");
+      ROT_HIP(hipEventCreate(&k_end[t]), "hipEventCreate");
+    }
+    if (int rc = build_hot_set()) return rc;
+    if (!graph_on_device) sampler = std::thread([this] { sampler_loop(); });
+    return GOSH_OK;
+  }
+
+  // Every visit of every rotation, then the write-back of what is still resident.
+  int run() {
+    std::vector<int32_t> keep;
+    const int64_t max_ahead = (pl.flags & GOSH_FLAG_BLOCKED_ORDER) ? P : 1;
+    for (int64_t vi = 0; vi < visits; ++vi) {
+      const Visit v = visit(vi);
+      // 1. the two parts of this visit (nothing is running that they could disturb: the
+      //    copy stream waits for the last kernel of any slot it overwrites)
+      keep.clear();
+      if (ensure_parts(vi, keep) == kError) return GOSH_EHIP;
+      const int sa = slot_of(v.a), sb = slot_of(v.b);
+      if (sa < 0 || sb < 0) return gosh::fail(GOSH_EHIP, "internal: part not resident");
+      // 2. the pool of this visit
+      if (int rc = graph_on_device ? pool_from_device(vi, v) : pool_from_sampler(vi, v)) return rc;
+      // 3. the pair kernel
+      if (int rc = launch_pair(vi, v, sa, sb)) return rc;
+      // 4. while that kernel runs: bring in what the next visit needs.  In the blocked order
+      //    the part after the one being streamed is known to be worth its slot, so there
+      //    the fetch runs as far ahead as slots that none of the visits in between uses can
+      //    be found; in the paper's order fetching further ahead evicts parts the next row
+      //    would have reused (measured: 376 GB instead of 309 GB per rotation at 5 slots).
+      keep.assign({v.a, v.b});
+      int got = kPlaced;
+      for (int64_t ahead = 1; ahead <= max_ahead && got == kPlaced; ++ahead) got = ensure_parts(vi + ahead, keep);
+      if (got == kError) return GOSH_EHIP;
+      // 5. keep the host from running ahead
+      if (graph_on_device) {
+        // it continues once the parts of this visit have arrived, as it does with a host
+        // sampler (with several swaps queued at once the copies of a swap took four times
+        // as long)
+        ROT_HIP(hipEventSynchronize(arrived), "hipEventSynchronize");
+      } else {
+        // hand the staging buffer back to the sampler once its upload is done
+        ROT_HIP(hipEventSynchronize(staging_done[vi % NS]), "hipEventSynchronize");
+        {
+          std::lock_guard<std::mutex> lock(mu);
+          released = vi + 1;
+        }
+        cv.notify_all();
+      }
+    }
+    return write_back_all();
+  }
+
+  gosh_parts_stats st{};
+
+ private:
+  struct Visit {
+    int32_t a, b;      // the two parts
+    uint32_t rot, q;   // rotation, index of the pair inside the rotation
+  };
+  enum { kPlaced = 0, kNoSlot = 1, kError = -2 };
+  // A part swap runs in kSwapChunks pieces: piece c of the new part goes up as soon as piece
+  // c of the old one is down, so both directions of the host link are busy at once.
+  static constexpr int kSwapChunks = 8;
+  // Kernel timing: a ring of event pairs, read when a pair is used again and at the end.
+  // The host is normally a few visits ahead of the kernels, so that read does not wait;
+  // when nothing else paces it (every part resident, graph on the device) the ring does,
+  // at kTimers visits.
+  static constexpr int kTimers = 64;
+
+  const RotationPlan pl;
+  const Layout L;
+  const int32_t P, S, NS;  // slots, device pools, host staging buffers for pools
+  const int32_t per_round, samples;
+  const bool seq;
+  const uint32_t key0, key1;
+  const int host_threads;
+  const bool graph_on_device;  // then it is sampled there: no sampler thread, no pool uploads
+  const size_t pool_ints;      // side 0 then side 1
+  std::vector<int32_t> pa, pb;
+  int64_t npairs = 0, visits = 0;
+
+  std::vector<float *> slot;
+  std::vector<int32_t *> dpool, staging;
+  std::vector<int32_t> slot_part;
+  uint32_t *hot_bits_dev = nullptr;
+  gosh::HotSet hot{nullptr, gosh::kHotNone};
+  hipStream_t compute = nullptr, copy = nullptr, copy_out = nullptr;
+  std::vector<hipEvent_t> chunk_flushed, slot_ready, slot_used, pool_ready, pool_used, staging_done, k_begin, k_end;
+  std::vector<char> k_pending;
+  hipEvent_t arrived = nullptr;  // device-sampled path: the parts of the current visit are in
+
+  // sampler thread state
+  std::mutex mu;
+  std::condition_variable cv;
+  int64_t filled = 0;    // pools produced so far (visit indices [0, filled))
+  int64_t released = 0;  // staging buffers given back (visit indices [0, released))
+  bool stop = false;
+  double sampler_busy_ms = 0;  // written by the sampler thread only, read after it has joined
+  std::thread sampler;
+
+  Visit visit(int64_t vi) const {
+    const uint32_t q = static_cast<uint32_t>(vi % npairs);
+    return Visit{pa[q], pb[q], static_cast<uint32_t>(vi / npairs), q};
+  }
+
+  // Hot rows: the degree rule evaluated once, where the graph lives.
+  int build_hot_set() {
+    const int64_t n = pl.g->n;
+    if (!seq) {
+      const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(pl.d);
+      const int64_t pair_sources = 2 * L.part_rows;
+      const int64_t waves = std::min<int64_t>((pair_sources + gpw - 1) / gpw, gosh::tuning().max_waves);
+      const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;
+      // per visit a row takes about B*k_neg uniform hits plus its own turn
+      int mode = ((static_cast<int64_t>(pl.B) * pl.k_neg + 1) * in_flight * gosh::tuning().hot_all_inv_eps >
+                  pair_sources)
+                     ? gosh::kHotAll
+                     : gosh::kHotBitmap;
+      if (pl.flags & GOSH_FLAG_PLAIN_STORES) mode = gosh::kHotNone;
+      if (pl.flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
+      if (mode == gosh::kHotBitmap) {
+        const int64_t min_degree = pl.g->nnz / (gosh::tuning().hot_inv_eps * in_flight * pl.B) + 1;
+        const int64_t words = (n + 63) / 64;
+        ROT_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
+        if (graph_on_device) {
+          const int blocks = static_cast<int>(std::min<int64_t>((words + 255) / 256, 65536));
+          if (pl.g->xadj_is64)
+            hipLaunchKernelGGL(degree_bitmap_kernel<int64_t>, dim3(blocks), dim3(256), 0, nullptr,
+                               static_cast<const int64_t *>(pl.g->xadj), n, min_degree,
+                               reinterpret_cast<uint64_t *>(hot_bits_dev));
+          else
+            hipLaunchKernelGGL(degree_bitmap_kernel<int32_t>, dim3(blocks), dim3(256), 0, nullptr,
+                               static_cast<const int32_t *>(pl.g->xadj), n, min_degree,
+                               reinterpret_cast<uint64_t *>(hot_bits_dev));
+          if (int rc = gosh::check_launch("degree_bitmap_kernel")) return rc;
+          ROT_HIP(hipDeviceSynchronize(), "hot bitmap");
+        } else {
+          const HostCsr csr{pl.g};
+          std::vector<uint64_t> bits(static_cast<size_t>(words), 0);
+#pragma omp parallel for num_threads(host_threads) schedule(static)
+          for (int64_t w64 = 0; w64 < words; ++w64) {
+            uint64_t word = 0;
+            for (int bit = 0; bit < 64; ++bit) {
+              const int64_t v = w64 * 64 + bit;
+              if (v < n && csr.begin(v + 1) - csr.begin(v) >= min_degree) word |= uint64_t{1} << bit;
+            }
+            bits[static_cast<size_t>(w64)] = word;
+          }
+          ROT_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
+        }
+        hot.bits = hot_bits_dev;
+      }
+      hot.mode = mode;
+    }
+    if (hot.bits == nullptr) {
+      // the kernel reads word 0 of the bitmap unconditionally
+      ROT_HIP(hipMalloc(&hot_bits_dev, 64), "hipMalloc hot bitmap");
+      ROT_HIP(hipMemset(hot_bits_dev, 0, 64), "hipMemset hot bitmap");
+      hot.bits = hot_bits_dev;
+    }
+    return GOSH_OK;
+  }
+
+  // Sampler thread (host graph only): pools of positives, at most NS visits ahead of their
+  // release.
+  void sampler_loop() {
+    for (int64_t vi = 0; vi < visits; ++vi) {
+      {
+        std::unique_lock<std::mutex> lock(mu);
+        cv.wait(lock, [&] { return stop || vi - released < NS; });
+        if (stop) return;
+      }
+      const Visit v = visit(vi);
+      int32_t *buf = staging[vi % NS];
+      const uint32_t w3 = level_word(pl.level, v.q);
+      const auto t_fill = std::chrono::steady_clock::now();
+      gosh::fill_pool(*pl.g, L.lo(v.a), L.size(v.a), L.lo(v.b), L.lo(v.b) + L.size(v.b), 0, pl.B, per_round, key0,
+                      key1, v.rot, w3, host_threads, buf);
+      if (v.a != v.b)
+        gosh::fill_pool(*pl.g, L.lo(v.b), L.size(v.b), L.lo(v.a), L.lo(v.a) + L.size(v.a), 1, pl.B, per_round, key0,
+                        key1, v.rot, w3, host_threads, buf + static_cast<size_t>(L.part_rows) * pl.B);
+      const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_fill).count();
+      sampler_busy_ms += ms;
+      {
+        std::lock_guard<std::mutex> lock(mu);
+        filled = vi + 1;
+      }
+      cv.notify_all();
+    }
+  }
+
+  // Next visit (>= from) that uses part p, or a large number.
+  int64_t next_use(int32_t p, int64_t from) const {
+    for (int64_t vi = from; vi < std::min(visits, from + 4 * npairs + 4); ++vi) {
+      const int64_t q = vi % npairs;
+      if (pa[q] == p || pb[q] == p) return vi;
+    }
+    return visits + npairs;
+  }
+  int slot_of(int32_t p) const {
+    for (int s = 0; s < P; ++s)
+      if (slot_part[s] == p) return s;
+    return -1;
+  }
+
+  // Brings part p into a slot whose part is not in `keep` (SwitchSubMatrices): among the
+  // other slots an empty one is taken, else the part whose next use is farthest is
+  // written back and replaced.  Everything is queued on the copy streams behind the last
+  // kernel that used the slot.  kNoSlot if every slot is kept, kError after a failed call.
+  int load_part(int32_t p, const std::vector<int32_t> &keep, int64_t now) {
+    int victim = -1;
+    int64_t farthest = -1;
+    for (int s = 0; s < P; ++s) {
+      const int32_t sp = slot_part[s];
+      if (sp == -1) { victim = s; break; }
+      if (std::find(keep.begin(), keep.end(), sp) != keep.end()) continue;
+      const int64_t nu = next_use(sp, now);
+      if (nu > farthest) { farthest = nu; victim = s; }
+    }
+    if (victim < 0) return kNoSlot;
+    if (swap_in(p, victim) != GOSH_OK) return kError;
+    slot_part[victim] = p;
+    return kPlaced;
+  }
+
+  int swap_in(int32_t p, int victim) {
+    const int32_t d = pl.d;
+    const size_t new_bytes = static_cast<size_t>(L.size(p)) * d * 4;
+    float *new_host = pl.M_host + static_cast<int64_t>(L.lo(p)) * d;
+    if (slot_part[victim] >= 0) {
+      // Write the old part back on the outbound stream and bring the new one in on the
+      // inbound stream, piece by piece: the upload of a piece waits only for the
+      // write-back of the same bytes of the slot.  A later upload of the old part must
+      // see its host bytes; it is queued on the inbound stream after these waits, the
+      // last of which covers the whole write-back.
+      const int32_t old = slot_part[victim];
+      const size_t old_bytes = static_cast<size_t>(L.size(old)) * d * 4;
+      float *old_host = pl.M_host + static_cast<int64_t>(L.lo(old)) * d;
+      const size_t longest = std::max(old_bytes, new_bytes);
+      size_t piece = (longest + kSwapChunks - 1) / kSwapChunks;
+      piece = std::max<size_t>((piece + 255) / 256 * 256, size_t(8) << 20);
+      // after the last kernel that used the slot, and after the upload that filled it (a
+      // part brought in ahead of time may leave again before any kernel has used it)
+      ROT_HIP(hipStreamWaitEvent(copy_out, slot_used[victim], 0), "hipStreamWaitEvent");
+      ROT_HIP(hipStreamWaitEvent(copy_out, slot_ready[victim], 0), "hipStreamWaitEvent");
+      char *slot_bytes = reinterpret_cast<char *>(slot[victim]);
+      int c = 0;
+      for (size_t off = 0; off < longest; off += piece, ++c) {
+        hipEvent_t flushed = chunk_flushed[static_cast<size_t>(victim) * kSwapChunks + c];
+        if (off < old_bytes) {
+          ROT_HIP(hipMemcpyAsync(reinterpret_cast<char *>(old_host) + off, slot_bytes + off,
+                                 std::min(piece, old_bytes - off), hipMemcpyDeviceToHost, copy_out),
+                  "part write-back");
+          ROT_HIP(hipEventRecord(flushed, copy_out), "hipEventRecord");
+          ROT_HIP(hipStreamWaitEvent(copy, flushed, 0), "hipStreamWaitEvent");
+        }
+        if (off < new_bytes)
+          ROT_HIP(hipMemcpyAsync(slot_bytes + off, reinterpret_cast<const char *>(new_host) + off,
+                                 std::min(piece, new_bytes - off), hipMemcpyHostToDevice, copy),
+                  "part upload");
+      }
+      st.bytes_d2h += old_bytes;
+    } else {
+      ROT_HIP(hipStreamWaitEvent(copy, slot_used[victim], 0), "hipStreamWaitEvent");
+      ROT_HIP(hipMemcpyAsync(slot[victim], new_host, new_bytes, hipMemcpyHostToDevice, copy), "part upload");
+    }
+    st.bytes_h2d += new_bytes;
+    ROT_HIP(hipEventRecord(slot_ready[victim], copy), "hipEventRecord");
+    return GOSH_OK;
+  }
+
+  // Makes the parts of visit vi resident as far as slots allow, never evicting a part in
+  // `keep` (the parts of the running visit and of the visits before vi).  kNoSlot if a
+  // needed part could not be placed (or vi is past the end), kError after a failed call,
+  // else kPlaced; the parts of vi join `keep`.
+  int ensure_parts(int64_t vi, std::vector<int32_t> &keep) {
+    if (vi >= visits) return kNoSlot;
+    const Visit v = visit(vi);
+    keep.push_back(v.a);
+    keep.push_back(v.b);
+    const int32_t need[2] = {v.a, v.b};
+    for (int t = 0; t < 2; ++t) {
+      if (t == 1 && need[1] == need[0]) break;
+      if (slot_of(need[t]) >= 0) continue;
+      const int got = load_part(need[t], keep, vi);
+      if (got != kPlaced) return got;
+    }
+    return kPlaced;
+  }
+
+  // The pool of a visit drawn on the device right before the kernel that reads it (same
+  // stream: the pool's previous reader is done, its next reader waits).
+  int pool_from_device(int64_t vi, const Visit &v) {
+    const int ps = static_cast<int>(vi % S);
+    const uint32_t w3 = level_word(pl.level, v.q);
+    auto fill = [&](int32_t lo, int32_t cnt, int32_t olo, int32_t ohi, int32_t side, int32_t *pool) {
+      if (cnt <= 0) return;
+      const int blocks = static_cast<int>(std::min<int64_t>((static_cast<int64_t>(cnt) + 255) / 256, 65536));
+      if (pl.g->xadj_is64)
+        hipLaunchKernelGGL(fill_pool_kernel<int64_t>, dim3(blocks), dim3(256), 0, compute,
+                           static_cast<const int64_t *>(pl.g->xadj), pl.g->adj, pl.g->nnz, lo, cnt, olo, ohi, side,
+                           pl.B, per_round, key0, key1, v.rot, w3, pool);
+      else
+        hipLaunchKernelGGL(fill_pool_kernel<int32_t>, dim3(blocks), dim3(256), 0, compute,
+                           static_cast<const int32_t *>(pl.g->xadj), pl.g->adj, pl.g->nnz, lo, cnt, olo, ohi, side,
+                           pl.B, per_round, key0, key1, v.rot, w3, pool);
+    };
+    fill(L.lo(v.a), L.size(v.a), L.lo(v.b), L.lo(v.b) + L.size(v.b), 0, dpool[ps]);
+    if (v.a != v.b)
+      fill(L.lo(v.b), L.size(v.b), L.lo(v.a), L.lo(v.a) + L.size(v.a), 1,
+           dpool[ps] + static_cast<size_t>(L.part_rows) * pl.B);
+    if (int rc = gosh::check_launch("fill_pool_kernel")) return rc;
+    ROT_HIP(hipEventRecord(pool_ready[ps], compute), "hipEventRecord");
+    // marks, on the inbound stream, the point up to which this visit's parts are in
+    ROT_HIP(hipEventRecord(arrived, copy), "hipEventRecord");
+    return GOSH_OK;
+  }
+
+  // The pool of a visit from the sampler thread: wait for it, upload on the copy stream.
+  int pool_from_sampler(int64_t vi, const Visit &v) {
+    const int ps = static_cast<int>(vi % S), hs = static_cast<int>(vi % NS);
+    {
+      const auto t_wait = std::chrono::steady_clock::now();
+      std::unique_lock<std::mutex> lock(mu);
+      cv.wait(lock, [&] { return filled > vi; });
+      st.sampler_wait_ms +=
+          std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_wait).count();
+    }
+    ROT_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
+    const size_t side0 = static_cast<size_t>(L.size(v.a)) * pl.B * 4;
+    ROT_HIP(hipMemcpyAsync(dpool[ps], staging[hs], side0, hipMemcpyHostToDevice, copy), "pool upload");
+    st.bytes_h2d += side0;
+    if (v.a != v.b) {
+      const size_t side1 = static_cast<size_t>(L.size(v.b)) * pl.B * 4;
+      ROT_HIP(hipMemcpyAsync(dpool[ps] + static_cast<size_t>(L.part_rows) * pl.B,
+                             staging[hs] + static_cast<size_t>(L.part_rows) * pl.B, side1, hipMemcpyHostToDevice,
+                             copy),
+              "pool upload");
+      st.bytes_h2d += side1;
+    }
+    ROT_HIP(hipEventRecord(pool_ready[ps], copy), "hipEventRecord");
+    ROT_HIP(hipEventRecord(staging_done[hs], copy), "hipEventRecord");
+    return GOSH_OK;
+  }
+
+  int launch_pair(int64_t vi, const Visit &v, int sa, int sb) {
+    const int ps = static_cast<int>(vi % S);
+    ROT_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
+    ROT_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
+    ROT_HIP(hipStreamWaitEvent(compute, pool_ready[ps], 0), "hipStreamWaitEvent");
+    PairWork w{};
+    w.a_lo = L.lo(v.a); w.a_n = L.size(v.a); w.b_lo = L.lo(v.b); w.b_n = L.size(v.b);
+    w.a_rows = slot[sa]; w.b_rows = slot[sb];
+    w.pool_a = dpool[ps];
+    w.pool_b = dpool[ps] + static_cast<size_t>(L.part_rows) * pl.B;
+    w.B = pl.B; w.per_round = per_round; w.d = pl.d; w.diagonal = v.a == v.b;
+    w.key0 = key0; w.key1 = key1; w.rotation = v.rot; w.word3 = level_word(pl.level, v.q);
+    gosh::SgdArgs args{};
+    args.hot = hot;
+    args.d = pl.d;
+    args.k_neg = pl.k_neg;
+    args.samples = samples;
+    args.lr = gosh_lr(pl.lr0, v.rot, pl.rotations);
+    const int timer = static_cast<int>(vi % kTimers);
+    if (k_pending[timer]) {
+      float ms = 0.f;
+      ROT_HIP(hipEventSynchronize(k_end[timer]), "hipEventSynchronize");
+      ROT_HIP(hipEventElapsedTime(&ms, k_begin[timer], k_end[timer]), "hipEventElapsedTime");
+      st.kernel_ms += ms;
+      k_pending[timer] = 0;
+    }
+    ROT_HIP(hipEventRecord(k_begin[timer], compute), "hipEventRecord");
+    gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, gosh::tuning().row_policy == 0,
+                                        gosh::tuning().max_waves, compute);
+    if (int rc = gosh::check_launch("sgd_kernel (pair)")) return rc;
+    ROT_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
+    k_pending[timer] = 1;
+    st.updates += w.count() * samples;
+    ROT_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
+    ROT_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
+    ROT_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
+    return GOSH_OK;
+  }
+
+  // Writes every resident part back and waits for all three streams.
+  int write_back_all() {
+    for (int s = 0; s < P; ++s) {
+      if (slot_part[s] < 0) continue;
+      const int32_t old = slot_part[s];
+      const size_t bytes = static_cast<size_t>(L.size(old)) * pl.d * 4;
+      ROT_HIP(hipStreamWaitEvent(copy_out, slot_used[s], 0), "hipStreamWaitEvent");
+      ROT_HIP(hipMemcpyAsync(pl.M_host + static_cast<int64_t>(L.lo(old)) * pl.d, slot[s], bytes,
+                             hipMemcpyDeviceToHost, copy_out),
+              "part write-back");
+      st.bytes_d2h += bytes;
+    }
+    ROT_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
+    ROT_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
+    ROT_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
+    for (int t = 0; t < kTimers; ++t) {
+      float ms = 0.f;
+      if (k_pending[t] && hipEventElapsedTime(&ms, k_begin[t], k_end[t]) == hipSuccess) st.kernel_ms += ms;
+      k_pending[t] = 0;
+    }
+    return GOSH_OK;
+  }
+};
+
 }  // namespace
 
 extern "C" {
@@ -336,7 +846,7 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
                      float lr0, uint64_t seed, uint32_t level, uint64_t device_budget_bytes,
                      int32_t P_gpu, int32_t S_gpu, int32_t B, int32_t force_K, uint32_t flags,
                      gosh_parts_stats *stats_out) {
-  if (int rc0 = check_parts_args(g_host, M_host, d, k_neg, P_gpu, S_gpu, B, flags)) return rc0;
+  if (int rc = check_parts_args(g_host, M_host, d, k_neg, P_gpu, S_gpu, B, flags)) return rc;
   if (epochs < 1) return gosh::fail(GOSH_EINVAL, "epochs = %lld: must be >= 1", (long long)epochs);
   const int64_t n = g_host->n;
   int32_t K = 0;
@@ -350,451 +860,23 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
     if (device_budget_bytes != 0 && planned_bytes > device_budget_bytes)
       return gosh::fail(GOSH_EBUDGET, "K = %d needs %llu device bytes, budget is %llu", K,
                         (unsigned long long)planned_bytes, (unsigned long long)device_budget_bytes);
-  } else if (int rc0 = gosh_parts_plan(n, d, epochs, device_budget_bytes, P_gpu, S_gpu, B, &K,
-                                       &rotations, &planned_bytes)) {
-    return rc0;
+  } else if (int rc = gosh_parts_plan(n, d, epochs, device_budget_bytes, P_gpu, S_gpu, B, &K, &rotations,
+                                      &planned_bytes)) {
+    return rc;
   }
-  const Layout L{n, K, (n + K - 1) / K};
-  const int32_t P = std::min(P_gpu, K), S = S_gpu;
-  const int32_t per_round = k_neg + 1, samples = B * per_round;
-  const bool seq = (flags & GOSH_FLAG_SEQUENTIAL) != 0;
-  const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
-  std::vector<int32_t> pa, pb;
-  // the blocked order keeps all slots but two for a block; the two take turns receiving
-  // the streamed parts
-  if (flags & GOSH_FLAG_BLOCKED_ORDER) pair_order_blocked(K, std::max(1, P - 2), pa, pb);
-  else pair_order(K, pa, pb);
-  const int64_t npairs = static_cast<int64_t>(pa.size());
-  const int64_t visits = rotations * npairs;
-  const int host_threads = std::max(1, omp_get_max_threads());
-  // A graph in device memory is sampled there (no sampler thread, no pool uploads).
-  const bool graph_on_device = gosh::is_device_pointer(g_host->xadj);
-  if (graph_on_device)
-    if (int rc0 = gosh::check_device_csr(g_host)) return rc0;
-  const HostCsr csr{g_host};
-  const size_t pool_ints = static_cast<size_t>(2) * L.part_rows * B;  // side 0 then side 1
-
-  int rc = GOSH_OK;
-  auto wall0 = std::chrono::steady_clock::now();
+  const auto wall0 = std::chrono::steady_clock::now();
+  const RotationPlan plan{g_host, M_host, d, k_neg, B, lr0, seed, level, flags, K, std::min(P_gpu, K), S_gpu,
+                          rotations};
   gosh_parts_stats st{};
-  st.K = K;
-  st.rotations = rotations;
-  st.pair_visits = visits;
+  int rc = GOSH_OK;
+  {
+    Rotation rotation(plan);
+    rc = rotation.prepare();
+    if (rc == GOSH_OK) rc = rotation.run();
+    rotation.finish();
+    st = rotation.st;
+  }
   st.device_bytes = planned_bytes;
-
-  // ---- device and pinned-host resources ------------------------------------------------
-  std::vector<float *> slot(P, nullptr);
-  std::vector<int32_t *> dpool(S, nullptr);
-  const int NS = S + 1;  // host staging buffers for pools
-  std::vector<int32_t *> staging(NS, nullptr);
-  uint32_t *hot_bits_dev = nullptr;
-  hipStream_t compute = nullptr, copy = nullptr, copy_out = nullptr;
-  // A part swap runs in kSwapChunks pieces: piece c of the new part goes up as soon as piece
-  // c of the old one is down, so both directions of the host link are busy at once.
-  constexpr int kSwapChunks = 8;
-  std::vector<hipEvent_t> chunk_flushed(static_cast<size_t>(P) * kSwapChunks, nullptr);
-  std::vector<hipEvent_t> slot_ready(P, nullptr), slot_used(P, nullptr), pool_ready(S, nullptr),
-      pool_used(S, nullptr), staging_done(NS, nullptr);
-  hipEvent_t arrived = nullptr;  // device-sampled path: the parts of the current visit are in
-  // Kernel timing: a ring of event pairs, read when a pair is used again and at the end.
-  // The host is normally a few visits ahead of the kernels, so that read does not wait;
-  // when nothing else paces it (every part resident, graph on the device) the ring does,
-  // at kTimers visits.
-  constexpr int kTimers = 64;
-  std::vector<hipEvent_t> k_begin(kTimers, nullptr), k_end(kTimers, nullptr);
-  std::vector<char> k_pending(kTimers, 0);
-  std::vector<int32_t> slot_part(P, -1);
-
-  // ---- sampler thread state -------------------------------------------------------------
-  std::mutex mu;
-  std::condition_variable cv;
-  int64_t filled = 0;    // pools produced so far (visit indices [0, filled))
-  int64_t released = 0;  // staging buffers given back (visit indices [0, released))
-  bool stop = false;
-  double sampler_busy_ms = 0;  // written by the sampler thread only, read after it joined
-  std::thread sampler;
-
-  auto visit_pair = [&](int64_t vi, int32_t &a, int32_t &b, uint32_t &rot, uint32_t &q) {
-    rot = static_cast<uint32_t>(vi / npairs);
-    q = static_cast<uint32_t>(vi % npairs);
-    a = pa[q];
-    b = pb[q];
-  };
-
-  gosh::HotSet hot{nullptr, gosh::kHotNone};
-
-  PARTS_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
-  PARTS_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
-  PARTS_HIP(hipStreamCreateWithFlags(&copy_out, hipStreamNonBlocking), "hipStreamCreate");
-  for (int s = 0; s < P; ++s) {
-    PARTS_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * d * 4), "hipMalloc part slot");
-    PARTS_HIP(hipEventCreateWithFlags(&slot_ready[s], hipEventDisableTiming), "hipEventCreate");
-    PARTS_HIP(hipEventCreateWithFlags(&slot_used[s], hipEventDisableTiming), "hipEventCreate");
-    for (int c = 0; c < kSwapChunks; ++c)
-      PARTS_HIP(hipEventCreateWithFlags(&chunk_flushed[static_cast<size_t>(s) * kSwapChunks + c],
-                                        hipEventDisableTiming), "hipEventCreate");
-  }
-  for (int s = 0; s < S; ++s) {
-    PARTS_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
-    PARTS_HIP(hipEventCreateWithFlags(&pool_ready[s], hipEventDisableTiming), "hipEventCreate");
-    PARTS_HIP(hipEventCreateWithFlags(&pool_used[s], hipEventDisableTiming), "hipEventCreate");
-  }
-  for (int s = 0; s < NS && !graph_on_device; ++s) {
-    PARTS_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
-              "hipHostMalloc staging");
-    PARTS_HIP(hipEventCreateWithFlags(&staging_done[s], hipEventDisableTiming), "hipEventCreate");
-  }
-  PARTS_HIP(hipEventCreateWithFlags(&arrived, hipEventDisableTiming), "hipEventCreate");
-  for (int t = 0; t < kTimers; ++t) {
-    PARTS_HIP(hipEventCreate(&k_begin[t]), "hipEventCreate");
-    PARTS_HIP(hipEventCreate(&k_end[t]), "hipEventCreate");
-  }
-
-  // ---- hot rows: degree rule evaluated once, where the graph lives -----------------------
-  if (!seq) {
-    const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(d);
-    const int64_t pair_sources = 2 * L.part_rows;
-    const int64_t waves = std::min<int64_t>((pair_sources + gpw - 1) / gpw, gosh::tuning().max_waves);
-    const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;
-    // per visit a row takes about B*k_neg uniform hits plus its own turn
-    int mode = ((static_cast<int64_t>(B) * k_neg + 1) * in_flight * gosh::tuning().hot_all_inv_eps > pair_sources)
-                   ? gosh::kHotAll
-                   : gosh::kHotBitmap;
-    if (flags & GOSH_FLAG_PLAIN_STORES) mode = gosh::kHotNone;
-    if (flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
-    if (mode == gosh::kHotBitmap) {
-      const int64_t min_degree = g_host->nnz / (gosh::tuning().hot_inv_eps * in_flight * B) + 1;
-      const int64_t words = (n + 63) / 64;
-      PARTS_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
-      if (graph_on_device) {
-        const int blocks = static_cast<int>(std::min<int64_t>((words + 255) / 256, 65536));
-        if (g_host->xadj_is64)
-          hipLaunchKernelGGL(degree_bitmap_kernel<int64_t>, dim3(blocks), dim3(256), 0, nullptr,
-                             static_cast<const int64_t *>(g_host->xadj), n, min_degree,
-                             reinterpret_cast<uint64_t *>(hot_bits_dev));
-        else
-          hipLaunchKernelGGL(degree_bitmap_kernel<int32_t>, dim3(blocks), dim3(256), 0, nullptr,
-                             static_cast<const int32_t *>(g_host->xadj), n, min_degree,
-                             reinterpret_cast<uint64_t *>(hot_bits_dev));
-        if ((rc = gosh::check_launch("degree_bitmap_kernel"))) goto done;
-        PARTS_HIP(hipDeviceSynchronize(), "hot bitmap");
-      } else {
-        std::vector<uint64_t> bits(static_cast<size_t>(words), 0);
-#pragma omp parallel for num_threads(host_threads) schedule(static)
-        for (int64_t w64 = 0; w64 < words; ++w64) {
-          uint64_t word = 0;
-          for (int bit = 0; bit < 64; ++bit) {
-            const int64_t v = w64 * 64 + bit;
-            if (v < n && csr.begin(v + 1) - csr.begin(v) >= min_degree) word |= uint64_t{1} << bit;
-          }
-          bits[static_cast<size_t>(w64)] = word;
-        }
-        PARTS_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
-      }
-      hot.bits = hot_bits_dev;
-    }
-    hot.mode = mode;
-  }
-  if (hot.bits == nullptr) {
-    // the kernel reads word 0 of the bitmap unconditionally
-    PARTS_HIP(hipMalloc(&hot_bits_dev, 64), "hipMalloc hot bitmap");
-    PARTS_HIP(hipMemset(hot_bits_dev, 0, 64), "hipMemset hot bitmap");
-    hot.bits = hot_bits_dev;
-  }
-
-  // ---- sampler thread: pools of positives, at most NS visits ahead of their release ------
-  // (only for a host graph; a device-resident graph is sampled by fill_pool_kernel)
-  if (!graph_on_device) sampler = std::thread([&] {
-    for (int64_t vi = 0; vi < visits; ++vi) {
-      {
-        std::unique_lock<std::mutex> lock(mu);
-        cv.wait(lock, [&] { return stop || vi - released < NS; });
-        if (stop) return;
-      }
-      int32_t a, b;
-      uint32_t rot, q;
-      visit_pair(vi, a, b, rot, q);
-      int32_t *buf = staging[vi % NS];
-      const uint32_t w3 = level_word(level, q);
-      const auto t_fill = std::chrono::steady_clock::now();
-      gosh::fill_pool(*g_host, L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, B, per_round, key0, key1,
-                rot, w3, host_threads, buf);
-      if (a != b)
-        gosh::fill_pool(*g_host, L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, B, per_round, key0, key1,
-                  rot, w3, host_threads, buf + static_cast<size_t>(L.part_rows) * B);
-      sampler_busy_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_fill).count();
-      {
-        std::lock_guard<std::mutex> lock(mu);
-        filled = vi + 1;
-      }
-      cv.notify_all();
-    }
-  });
-
-  {
-    // next visit (>= from) that uses part p, or a large number
-    auto next_use = [&](int32_t p, int64_t from) {
-      for (int64_t vi = from; vi < std::min(visits, from + 4 * npairs + 4); ++vi) {
-        const int64_t q = vi % npairs;
-        if (pa[q] == p || pb[q] == p) return vi;
-      }
-      return visits + npairs;
-    };
-    auto slot_of = [&](int32_t p) {
-      for (int s = 0; s < P; ++s)
-        if (slot_part[s] == p) return s;
-      return -1;
-    };
-    // Brings part p into a slot whose part is not in `keep` (SwitchSubMatrices): among the
-    // other slots an empty one is taken, else the part whose next use is farthest is
-    // written back and replaced.  Everything is queued on the copy stream behind the last
-    // kernel that used the slot.  Returns the slot, -1 if every slot is kept, -2 on error.
-    auto load_part = [&](int32_t p, const std::vector<int32_t> &keep, int64_t now) -> int {
-      int victim = -1;
-      int64_t farthest = -1;
-      for (int s = 0; s < P; ++s) {
-        const int32_t sp = slot_part[s];
-        if (sp == -1) { victim = s; break; }
-        if (std::find(keep.begin(), keep.end(), sp) != keep.end()) continue;
-        const int64_t nu = next_use(sp, now);
-        if (nu > farthest) { farthest = nu; victim = s; }
-      }
-      if (victim < 0) return -1;
-      const size_t new_bytes = static_cast<size_t>(L.size(p)) * d * 4;
-      float *new_host = M_host + static_cast<int64_t>(L.lo(p)) * d;
-      if (slot_part[victim] >= 0) {
-        // Write the old part back on the outbound stream and bring the new one in on the
-        // inbound stream, piece by piece: the upload of a piece waits only for the
-        // write-back of the same bytes of the slot.  A later upload of the old part must
-        // see its host bytes; it is queued on the inbound stream after these waits, the
-        // last of which covers the whole write-back.
-        const int32_t old = slot_part[victim];
-        const size_t old_bytes = static_cast<size_t>(L.size(old)) * d * 4;
-        float *old_host = M_host + static_cast<int64_t>(L.lo(old)) * d;
-        const size_t longest = std::max(old_bytes, new_bytes);
-        size_t piece = (longest + kSwapChunks - 1) / kSwapChunks;
-        piece = std::max<size_t>((piece + 255) / 256 * 256, size_t(8) << 20);
-        // after the last kernel that used the slot, and after the upload that filled it (a
-        // part brought in ahead of time may leave again before any kernel has used it)
-        if (hipStreamWaitEvent(copy_out, slot_used[victim], 0) != hipSuccess) return -2;
-        if (hipStreamWaitEvent(copy_out, slot_ready[victim], 0) != hipSuccess) return -2;
-        char *slot_bytes = reinterpret_cast<char *>(slot[victim]);
-        int c = 0;
-        for (size_t off = 0; off < longest; off += piece, ++c) {
-          hipEvent_t flushed = chunk_flushed[static_cast<size_t>(victim) * kSwapChunks + c];
-          if (off < old_bytes) {
-            if (hipMemcpyAsync(reinterpret_cast<char *>(old_host) + off, slot_bytes + off,
-                               std::min(piece, old_bytes - off), hipMemcpyDeviceToHost, copy_out) != hipSuccess)
-              return -2;
-            if (hipEventRecord(flushed, copy_out) != hipSuccess) return -2;
-            if (hipStreamWaitEvent(copy, flushed, 0) != hipSuccess) return -2;
-          }
-          if (off < new_bytes &&
-              hipMemcpyAsync(slot_bytes + off, reinterpret_cast<const char *>(new_host) + off,
-                             std::min(piece, new_bytes - off), hipMemcpyHostToDevice, copy) != hipSuccess)
-            return -2;
-        }
-        st.bytes_d2h += old_bytes;
-      } else {
-        if (hipStreamWaitEvent(copy, slot_used[victim], 0) != hipSuccess) return -2;
-        if (hipMemcpyAsync(slot[victim], new_host, new_bytes, hipMemcpyHostToDevice, copy) != hipSuccess) return -2;
-      }
-      st.bytes_h2d += new_bytes;
-      if (hipEventRecord(slot_ready[victim], copy) != hipSuccess) return -2;
-      slot_part[victim] = p;
-      return victim;
-    };
-    // Makes the parts of visit vi resident as far as slots allow, never evicting a part
-    // in `keep` (the parts of the running visit and of the visits before vi).  Returns 1 if
-    // a needed part could not be placed, -2 on error, else 0; the parts of vi join `keep`.
-    auto ensure_parts = [&](int64_t vi, std::vector<int32_t> &keep) -> int {
-      if (vi >= visits) return 1;
-      const int64_t q = vi % npairs;
-      keep.push_back(pa[q]);
-      keep.push_back(pb[q]);
-      const int32_t need[2] = {pa[q], pb[q]};
-      for (int t = 0; t < 2; ++t) {
-        if (t == 1 && need[1] == need[0]) break;
-        if (slot_of(need[t]) >= 0) continue;
-        const int got = load_part(need[t], keep, vi);
-        if (got == -2) return -2;
-        if (got == -1) return 1;
-      }
-      return 0;
-    };
-    std::vector<int32_t> keep;
-    const int64_t max_ahead = (flags & GOSH_FLAG_BLOCKED_ORDER) ? P : 1;
-
-    for (int64_t vi = 0; vi < visits && rc == GOSH_OK; ++vi) {
-      int32_t a, b;
-      uint32_t rot, q;
-      visit_pair(vi, a, b, rot, q);
-      // 1. the two parts of this visit (nothing is running that they could disturb: the
-      //    copy stream waits for the last kernel of any slot it overwrites)
-      keep.clear();
-      if (ensure_parts(vi, keep) == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
-      const int sa = slot_of(a), sb = slot_of(b);
-      if (sa < 0 || sb < 0) { rc = gosh::fail(GOSH_EHIP, "internal: part not resident"); break; }
-      const int ps = static_cast<int>(vi % S), hs = static_cast<int>(vi % NS);
-      if (graph_on_device) {
-        // 2. the pool of this visit, drawn on the device right before the kernel that reads
-        //    it (same stream: the pool's previous reader is done, its next reader waits)
-        const uint32_t w3 = level_word(level, q);
-        auto fill = [&](int32_t lo, int32_t cnt, int32_t olo, int32_t ohi, int32_t side, int32_t *pool) {
-          if (cnt <= 0) return;
-          const int blocks = static_cast<int>(std::min<int64_t>((static_cast<int64_t>(cnt) + 255) / 256, 65536));
-          if (g_host->xadj_is64)
-            hipLaunchKernelGGL(fill_pool_kernel<int64_t>, dim3(blocks), dim3(256), 0, compute,
-                               static_cast<const int64_t *>(g_host->xadj), g_host->adj, g_host->nnz, lo, cnt, olo, ohi, side, B,
-                               per_round, key0, key1, rot, w3, pool);
-          else
-            hipLaunchKernelGGL(fill_pool_kernel<int32_t>, dim3(blocks), dim3(256), 0, compute,
-                               static_cast<const int32_t *>(g_host->xadj), g_host->adj, g_host->nnz, lo, cnt, olo, ohi, side, B,
-                               per_round, key0, key1, rot, w3, pool);
-        };
-        fill(L.lo(a), L.size(a), L.lo(b), L.lo(b) + L.size(b), 0, dpool[ps]);
-        if (a != b)
-          fill(L.lo(b), L.size(b), L.lo(a), L.lo(a) + L.size(a), 1, dpool[ps] + static_cast<size_t>(L.part_rows) * B);
-        if ((rc = gosh::check_launch("fill_pool_kernel"))) break;
-        PARTS_HIP(hipEventRecord(pool_ready[ps], compute), "hipEventRecord");
-        // marks, on the inbound stream, the point up to which this visit's parts are in
-        PARTS_HIP(hipEventRecord(arrived, copy), "hipEventRecord");
-      } else {
-      // 2. the pool of this visit: wait for the sampler, upload on the copy stream
-      {
-        const auto t_wait = std::chrono::steady_clock::now();
-        std::unique_lock<std::mutex> lock(mu);
-        cv.wait(lock, [&] { return filled > vi; });
-        st.sampler_wait_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_wait).count();
-      }
-      PARTS_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
-      {
-        const size_t side0 = static_cast<size_t>(L.size(a)) * B * 4;
-        PARTS_HIP(hipMemcpyAsync(dpool[ps], staging[hs], side0, hipMemcpyHostToDevice, copy), "pool upload");
-        st.bytes_h2d += side0;
-        if (a != b) {
-          const size_t side1 = static_cast<size_t>(L.size(b)) * B * 4;
-          PARTS_HIP(hipMemcpyAsync(dpool[ps] + static_cast<size_t>(L.part_rows) * B,
-                                   staging[hs] + static_cast<size_t>(L.part_rows) * B, side1,
-                                   hipMemcpyHostToDevice, copy), "pool upload");
-          st.bytes_h2d += side1;
-        }
-      }
-      PARTS_HIP(hipEventRecord(pool_ready[ps], copy), "hipEventRecord");
-      PARTS_HIP(hipEventRecord(staging_done[hs], copy), "hipEventRecord");
-      }
-      // 3. the pair kernel
-      PARTS_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
-      PARTS_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
-      PARTS_HIP(hipStreamWaitEvent(compute, pool_ready[ps], 0), "hipStreamWaitEvent");
-      {
-        PairWork w{};
-        w.a_lo = L.lo(a); w.a_n = L.size(a); w.b_lo = L.lo(b); w.b_n = L.size(b);
-        w.a_rows = slot[sa]; w.b_rows = slot[sb];
-        w.pool_a = dpool[ps];
-        w.pool_b = dpool[ps] + static_cast<size_t>(L.part_rows) * B;
-        w.B = B; w.per_round = per_round; w.d = d; w.diagonal = a == b;
-        w.key0 = key0; w.key1 = key1; w.rotation = rot; w.word3 = level_word(level, q);
-        gosh::SgdArgs args{};
-        args.hot = hot;
-        args.d = d;
-        args.k_neg = k_neg;
-        args.samples = samples;
-        args.lr = gosh_lr(lr0, rot, rotations);
-        const int timer = static_cast<int>(vi % kTimers);
-        if (k_pending[timer]) {
-          float ms = 0.f;
-          PARTS_HIP(hipEventSynchronize(k_end[timer]), "hipEventSynchronize");
-          PARTS_HIP(hipEventElapsedTime(&ms, k_begin[timer], k_end[timer]), "hipEventElapsedTime");
-          st.kernel_ms += ms;
-          k_pending[timer] = 0;
-        }
-        PARTS_HIP(hipEventRecord(k_begin[timer], compute), "hipEventRecord");
-        gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, gosh::tuning().row_policy == 0,
-                                            gosh::tuning().max_waves, compute);
-        if ((rc = gosh::check_launch("sgd_kernel (pair)"))) break;
-        PARTS_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
-        k_pending[timer] = 1;
-        st.updates += w.count() * samples;
-      }
-      PARTS_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
-      PARTS_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
-      PARTS_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
-      // 4. while that kernel runs: bring in what the next visit needs.  In the blocked order
-      //    the part after the one being streamed is known to be worth its slot, so there
-      //    the fetch runs as far ahead as slots that none of the visits in between uses can
-      //    be found; in the paper's order fetching further ahead evicts parts the next row
-      //    would have reused (measured: 376 GB instead of 309 GB per rotation at 5 slots).
-      {
-        keep.assign({a, b});
-        int got = 0;
-        for (int64_t ahead = 1; ahead <= max_ahead && got == 0; ++ahead) got = ensure_parts(vi + ahead, keep);
-        if (got == -2) { rc = gosh::fail(GOSH_EHIP, "part transfer failed"); break; }
-      }
-      if (graph_on_device) {
-        // 5. nothing to hand back; only keep the host from running ahead: it continues once
-        //    the parts of this visit have arrived, as it does with a host sampler (with
-        //    several swaps queued at once the copies of a swap took four times as long)
-        PARTS_HIP(hipEventSynchronize(arrived), "hipEventSynchronize");
-      } else {
-        // 5. hand the staging buffer back to the sampler once its upload is done
-        PARTS_HIP(hipEventSynchronize(staging_done[hs]), "hipEventSynchronize");
-        {
-          std::lock_guard<std::mutex> lock(mu);
-          released = vi + 1;
-        }
-        cv.notify_all();
-      }
-    }
-    if (rc == GOSH_OK) {
-      // write every resident part back
-      for (int s = 0; s < P; ++s) {
-        if (slot_part[s] < 0) continue;
-        const int32_t old = slot_part[s];
-        const size_t bytes = static_cast<size_t>(L.size(old)) * d * 4;
-        PARTS_HIP(hipStreamWaitEvent(copy_out, slot_used[s], 0), "hipStreamWaitEvent");
-        PARTS_HIP(hipMemcpyAsync(M_host + static_cast<int64_t>(L.lo(old)) * d, slot[s], bytes,
-                                 hipMemcpyDeviceToHost, copy_out), "part write-back");
-        st.bytes_d2h += bytes;
-      }
-      PARTS_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
-      PARTS_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
-      PARTS_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
-      for (int t = 0; t < kTimers; ++t) {
-        float ms = 0.f;
-        if (k_pending[t] && hipEventElapsedTime(&ms, k_begin[t], k_end[t]) == hipSuccess) st.kernel_ms += ms;
-      }
-    }
-  }
-
-done:
-  {
-    std::lock_guard<std::mutex> lock(mu);
-    stop = true;
-    released = visits + NS;  // unblock the sampler
-  }
-  cv.notify_all();
-  if (sampler.joinable()) sampler.join();
-  st.sampler_ms = sampler_busy_ms;
-  if (compute) (void)hipStreamSynchronize(compute);
-  if (copy) (void)hipStreamSynchronize(copy);
-  if (copy_out) (void)hipStreamSynchronize(copy_out);
-  if (arrived) (void)hipEventDestroy(arrived);
-  for (auto e : chunk_flushed) if (e) (void)hipEventDestroy(e);
-  for (auto e : k_begin) if (e) (void)hipEventDestroy(e);
-  for (auto e : k_end) if (e) (void)hipEventDestroy(e);
-  for (auto e : slot_ready) if (e) (void)hipEventDestroy(e);
-  for (auto e : slot_used) if (e) (void)hipEventDestroy(e);
-  for (auto e : pool_ready) if (e) (void)hipEventDestroy(e);
-  for (auto e : pool_used) if (e) (void)hipEventDestroy(e);
-  for (auto e : staging_done) if (e) (void)hipEventDestroy(e);
-  for (auto p : slot) if (p) (void)hipFree(p);
-  for (auto p : dpool) if (p) (void)hipFree(p);
-  for (auto p : staging) if (p) (void)hipHostFree(p);
-  if (hot_bits_dev) (void)hipFree(hot_bits_dev);
-  if (compute) (void)hipStreamDestroy(compute);
-  if (copy) (void)hipStreamDestroy(copy);
-  if (copy_out) (void)hipStreamDestroy(copy_out);
   st.wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   if (stats_out) *stats_out = st;
   return rc;
