@@ -62,6 +62,12 @@ def test_random_cases_match_the_oracle(sweep_seed):
         want = M0.copy()
         O.train_epoch(xadj, adj, want, k, lr, seed, epoch, level)
         assert rel_err(M.cpu().numpy(), want) <= 1e-5
+        # the concurrent kernels (default mix, plain stores, atomic adds) move nothing at lr = 0
+        for flags in (0, G.GOSH_FLAG_PLAIN_STORES, G.GOSH_FLAG_ATOMIC_ADDS):
+            M = torch.from_numpy(M0.copy()).to(DEV)
+            G.gosh_train_epoch(g, M, k, 0.0, seed, epoch, level, flags)
+            torch.cuda.synchronize()
+            assert np.array_equal(M.cpu().numpy(), M0)
 
         # Alg. 4 on the device and the sequential V-cycle of Alg. 2
         thr, shrink = int(rng.choice([1, 10, 100])), float(rng.choice([0.5, 0.8, 0.95]))
