@@ -184,9 +184,12 @@ def test_concurrent_rotation_with_zero_lr_moves_nothing(flags):
         for a, b in G.gosh_pair_order(5))
 
 
-def test_concurrent_rotation_aucroc():
+@pytest.mark.parametrize("blocked_on_device", [False, True])
+def test_concurrent_rotation_aucroc(blocked_on_device):
     """Rotation training with a budget a quarter of the matrix reaches the quality of the
-    oracle's rotation and of ordinary in-device training."""
+    oracle's rotation and of ordinary in-device training -- in the paper's pair order with
+    the host sampler, and in the blocked order with four slots and positives drawn on the
+    device."""
     n = 1 << 12
     edges = graphgen.rmat(12, 1 << 16, 2)
     train, test = graphgen.holdout_split(edges, 0.1, 1002)
@@ -195,12 +198,18 @@ def test_concurrent_rotation_aucroc():
     sets = make_eval_sets(n, train.numpy(), test.numpy(), seed=1)
     d, k, epochs, lr0, B = 32, 3, 300, 0.045, 5
     budget = n * d * 4 // 4 * 2
-    plan = G.gosh_parts_plan(n, d, epochs, budget, 3, 4, B)
+    P = 4 if blocked_on_device else 3
+    plan = G.gosh_parts_plan(n, d, epochs, budget, P, 4, B)
     K = plan["K"]
     Mo = O.init_embedding(n, d, 1, 0)
-    O.train_parts(xadj, adj, Mo, k, epochs, lr0, 1, 0, K, B)
+    O.train_parts(xadj, adj, Mo, k, epochs, lr0, 1, 0, K, B,
+                  block=O.blocked_block_size(P, K) if blocked_on_device else 0)
     M = torch.from_numpy(O.init_embedding(n, d, 1, 0)).pin_memory()
-    st = G.gosh_train_parts(n, c.xadj, c.adj, M, k, epochs, lr0, 1, device_budget_bytes=budget, B=B)
+    if blocked_on_device:
+        st = G.gosh_train_parts(n, c.xadj.to(DEV), c.adj.to(DEV), M, k, epochs, lr0, 1, device_budget_bytes=budget,
+                                P_gpu=P, B=B, flags=G.GOSH_FLAG_BLOCKED_ORDER)
+    else:
+        st = G.gosh_train_parts(n, c.xadj, c.adj, M, k, epochs, lr0, 1, device_budget_bytes=budget, B=B)
     ho, fo = aucroc(Mo, sets)
     hg, fg = aucroc(M.numpy(), sets)
     say(f"[auc parts] K={K} rotations={st['rotations']} oracle {ho:.4f}/{fo:.4f} gpu {hg:.4f}/{fg:.4f} "
