@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 
 #include "gosh_common.h"
 
@@ -110,12 +111,14 @@ struct HotScratch {
 };
 constexpr int kMaxDevices = 64;
 HotScratch g_hot_scratch[kMaxDevices];
+std::mutex g_hot_scratch_mutex;  // guards the table, not the use of the buffers
 }  // namespace
 
 int hot_scratch(size_t bytes, void **out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
     return fail(GOSH_EHIP, "cannot identify the current device");
+  std::lock_guard<std::mutex> lock(g_hot_scratch_mutex);
   HotScratch &h = g_hot_scratch[dev];
   if (h.bytes < bytes) {
     if (h.ptr) (void)hipFree(h.ptr);
