@@ -255,7 +255,9 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
                float *M0_dev, gosh_level_stats *stats, void *hip_stream);
 
 /* Alg. 2 including its "fits into GPU" branch, with the result on the host.  Levels whose
- * graph and matrix fit device_budget_bytes (0 = everything fits) are trained as in
+ * graph and matrix fit device_budget_bytes (0 = what the current device has free when the
+ * call starts, less a sixteenth; graphs the hierarchy already keeps there are outside
+ * that figure) are trained as in
  * gosh_embed; the others are trained with gosh_train_parts(level i, e_i epochs, the same
  * budget, P_gpu, S_gpu, B) on a host-resident matrix.  Projection runs on the device
  * (slice by slice when the finer level lives on the host); only when both levels live

@@ -99,6 +99,7 @@ struct Plan {
   uint32_t parts_flags;  // for the rotation calls: the same plus GOSH_FLAG_BLOCKED_ORDER if asked
   bool edge_epochs;
   uint64_t budget;
+  bool budget_is_free_memory;  // measured, not given: graphs already on the device are outside it
   int32_t P_gpu, S_gpu, B;
 };
 
@@ -180,7 +181,12 @@ class MultilevelRun {
     const gosh::DeviceLevel *dl = gosh::hierarchy_device_level(h, i);
     return dl != nullptr && dl->device == current_device ? dl : nullptr;
   }
-  bool fits(int i) const { return pl.budget == 0 || level_bytes(G[static_cast<size_t>(i)], d) <= pl.budget; }
+  bool fits(int i) const {
+    if (pl.budget == 0) return true;
+    const gosh_csr &g = G[static_cast<size_t>(i)];
+    if (pl.budget_is_free_memory && resident(i) != nullptr) return static_cast<size_t>(g.n) * d * 4 <= pl.budget;
+    return level_bytes(g, d) <= pl.budget;
+  }
 
   // "Randomly initialize M_{D-1}"
   int init_coarsest(int i) {
@@ -413,7 +419,7 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
   // A level above level 0 can only exceed the budget if level 0 does too, which is refused.
   const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
   const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
-                device_budget_bytes, 3, 4, 5};
+                device_budget_bytes, false, 3, 4, 5};
   return embed_impl(h, pl, epochs, p, M0_dev, nullptr, stats, gosh::as_stream(hip_stream));
 }
 
@@ -426,8 +432,17 @@ int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t e
   if (P_gpu < 2 || S_gpu < 1 || B < 1)
     return gosh::fail(GOSH_EINVAL, "need P_gpu >= 2, S_gpu >= 1, B >= 1");
   const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
+  // No budget given: Alg. 2's "fits into the GPU" is asked of the device itself -- what it has
+  // free now, less a sixteenth for the staging buffers and pools of the calls below.
+  const bool measure = device_budget_bytes == 0;
+  if (measure) {
+    size_t free_bytes = 0, total_bytes = 0;
+    GOSH_HIP(hipMemGetInfo(&free_bytes, &total_bytes), "hipMemGetInfo");
+    device_budget_bytes = free_bytes - free_bytes / 16;
+    if (device_budget_bytes == 0) return gosh::fail(GOSH_ENOMEM, "the device has no free memory");
+  }
   const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags | (flags & GOSH_FLAG_BLOCKED_ORDER),
-                (flags & GOSH_FLAG_EDGE_EPOCHS) != 0, device_budget_bytes, P_gpu, S_gpu, B};
+                (flags & GOSH_FLAG_EDGE_EPOCHS) != 0, device_budget_bytes, measure, P_gpu, S_gpu, B};
   return embed_impl(h, pl, epochs, p, nullptr, M0_host, stats, gosh::as_stream(hip_stream));
 }
 
