@@ -333,12 +333,6 @@ struct Buffers {
   }
 };
 
-#define COARSE_HIP(call, what)                                                         \
-  do {                                                                                 \
-    hipError_t e_ = (call);                                                            \
-    if (e_ != hipSuccess) return gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_)); \
-  } while (0)
-
 int blocks_for(int64_t items, int per_block) {
   int64_t b = (items + per_block - 1) / per_block;
   return static_cast<int>(std::min<int64_t>(std::max<int64_t>(b, 1), 1 << 16));
@@ -406,7 +400,7 @@ void device_level_drop_map(DeviceLevel &level) {
 
 int device_level_upload(DeviceCoarsener *dc, const gosh_csr &host, DeviceLevel &out) {
   device_level_free(out);
-  COARSE_HIP(hipGetDevice(&out.device), "hipGetDevice");
+  GOSH_TRY_HIP(hipGetDevice(&out.device), "hipGetDevice");
   out.n = host.n;
   out.nnz = host.nnz;
   out.xadj_is64 = host.xadj_is64 ? 1 : 0;
@@ -422,7 +416,7 @@ int device_level_upload(DeviceCoarsener *dc, const gosh_csr &host, DeviceLevel &
 
 int device_level_borrow(const gosh_csr &on_device, DeviceLevel &out) {
   device_level_free(out);
-  COARSE_HIP(hipGetDevice(&out.device), "hipGetDevice");
+  GOSH_TRY_HIP(hipGetDevice(&out.device), "hipGetDevice");
   out.n = on_device.n;
   out.nnz = on_device.nnz;
   out.xadj_is64 = on_device.xadj_is64 ? 1 : 0;
@@ -451,7 +445,7 @@ int device_level_check(const DeviceLevel &out) {
     ~FlagGuard() { (void)hipFree(p); }
   } guard{bad_dev};
   int32_t bad = 0;
-  COARSE_HIP(hipMemset(bad_dev, 0, 4), "clear check flag");
+  GOSH_TRY_HIP(hipMemset(bad_dev, 0, 4), "clear check flag");
   const int off_blocks = blocks_for(host.n, 256);
   if (host.xadj_is64)
     hipLaunchKernelGGL(check_offsets_kernel<int64_t>, dim3(off_blocks), dim3(256), 0, nullptr,
@@ -460,13 +454,13 @@ int device_level_check(const DeviceLevel &out) {
     hipLaunchKernelGGL(check_offsets_kernel<int32_t>, dim3(off_blocks), dim3(256), 0, nullptr,
                        static_cast<const int32_t *>(out.xadj), out.n, out.nnz, bad_dev);
   if (int rc = gosh::check_launch("check_offsets_kernel")) return rc;
-  COARSE_HIP(hipMemcpy(&bad, bad_dev, 4, hipMemcpyDeviceToHost), "read check flag");
+  GOSH_TRY_HIP(hipMemcpy(&bad, bad_dev, 4, hipMemcpyDeviceToHost), "read check flag");
   if (bad) return gosh::fail(GOSH_EINVAL, "xadj does not run from 0 to nnz without decreasing");
   if (host.nnz > 0) {
     hipLaunchKernelGGL(check_neighbours_kernel, dim3(blocks_for(host.nnz, 256)), dim3(256), 0, nullptr, out.adj,
                        out.nnz, out.n, bad_dev);
     if (int rc = gosh::check_launch("check_neighbours_kernel")) return rc;
-    COARSE_HIP(hipMemcpy(&bad, bad_dev, 4, hipMemcpyDeviceToHost), "read check flag");
+    GOSH_TRY_HIP(hipMemcpy(&bad, bad_dev, 4, hipMemcpyDeviceToHost), "read check flag");
     if (bad) return gosh::fail(GOSH_EINVAL, "a neighbour id is outside [0, n)");
   }
   return GOSH_OK;
@@ -475,7 +469,7 @@ int device_level_check(const DeviceLevel &out) {
 int device_level_set_map(DeviceLevel &level, const int32_t *map_host) {
   if (level.map == nullptr)
     if (int rc = persistent(&level.map, static_cast<size_t>(level.n), "map")) return rc;
-  COARSE_HIP(hipMemcpy(level.map, map_host, static_cast<size_t>(level.n) * 4, hipMemcpyHostToDevice), "copy map");
+  GOSH_TRY_HIP(hipMemcpy(level.map, map_host, static_cast<size_t>(level.n) * 4, hipMemcpyHostToDevice), "copy map");
   return GOSH_OK;
 }
 
@@ -499,12 +493,12 @@ struct StagedCopy {
     for (int i = 0; i < 2; ++i)
       if (dc->slot[i] == nullptr) {
         void *p = nullptr;
-        COARSE_HIP(hipHostMalloc(&p, DeviceCoarsener::kSlotBytes, hipHostMallocDefault), "allocate pinned staging");
+        GOSH_TRY_HIP(hipHostMalloc(&p, DeviceCoarsener::kSlotBytes, hipHostMallocDefault), "allocate pinned staging");
         dc->slot[i] = static_cast<char *>(p);
       }
-    COARSE_HIP(hipStreamCreate(&stream), "create copy stream");
+    GOSH_TRY_HIP(hipStreamCreate(&stream), "create copy stream");
     for (int i = 0; i < 2; ++i)
-      COARSE_HIP(hipEventCreateWithFlags(&done[i], hipEventDisableTiming), "create copy event");
+      GOSH_TRY_HIP(hipEventCreateWithFlags(&done[i], hipEventDisableTiming), "create copy event");
     return GOSH_OK;
   }
   void host_copy(char *to, const char *from, size_t bytes) const {
@@ -531,7 +525,7 @@ bool is_pinned_host(const void *p) {
 int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t bytes) {
   if (bytes == 0) return GOSH_OK;
   if (dc == nullptr || bytes < 4 * DeviceCoarsener::kSlotBytes) {
-    COARSE_HIP(hipMemcpy(dst, src_dev, bytes, hipMemcpyDeviceToHost), "download");
+    GOSH_TRY_HIP(hipMemcpy(dst, src_dev, bytes, hipMemcpyDeviceToHost), "download");
     return GOSH_OK;
   }
   StagedCopy q(dc);
@@ -544,11 +538,11 @@ int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t 
                                   piece_bytes(c), hipMemcpyDeviceToHost, q.stream);
     return e != hipSuccess ? e : hipEventRecord(q.done[c & 1], q.stream);
   };
-  COARSE_HIP(start(0), "start download");
+  GOSH_TRY_HIP(start(0), "start download");
   for (size_t c = 0; c < pieces; ++c) {
     // slot (c + 1) & 1 was emptied in the previous iteration
-    if (c + 1 < pieces) COARSE_HIP(start(c + 1), "start download");
-    COARSE_HIP(hipEventSynchronize(q.done[c & 1]), "wait for download");
+    if (c + 1 < pieces) GOSH_TRY_HIP(start(c + 1), "start download");
+    GOSH_TRY_HIP(hipEventSynchronize(q.done[c & 1]), "wait for download");
     q.host_copy(static_cast<char *>(dst) + c * slot_bytes, dc->slot[c & 1], piece_bytes(c));
   }
   return GOSH_OK;
@@ -557,7 +551,7 @@ int device_download(DeviceCoarsener *dc, void *dst, const void *src_dev, size_t 
 int device_upload(DeviceCoarsener *dc, void *dst_dev, const void *src, size_t bytes) {
   if (bytes == 0) return GOSH_OK;
   if (dc == nullptr || bytes < 4 * DeviceCoarsener::kSlotBytes || is_pinned_host(src)) {
-    COARSE_HIP(hipMemcpy(dst_dev, src, bytes, hipMemcpyHostToDevice), "upload");
+    GOSH_TRY_HIP(hipMemcpy(dst_dev, src, bytes, hipMemcpyHostToDevice), "upload");
     return GOSH_OK;
   }
   StagedCopy q(dc);
@@ -567,13 +561,13 @@ int device_upload(DeviceCoarsener *dc, void *dst_dev, const void *src, size_t by
   for (size_t c = 0; c < pieces; ++c) {
     const size_t len = std::min(slot_bytes, bytes - c * slot_bytes);
     // the DMA of piece c - 2 must have drained this slot
-    if (c >= 2) COARSE_HIP(hipEventSynchronize(q.done[c & 1]), "wait for upload");
+    if (c >= 2) GOSH_TRY_HIP(hipEventSynchronize(q.done[c & 1]), "wait for upload");
     q.host_copy(dc->slot[c & 1], static_cast<const char *>(src) + c * slot_bytes, len);
-    COARSE_HIP(hipMemcpyAsync(static_cast<char *>(dst_dev) + c * slot_bytes, dc->slot[c & 1], len,
+    GOSH_TRY_HIP(hipMemcpyAsync(static_cast<char *>(dst_dev) + c * slot_bytes, dc->slot[c & 1], len,
                               hipMemcpyHostToDevice, q.stream), "upload piece");
-    COARSE_HIP(hipEventRecord(q.done[c & 1], q.stream), "record upload");
+    GOSH_TRY_HIP(hipEventRecord(q.done[c & 1], q.stream), "record upload");
   }
-  COARSE_HIP(hipStreamSynchronize(q.stream), "finish upload");
+  GOSH_TRY_HIP(hipStreamSynchronize(q.stream), "finish upload");
   return GOSH_OK;
 }
 
@@ -601,20 +595,20 @@ int mark_impl(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *d
   if (int rc = gosh::check_launch("degree_keys_kernel")) return rc;
   {
     size_t temp_bytes = 0;
-    COARSE_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, ids, order,
+    GOSH_TRY_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, ids, order,
                                          static_cast<size_t>(n), 0u, 31u, nullptr),
                "degree sort (size query)");
     char *temp = nullptr;
     if (int rc = buf.alloc(&temp, temp_bytes, "sort workspace")) return rc;
-    COARSE_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, ids, order,
+    GOSH_TRY_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, ids, order,
                                          static_cast<size_t>(n), 0u, 31u, nullptr),
                "degree sort");
-    COARSE_HIP(hipDeviceSynchronize(), "degree sort");
+    GOSH_TRY_HIP(hipDeviceSynchronize(), "degree sort");
     buf.release(temp);
   }
   hipLaunchKernelGGL(rank_kernel, dim3(flat_blocks), dim3(256), 0, nullptr, keys_sorted, order, n, nnz, rk);
   if (int rc = gosh::check_launch("rank_kernel")) return rc;
-  COARSE_HIP(hipDeviceSynchronize(), "ranks");
+  GOSH_TRY_HIP(hipDeviceSynchronize(), "ranks");
   buf.release(keys);
   buf.release(keys_sorted);
   buf.release(ids);
@@ -627,25 +621,25 @@ int mark_impl(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *d
   if (int rc = buf.alloc(&pending, static_cast<size_t>(n), "pending list")) return rc;
   if (int rc = buf.alloc(&still, static_cast<size_t>(n), "pending list")) return rc;
   if (int rc = buf.alloc(&counters, 2, "pending counters")) return rc;
-  COARSE_HIP(hipMemset(counters, 0, 16), "clear counters");
+  GOSH_TRY_HIP(hipMemset(counters, 0, 16), "clear counters");
   const int wave_blocks = blocks_for(n, 4);  // four wavefronts (vertices) per block
   hipLaunchKernelGGL(classify_kernel<OffT>, dim3(wave_blocks), dim3(256), 0, nullptr, xadj, adj, rk, n, status,
                      pending, counters);
   if (int rc = gosh::check_launch("classify_kernel")) return rc;
   unsigned long long count = 0;
-  COARSE_HIP(hipMemcpy(&count, counters, 8, hipMemcpyDeviceToHost), "read pending count");
+  GOSH_TRY_HIP(hipMemcpy(&count, counters, 8, hipMemcpyDeviceToHost), "read pending count");
 
   // rounds: each decides at least the first pending vertex of the order, usually most
   const int kMaxRounds = 256;
   int which = 0;  // counters[which] is the size of `pending`
   for (int round = 0; count > 0; ++round) {
     if (round == kMaxRounds) return GOSH_OK;  // *done stays false
-    COARSE_HIP(hipMemset(counters + (which ^ 1), 0, 8), "clear counter");
+    GOSH_TRY_HIP(hipMemset(counters + (which ^ 1), 0, 8), "clear counter");
     hipLaunchKernelGGL(round_kernel<OffT>, dim3(blocks_for(static_cast<int64_t>(count), 4)), dim3(256), 0, nullptr,
                        xadj, adj, rk, status, pending, static_cast<int64_t>(count), still, counters + (which ^ 1));
     if (int rc = gosh::check_launch("round_kernel")) return rc;
     unsigned long long left = 0;
-    COARSE_HIP(hipMemcpy(&left, counters + (which ^ 1), 8, hipMemcpyDeviceToHost), "read pending count");
+    GOSH_TRY_HIP(hipMemcpy(&left, counters + (which ^ 1), 8, hipMemcpyDeviceToHost), "read pending count");
     // a long chain: a few vertices per round would take forever
     if (round >= 16 && left > 4096 && left * 100 > count * 99) return GOSH_OK;
     std::swap(pending, still);
@@ -663,20 +657,20 @@ int mark_impl(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *d
   if (int rc = gosh::check_launch("hub_flags_kernel")) return rc;
   {
     size_t temp_bytes = 0;
-    COARSE_HIP(rocprim::exclusive_scan(nullptr, temp_bytes, flags, index, int32_t(0), static_cast<size_t>(n),
+    GOSH_TRY_HIP(rocprim::exclusive_scan(nullptr, temp_bytes, flags, index, int32_t(0), static_cast<size_t>(n),
                                        rocprim::plus<int32_t>(), nullptr),
                "hub scan (size query)");
     char *temp = nullptr;
     if (int rc = buf.alloc(&temp, temp_bytes, "scan workspace")) return rc;
-    COARSE_HIP(rocprim::exclusive_scan(temp, temp_bytes, flags, index, int32_t(0), static_cast<size_t>(n),
+    GOSH_TRY_HIP(rocprim::exclusive_scan(temp, temp_bytes, flags, index, int32_t(0), static_cast<size_t>(n),
                                        rocprim::plus<int32_t>(), nullptr),
                "hub scan");
-    COARSE_HIP(hipDeviceSynchronize(), "hub scan");
+    GOSH_TRY_HIP(hipDeviceSynchronize(), "hub scan");
     buf.release(temp);
   }
   int32_t last_flag = 0, last_index = 0;
-  COARSE_HIP(hipMemcpy(&last_flag, flags + (n - 1), 4, hipMemcpyDeviceToHost), "read hub count");
-  COARSE_HIP(hipMemcpy(&last_index, index + (n - 1), 4, hipMemcpyDeviceToHost), "read hub count");
+  GOSH_TRY_HIP(hipMemcpy(&last_flag, flags + (n - 1), 4, hipMemcpyDeviceToHost), "read hub count");
+  GOSH_TRY_HIP(hipMemcpy(&last_index, index + (n - 1), 4, hipMemcpyDeviceToHost), "read hub count");
   if (fine.map == nullptr)
     if (int rc = persistent(&fine.map, static_cast<size_t>(n), "map")) return rc;
   hipLaunchKernelGGL(number_hubs_kernel, dim3(flat_blocks), dim3(256), 0, nullptr, flags, index, order, n, fine.map);
@@ -684,7 +678,7 @@ int mark_impl(DeviceCoarsener *dc, DeviceLevel &fine, int64_t *n_coarse, bool *d
   hipLaunchKernelGGL(join_kernel<OffT>, dim3(wave_blocks), dim3(256), 0, nullptr, xadj, adj, rk, status, order, n,
                      fine.map);
   if (int rc = gosh::check_launch("join_kernel")) return rc;
-  COARSE_HIP(hipDeviceSynchronize(), "marking");
+  GOSH_TRY_HIP(hipDeviceSynchronize(), "marking");
   *n_coarse = static_cast<int64_t>(last_flag) + last_index;
   *done = true;
   return GOSH_OK;
@@ -715,7 +709,7 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
   coarse.xadj = xadj_out;
   if (nnz == 0) {
     coarse.nnz = 0;
-    COARSE_HIP(hipMemset(xadj_out, 0, (static_cast<size_t>(n_coarse) + 1) * 8), "clear coarse offsets");
+    GOSH_TRY_HIP(hipMemset(xadj_out, 0, (static_cast<size_t>(n_coarse) + 1) * 8), "clear coarse offsets");
     if (int rc = persistent(&coarse.adj, 0, "coarse adjacency")) return rc;
     if (int rc = persistent(&coarse.mult, 0, "coarse multiplicities")) return rc;
     return GOSH_OK;
@@ -746,25 +740,25 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
     if (int rc = buf.alloc(&vals_sorted, static_cast<size_t>(nnz), "sorted values")) return rc;
   size_t temp_bytes = 0;
   if (weighted)
-    COARSE_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, vals, vals_sorted,
+    GOSH_TRY_HIP(rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_sorted, vals, vals_sorted,
                                          static_cast<size_t>(nnz), 0u, end_bit, nullptr),
                "radix sort (size query)");
   else
-    COARSE_HIP(rocprim::radix_sort_keys(nullptr, temp_bytes, keys, keys_sorted, static_cast<size_t>(nnz), 0u,
+    GOSH_TRY_HIP(rocprim::radix_sort_keys(nullptr, temp_bytes, keys, keys_sorted, static_cast<size_t>(nnz), 0u,
                                         end_bit, nullptr),
                "radix sort (size query)");
   {
     char *temp = nullptr;
     if (int rc = buf.alloc(&temp, temp_bytes, "sort workspace")) return rc;
     if (weighted)
-      COARSE_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, vals, vals_sorted,
+      GOSH_TRY_HIP(rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_sorted, vals, vals_sorted,
                                            static_cast<size_t>(nnz), 0u, end_bit, nullptr),
                  "radix sort");
     else
-      COARSE_HIP(rocprim::radix_sort_keys(temp, temp_bytes, keys, keys_sorted, static_cast<size_t>(nnz), 0u,
+      GOSH_TRY_HIP(rocprim::radix_sort_keys(temp, temp_bytes, keys, keys_sorted, static_cast<size_t>(nnz), 0u,
                                           end_bit, nullptr),
                  "radix sort");
-    COARSE_HIP(hipDeviceSynchronize(), "radix sort");
+    GOSH_TRY_HIP(hipDeviceSynchronize(), "radix sort");
     buf.release(temp);
   }
   // distinct keys go where the unsorted ones were (at most one distinct key per fine entry;
@@ -778,17 +772,17 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
   unsigned long long n_unique = 0;
   auto reduce = [&](auto values_in) -> int {
     size_t bytes = 0;
-    COARSE_HIP(rocprim::reduce_by_key(nullptr, bytes, keys_sorted, values_in, static_cast<size_t>(nnz),
+    GOSH_TRY_HIP(rocprim::reduce_by_key(nullptr, bytes, keys_sorted, values_in, static_cast<size_t>(nnz),
                                       unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
                                       rocprim::equal_to<uint64_t>(), nullptr),
                "reduce by key (size query)");
     char *temp = nullptr;
     if (int rc = buf.alloc(&temp, bytes, "reduce workspace")) return rc;
-    COARSE_HIP(rocprim::reduce_by_key(temp, bytes, keys_sorted, values_in, static_cast<size_t>(nnz),
+    GOSH_TRY_HIP(rocprim::reduce_by_key(temp, bytes, keys_sorted, values_in, static_cast<size_t>(nnz),
                                       unique_keys, sums, count_dev, rocprim::plus<int64_t>(),
                                       rocprim::equal_to<uint64_t>(), nullptr),
                "reduce by key");
-    COARSE_HIP(hipMemcpy(&n_unique, count_dev, sizeof(n_unique), hipMemcpyDeviceToHost), "copy distinct count");
+    GOSH_TRY_HIP(hipMemcpy(&n_unique, count_dev, sizeof(n_unique), hipMemcpyDeviceToHost), "copy distinct count");
     buf.release(temp);
     return GOSH_OK;
   };
@@ -802,7 +796,7 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
   // entries inside clusters collapse into one sentinel key, the largest: drop it
   if (n_unique > 0) {
     uint64_t last = 0;
-    COARSE_HIP(hipMemcpy(&last, unique_keys + (n_unique - 1), 8, hipMemcpyDeviceToHost), "copy last key");
+    GOSH_TRY_HIP(hipMemcpy(&last, unique_keys + (n_unique - 1), 8, hipMemcpyDeviceToHost), "copy last key");
     if (last == sentinel) --n_unique;
   }
   const int64_t nnz_coarse = static_cast<int64_t>(n_unique);
@@ -817,7 +811,7 @@ int device_rebuild(DeviceCoarsener *dc, const DeviceLevel &fine, int64_t n_coars
                        nnz_coarse, nc, coarse.adj, coarse.mult);
     if (int rc = gosh::check_launch("columns_kernel")) return rc;
   }
-  COARSE_HIP(hipDeviceSynchronize(), "coarse CSR");
+  GOSH_TRY_HIP(hipDeviceSynchronize(), "coarse CSR");
   return GOSH_OK;
 }
 

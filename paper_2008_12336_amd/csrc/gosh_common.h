@@ -29,6 +29,17 @@ inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 // Turns a failed launch into GOSH_EHIP.
 int check_launch(const char *kernel);
 
+// Records the failure of a HIP call for gosh_last_error() and returns its status:
+// GOSH_ENOMEM when device or pinned memory ran out, GOSH_EHIP otherwise.
+int hip_fail(hipError_t e, const char *what);
+
+// Returns from the enclosing function with that status if the call fails.
+#define GOSH_TRY_HIP(call, what)                                 \
+  do {                                                           \
+    hipError_t e_ = (call);                                      \
+    if (e_ != hipSuccess) return gosh::hip_fail(e_, what);       \
+  } while (0)
+
 // Tuning / experiment overrides, read once from the environment.
 //   GOSH_ROW_POLICY=0      plain 128-bit row accesses also in the concurrent kernels
 //                          (coherent inside one XCD only)

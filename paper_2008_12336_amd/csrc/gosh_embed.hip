@@ -68,12 +68,6 @@ double ms_since(std::chrono::steady_clock::time_point t0) {
   return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
 }
 
-#define GOSH_HIP(call, what)                                                           \
-  do {                                                                                 \
-    hipError_t e_ = (call);                                                            \
-    if (e_ != hipSuccess) return gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_)); \
-  } while (0)
-
 size_t level_bytes(const gosh_csr &g, int32_t d) {
   return static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4) + static_cast<size_t>(g.nnz) * 4 +
          static_cast<size_t>(g.n) * d * 4;
@@ -127,13 +121,13 @@ class MultilevelRun {
     G.resize(static_cast<size_t>(D));
     for (int i = 0; i < D; ++i)
       if (int rc = gosh::hierarchy_shape(h, i, &G[static_cast<size_t>(i)])) return rc;
-    GOSH_HIP(hipGetDevice(&current_device), "hipGetDevice");
+    GOSH_TRY_HIP(hipGetDevice(&current_device), "hipGetDevice");
     if (M0_dev != nullptr && !fits(0))
       return gosh::fail(GOSH_EBUDGET,
                         "level 0 needs %zu bytes on the device, budget is %llu: use gosh_embed_host",
                         level_bytes(G[0], d), (unsigned long long)pl.budget);
-    GOSH_HIP(hipEventCreate(&ev0), "hipEventCreate");
-    GOSH_HIP(hipEventCreate(&ev1), "hipEventCreate");
+    GOSH_TRY_HIP(hipEventCreate(&ev0), "hipEventCreate");
+    GOSH_TRY_HIP(hipEventCreate(&ev1), "hipEventCreate");
 
     for (int i = D - 1; i >= 0; --i) {
       const gosh_csr &g = G[static_cast<size_t>(i)];
@@ -156,9 +150,9 @@ class MultilevelRun {
     }
     // Deliver M_0 where the caller wants it.
     if (M0_host && cur_dev) {
-      GOSH_HIP(hipMemcpyAsync(M0_host, cur_dev, static_cast<size_t>(G[0].n) * d * 4, hipMemcpyDeviceToHost, st),
+      GOSH_TRY_HIP(hipMemcpyAsync(M0_host, cur_dev, static_cast<size_t>(G[0].n) * d * 4, hipMemcpyDeviceToHost, st),
                "download M_0");
-      GOSH_HIP(hipStreamSynchronize(st), "download M_0");
+      GOSH_TRY_HIP(hipStreamSynchronize(st), "download M_0");
     }
     return GOSH_OK;
   }
@@ -213,10 +207,10 @@ class MultilevelRun {
       const int64_t cnt = std::min(rows, g.n - lo);
       if (int rc = gosh::init_rows(static_cast<float *>(slice.ptr), lo, cnt, d, pl.seed, static_cast<uint32_t>(i), st))
         return rc;
-      GOSH_HIP(hipMemcpyAsync(cur_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4, hipMemcpyDeviceToHost,
+      GOSH_TRY_HIP(hipMemcpyAsync(cur_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4, hipMemcpyDeviceToHost,
                               st),
                "copy initial rows");
-      GOSH_HIP(hipStreamSynchronize(st), "initialise on host");
+      GOSH_TRY_HIP(hipStreamSynchronize(st), "initialise on host");
     }
     return GOSH_OK;
   }
@@ -237,26 +231,26 @@ class MultilevelRun {
       const size_t adj_bytes = static_cast<size_t>(g.nnz) * 4;
       if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
       if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
-      GOSH_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
+      GOSH_TRY_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
       if (adj_bytes)
-        GOSH_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
-      GOSH_HIP(hipStreamSynchronize(st), "upload graph");
+        GOSH_TRY_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
+      GOSH_TRY_HIP(hipStreamSynchronize(st), "upload graph");
       dev = g;
       dev.xadj = xadj_dev.ptr;
       dev.adj = static_cast<const int32_t *>(adj_dev.ptr);
     }
     ls.upload_ms = ms_since(t0);
-    GOSH_HIP(hipEventRecord(ev0, st), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(ev0, st), "hipEventRecord");
     for (int64_t j = 0; j < ls.epochs; ++j) {
       const float lr = gosh_lr(pl.lr0, j, ls.epochs);
       if (int rc = gosh_train_epoch(&dev, cur_dev, d, pl.k_neg, lr, pl.seed, static_cast<uint32_t>(j),
                                     static_cast<uint32_t>(i), pl.flags, st))
         return rc;
     }
-    GOSH_HIP(hipEventRecord(ev1, st), "hipEventRecord");
-    GOSH_HIP(hipEventSynchronize(ev1), "train level");
+    GOSH_TRY_HIP(hipEventRecord(ev1, st), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventSynchronize(ev1), "train level");
     float ms = 0.f;
-    GOSH_HIP(hipEventElapsedTime(&ms, ev0, ev1), "hipEventElapsedTime");
+    GOSH_TRY_HIP(hipEventElapsedTime(&ms, ev0, ev1), "hipEventElapsedTime");
     ls.train_ms = ms;
     return GOSH_OK;
   }
@@ -317,7 +311,7 @@ class MultilevelRun {
       const size_t smallest_slice = 64 * (static_cast<size_t>(d) * 4 + 4);
       if (pl.budget == 0 || mat_bytes + smallest_slice <= pl.budget) {
         if (int rc = src_visit.alloc(mat_bytes, "coarse embedding (projection)")) return rc;
-        GOSH_HIP(hipMemcpyAsync(src_visit.ptr, cur_host, mat_bytes, hipMemcpyHostToDevice, st),
+        GOSH_TRY_HIP(hipMemcpyAsync(src_visit.ptr, cur_host, mat_bytes, hipMemcpyHostToDevice, st),
                  "upload coarse embedding");
         src_dev = static_cast<const float *>(src_visit.ptr);
       }
@@ -327,12 +321,12 @@ class MultilevelRun {
       const int32_t *map_on_device = map_dev_resident;
       if (map_on_device == nullptr) {
         if (int rc = map_dev.alloc(static_cast<size_t>(n_fine) * 4, "map")) return rc;
-        GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host, static_cast<size_t>(n_fine) * 4, hipMemcpyHostToDevice, st),
+        GOSH_TRY_HIP(hipMemcpyAsync(map_dev.ptr, map_host, static_cast<size_t>(n_fine) * 4, hipMemcpyHostToDevice, st),
                  "copy map");
         map_on_device = static_cast<const int32_t *>(map_dev.ptr);
       }
       if (int rc = gosh_project(src_dev, g.n, map_on_device, n_fine, d, next_dev, st)) return rc;
-      GOSH_HIP(hipStreamSynchronize(st), "project");
+      GOSH_TRY_HIP(hipStreamSynchronize(st), "project");
     } else if (src_dev && next_host) {
       // project slice by slice through a device staging buffer
       int64_t rows = 0;
@@ -346,13 +340,13 @@ class MultilevelRun {
         const int32_t *map_slice =
             map_dev_resident ? map_dev_resident + lo : static_cast<const int32_t *>(map_dev.ptr);
         if (map_dev_resident == nullptr)
-          GOSH_HIP(hipMemcpyAsync(map_dev.ptr, map_host + lo, static_cast<size_t>(cnt) * 4, hipMemcpyHostToDevice, st),
+          GOSH_TRY_HIP(hipMemcpyAsync(map_dev.ptr, map_host + lo, static_cast<size_t>(cnt) * 4, hipMemcpyHostToDevice, st),
                    "copy map slice");
         if (int rc = gosh_project(src_dev, g.n, map_slice, cnt, d, static_cast<float *>(slice.ptr), st)) return rc;
-        GOSH_HIP(hipMemcpyAsync(next_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4,
+        GOSH_TRY_HIP(hipMemcpyAsync(next_host + lo * d, slice.ptr, static_cast<size_t>(cnt) * d * 4,
                                 hipMemcpyDeviceToHost, st),
                  "copy projected slice");
-        GOSH_HIP(hipStreamSynchronize(st), "project slice");
+        GOSH_TRY_HIP(hipStreamSynchronize(st), "project slice");
       }
     } else {
       // the coarse matrix is on the host and too large to visit the device: gather its
@@ -374,8 +368,8 @@ class MultilevelRun {
       for (int64_t v = 0; v < n_fine; ++v)
         std::memcpy(target + v * row_len, coarse + static_cast<int64_t>(map_host[v]) * row_len, row_bytes);
       if (next_dev) {
-        GOSH_HIP(hipMemcpyAsync(next_dev, target, fine_bytes, hipMemcpyHostToDevice, st), "upload");
-        GOSH_HIP(hipStreamSynchronize(st), "upload projected level");
+        GOSH_TRY_HIP(hipMemcpyAsync(next_dev, target, fine_bytes, hipMemcpyHostToDevice, st), "upload");
+        GOSH_TRY_HIP(hipStreamSynchronize(st), "upload projected level");
       }
     }
     ls.project_ms = ms_since(t0);
@@ -437,7 +431,7 @@ int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t e
   const bool measure = device_budget_bytes == 0;
   if (measure) {
     size_t free_bytes = 0, total_bytes = 0;
-    GOSH_HIP(hipMemGetInfo(&free_bytes, &total_bytes), "hipMemGetInfo");
+    GOSH_TRY_HIP(hipMemGetInfo(&free_bytes, &total_bytes), "hipMemGetInfo");
     device_budget_bytes = free_bytes - free_bytes / 16;
     if (device_budget_bytes == 0) return gosh::fail(GOSH_ENOMEM, "the device has no free memory");
   }

@@ -73,6 +73,12 @@ int check_device_csr(const gosh_csr *g) {
   return GOSH_OK;
 }
 
+int hip_fail(hipError_t e, const char *what) {
+  (void)hipGetLastError();  // the runtime keeps the error until it is read
+  const int code = (e == hipErrorOutOfMemory || e == hipErrorMemoryAllocation) ? GOSH_ENOMEM : GOSH_EHIP;
+  return fail(code, "%s: %s", what, hipGetErrorString(e));
+}
+
 int check_launch(const char *kernel) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(GOSH_EHIP, "%s: %s", kernel, hipGetErrorString(e));

@@ -206,7 +206,7 @@ void pair_order_blocked(int32_t K, int32_t R, std::vector<int32_t> &a, std::vect
   do {                                                                                 \
     hipError_t e_ = (call);                                                            \
     if (e_ != hipSuccess) {                                                            \
-      rc = gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_));               \
+      rc = gosh::hip_fail(e_, what);                                                   \
       goto done;                                                                       \
     }                                                                                  \
   } while (0)
@@ -234,12 +234,6 @@ int check_parts_args(const gosh_csr *g, const float *M, int32_t d, int32_t k_neg
 }
 
 constexpr int32_t kMaxParts = 4096;
-
-#define ROT_HIP(call, what)                                                                         \
-  do {                                                                                              \
-    hipError_t e_ = (call);                                                                         \
-    if (e_ != hipSuccess) return gosh::fail(GOSH_EHIP, "%s: %s", what, hipGetErrorString(e_));      \
-  } while (0)
 
 // What a call of gosh_train_parts is asked to do, after planning.
 struct RotationPlan {
@@ -324,21 +318,21 @@ class Rotation {
     k_begin.assign(kTimers, nullptr);
     k_end.assign(kTimers, nullptr);
     k_pending.assign(kTimers, 0);
-    ROT_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
-    ROT_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
-    ROT_HIP(hipStreamCreateWithFlags(&copy_out, hipStreamNonBlocking), "hipStreamCreate");
+    GOSH_TRY_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
+    GOSH_TRY_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
+    GOSH_TRY_HIP(hipStreamCreateWithFlags(&copy_out, hipStreamNonBlocking), "hipStreamCreate");
     for (int s = 0; s < P; ++s)
-      ROT_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * pl.d * 4), "hipMalloc part slot");
-    for (int s = 0; s < S; ++s) ROT_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
+      GOSH_TRY_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * pl.d * 4), "hipMalloc part slot");
+    for (int s = 0; s < S; ++s) GOSH_TRY_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
     for (int s = 0; s < NS && !graph_on_device; ++s)
-      ROT_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
+      GOSH_TRY_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
               "hipHostMalloc staging");
     for (auto *events : {&chunk_flushed, &slot_ready, &slot_used, &pool_ready, &pool_used, &staging_done})
-      for (hipEvent_t &e : *events) ROT_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
-    ROT_HIP(hipEventCreateWithFlags(&arrived, hipEventDisableTiming), "hipEventCreate");
+      for (hipEvent_t &e : *events) GOSH_TRY_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+    GOSH_TRY_HIP(hipEventCreateWithFlags(&arrived, hipEventDisableTiming), "hipEventCreate");
     for (int t = 0; t < kTimers; ++t) {
-      ROT_HIP(hipEventCreate(&k_begin[t]), "hipEventCreate");
-      ROT_HIP(hipEventCreate(&k_end[t]), "hipEventCreate");
+      GOSH_TRY_HIP(hipEventCreate(&k_begin[t]), "hipEventCreate");
+      GOSH_TRY_HIP(hipEventCreate(&k_end[t]), "hipEventCreate");
     }
     if (int rc = build_hot_set()) return rc;
     if (!graph_on_device) sampler = std::thread([this] { sampler_loop(); });
@@ -354,7 +348,7 @@ class Rotation {
       // 1. the two parts of this visit (nothing is running that they could disturb: the
       //    copy stream waits for the last kernel of any slot it overwrites)
       keep.clear();
-      if (ensure_parts(vi, keep) == kError) return GOSH_EHIP;
+      if (ensure_parts(vi, keep) == kError) return error;
       const int sa = slot_of(v.a), sb = slot_of(v.b);
       if (sa < 0 || sb < 0) return gosh::fail(GOSH_EHIP, "internal: part not resident");
       // 2. the pool of this visit
@@ -369,16 +363,16 @@ class Rotation {
       keep.assign({v.a, v.b});
       int got = kPlaced;
       for (int64_t ahead = 1; ahead <= max_ahead && got == kPlaced; ++ahead) got = ensure_parts(vi + ahead, keep);
-      if (got == kError) return GOSH_EHIP;
+      if (got == kError) return error;
       // 5. keep the host from running ahead
       if (graph_on_device) {
         // it continues once the parts of this visit have arrived, as it does with a host
         // sampler (with several swaps queued at once the copies of a swap took four times
         // as long)
-        ROT_HIP(hipEventSynchronize(arrived), "hipEventSynchronize");
+        GOSH_TRY_HIP(hipEventSynchronize(arrived), "hipEventSynchronize");
       } else {
         // hand the staging buffer back to the sampler once its upload is done
-        ROT_HIP(hipEventSynchronize(staging_done[vi % NS]), "hipEventSynchronize");
+        GOSH_TRY_HIP(hipEventSynchronize(staging_done[vi % NS]), "hipEventSynchronize");
         {
           std::lock_guard<std::mutex> lock(mu);
           released = vi + 1;
@@ -433,6 +427,7 @@ class Rotation {
   std::condition_variable cv;
   int64_t filled = 0;    // pools produced so far (visit indices [0, filled))
   int64_t released = 0;  // staging buffers given back (visit indices [0, released))
+  int error = GOSH_OK;  // status behind a kError
   bool stop = false;
   double sampler_busy_ms = 0;  // written by the sampler thread only, read after it has joined
   std::thread sampler;
@@ -460,7 +455,7 @@ class Rotation {
       if (mode == gosh::kHotBitmap) {
         const int64_t min_degree = pl.g->nnz / (gosh::tuning().hot_inv_eps * in_flight * pl.B) + 1;
         const int64_t words = (n + 63) / 64;
-        ROT_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
+        GOSH_TRY_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
         if (graph_on_device) {
           const int blocks = static_cast<int>(std::min<int64_t>((words + 255) / 256, 65536));
           if (pl.g->xadj_is64)
@@ -472,7 +467,7 @@ class Rotation {
                                static_cast<const int32_t *>(pl.g->xadj), n, min_degree,
                                reinterpret_cast<uint64_t *>(hot_bits_dev));
           if (int rc = gosh::check_launch("degree_bitmap_kernel")) return rc;
-          ROT_HIP(hipDeviceSynchronize(), "hot bitmap");
+          GOSH_TRY_HIP(hipDeviceSynchronize(), "hot bitmap");
         } else {
           const HostCsr csr{pl.g};
           std::vector<uint64_t> bits(static_cast<size_t>(words), 0);
@@ -485,7 +480,7 @@ class Rotation {
             }
             bits[static_cast<size_t>(w64)] = word;
           }
-          ROT_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
+          GOSH_TRY_HIP(hipMemcpy(hot_bits_dev, bits.data(), bits.size() * 8, hipMemcpyHostToDevice), "copy bitmap");
         }
         hot.bits = hot_bits_dev;
       }
@@ -493,8 +488,8 @@ class Rotation {
     }
     if (hot.bits == nullptr) {
       // the kernel reads word 0 of the bitmap unconditionally
-      ROT_HIP(hipMalloc(&hot_bits_dev, 64), "hipMalloc hot bitmap");
-      ROT_HIP(hipMemset(hot_bits_dev, 0, 64), "hipMemset hot bitmap");
+      GOSH_TRY_HIP(hipMalloc(&hot_bits_dev, 64), "hipMalloc hot bitmap");
+      GOSH_TRY_HIP(hipMemset(hot_bits_dev, 0, 64), "hipMemset hot bitmap");
       hot.bits = hot_bits_dev;
     }
     return GOSH_OK;
@@ -557,7 +552,7 @@ class Rotation {
       if (nu > farthest) { farthest = nu; victim = s; }
     }
     if (victim < 0) return kNoSlot;
-    if (swap_in(p, victim) != GOSH_OK) return kError;
+    if ((error = swap_in(p, victim)) != GOSH_OK) return kError;
     slot_part[victim] = p;
     return kPlaced;
   }
@@ -580,31 +575,31 @@ class Rotation {
       piece = std::max<size_t>((piece + 255) / 256 * 256, size_t(8) << 20);
       // after the last kernel that used the slot, and after the upload that filled it (a
       // part brought in ahead of time may leave again before any kernel has used it)
-      ROT_HIP(hipStreamWaitEvent(copy_out, slot_used[victim], 0), "hipStreamWaitEvent");
-      ROT_HIP(hipStreamWaitEvent(copy_out, slot_ready[victim], 0), "hipStreamWaitEvent");
+      GOSH_TRY_HIP(hipStreamWaitEvent(copy_out, slot_used[victim], 0), "hipStreamWaitEvent");
+      GOSH_TRY_HIP(hipStreamWaitEvent(copy_out, slot_ready[victim], 0), "hipStreamWaitEvent");
       char *slot_bytes = reinterpret_cast<char *>(slot[victim]);
       int c = 0;
       for (size_t off = 0; off < longest; off += piece, ++c) {
         hipEvent_t flushed = chunk_flushed[static_cast<size_t>(victim) * kSwapChunks + c];
         if (off < old_bytes) {
-          ROT_HIP(hipMemcpyAsync(reinterpret_cast<char *>(old_host) + off, slot_bytes + off,
+          GOSH_TRY_HIP(hipMemcpyAsync(reinterpret_cast<char *>(old_host) + off, slot_bytes + off,
                                  std::min(piece, old_bytes - off), hipMemcpyDeviceToHost, copy_out),
                   "part write-back");
-          ROT_HIP(hipEventRecord(flushed, copy_out), "hipEventRecord");
-          ROT_HIP(hipStreamWaitEvent(copy, flushed, 0), "hipStreamWaitEvent");
+          GOSH_TRY_HIP(hipEventRecord(flushed, copy_out), "hipEventRecord");
+          GOSH_TRY_HIP(hipStreamWaitEvent(copy, flushed, 0), "hipStreamWaitEvent");
         }
         if (off < new_bytes)
-          ROT_HIP(hipMemcpyAsync(slot_bytes + off, reinterpret_cast<const char *>(new_host) + off,
+          GOSH_TRY_HIP(hipMemcpyAsync(slot_bytes + off, reinterpret_cast<const char *>(new_host) + off,
                                  std::min(piece, new_bytes - off), hipMemcpyHostToDevice, copy),
                   "part upload");
       }
       st.bytes_d2h += old_bytes;
     } else {
-      ROT_HIP(hipStreamWaitEvent(copy, slot_used[victim], 0), "hipStreamWaitEvent");
-      ROT_HIP(hipMemcpyAsync(slot[victim], new_host, new_bytes, hipMemcpyHostToDevice, copy), "part upload");
+      GOSH_TRY_HIP(hipStreamWaitEvent(copy, slot_used[victim], 0), "hipStreamWaitEvent");
+      GOSH_TRY_HIP(hipMemcpyAsync(slot[victim], new_host, new_bytes, hipMemcpyHostToDevice, copy), "part upload");
     }
     st.bytes_h2d += new_bytes;
-    ROT_HIP(hipEventRecord(slot_ready[victim], copy), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(slot_ready[victim], copy), "hipEventRecord");
     return GOSH_OK;
   }
 
@@ -649,9 +644,9 @@ class Rotation {
       fill(L.lo(v.b), L.size(v.b), L.lo(v.a), L.lo(v.a) + L.size(v.a), 1,
            dpool[ps] + static_cast<size_t>(L.part_rows) * pl.B);
     if (int rc = gosh::check_launch("fill_pool_kernel")) return rc;
-    ROT_HIP(hipEventRecord(pool_ready[ps], compute), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(pool_ready[ps], compute), "hipEventRecord");
     // marks, on the inbound stream, the point up to which this visit's parts are in
-    ROT_HIP(hipEventRecord(arrived, copy), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(arrived, copy), "hipEventRecord");
     return GOSH_OK;
   }
 
@@ -665,28 +660,28 @@ class Rotation {
       st.sampler_wait_ms +=
           std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_wait).count();
     }
-    ROT_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
+    GOSH_TRY_HIP(hipStreamWaitEvent(copy, pool_used[ps], 0), "hipStreamWaitEvent");
     const size_t side0 = static_cast<size_t>(L.size(v.a)) * pl.B * 4;
-    ROT_HIP(hipMemcpyAsync(dpool[ps], staging[hs], side0, hipMemcpyHostToDevice, copy), "pool upload");
+    GOSH_TRY_HIP(hipMemcpyAsync(dpool[ps], staging[hs], side0, hipMemcpyHostToDevice, copy), "pool upload");
     st.bytes_h2d += side0;
     if (v.a != v.b) {
       const size_t side1 = static_cast<size_t>(L.size(v.b)) * pl.B * 4;
-      ROT_HIP(hipMemcpyAsync(dpool[ps] + static_cast<size_t>(L.part_rows) * pl.B,
+      GOSH_TRY_HIP(hipMemcpyAsync(dpool[ps] + static_cast<size_t>(L.part_rows) * pl.B,
                              staging[hs] + static_cast<size_t>(L.part_rows) * pl.B, side1, hipMemcpyHostToDevice,
                              copy),
               "pool upload");
       st.bytes_h2d += side1;
     }
-    ROT_HIP(hipEventRecord(pool_ready[ps], copy), "hipEventRecord");
-    ROT_HIP(hipEventRecord(staging_done[hs], copy), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(pool_ready[ps], copy), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(staging_done[hs], copy), "hipEventRecord");
     return GOSH_OK;
   }
 
   int launch_pair(int64_t vi, const Visit &v, int sa, int sb) {
     const int ps = static_cast<int>(vi % S);
-    ROT_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
-    ROT_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
-    ROT_HIP(hipStreamWaitEvent(compute, pool_ready[ps], 0), "hipStreamWaitEvent");
+    GOSH_TRY_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
+    GOSH_TRY_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
+    GOSH_TRY_HIP(hipStreamWaitEvent(compute, pool_ready[ps], 0), "hipStreamWaitEvent");
     PairWork w{};
     w.a_lo = L.lo(v.a); w.a_n = L.size(v.a); w.b_lo = L.lo(v.b); w.b_n = L.size(v.b);
     w.a_rows = slot[sa]; w.b_rows = slot[sb];
@@ -703,21 +698,21 @@ class Rotation {
     const int timer = static_cast<int>(vi % kTimers);
     if (k_pending[timer]) {
       float ms = 0.f;
-      ROT_HIP(hipEventSynchronize(k_end[timer]), "hipEventSynchronize");
-      ROT_HIP(hipEventElapsedTime(&ms, k_begin[timer], k_end[timer]), "hipEventElapsedTime");
+      GOSH_TRY_HIP(hipEventSynchronize(k_end[timer]), "hipEventSynchronize");
+      GOSH_TRY_HIP(hipEventElapsedTime(&ms, k_begin[timer], k_end[timer]), "hipEventElapsedTime");
       st.kernel_ms += ms;
       k_pending[timer] = 0;
     }
-    ROT_HIP(hipEventRecord(k_begin[timer], compute), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(k_begin[timer], compute), "hipEventRecord");
     gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, gosh::tuning().row_policy == 0,
                                         gosh::tuning().max_waves, compute);
     if (int rc = gosh::check_launch("sgd_kernel (pair)")) return rc;
-    ROT_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
     k_pending[timer] = 1;
     st.updates += w.count() * samples;
-    ROT_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
-    ROT_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
-    ROT_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
+    GOSH_TRY_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
     return GOSH_OK;
   }
 
@@ -727,15 +722,15 @@ class Rotation {
       if (slot_part[s] < 0) continue;
       const int32_t old = slot_part[s];
       const size_t bytes = static_cast<size_t>(L.size(old)) * pl.d * 4;
-      ROT_HIP(hipStreamWaitEvent(copy_out, slot_used[s], 0), "hipStreamWaitEvent");
-      ROT_HIP(hipMemcpyAsync(pl.M_host + static_cast<int64_t>(L.lo(old)) * pl.d, slot[s], bytes,
+      GOSH_TRY_HIP(hipStreamWaitEvent(copy_out, slot_used[s], 0), "hipStreamWaitEvent");
+      GOSH_TRY_HIP(hipMemcpyAsync(pl.M_host + static_cast<int64_t>(L.lo(old)) * pl.d, slot[s], bytes,
                              hipMemcpyDeviceToHost, copy_out),
               "part write-back");
       st.bytes_d2h += bytes;
     }
-    ROT_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
-    ROT_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
-    ROT_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
+    GOSH_TRY_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
+    GOSH_TRY_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
+    GOSH_TRY_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
     for (int t = 0; t < kTimers; ++t) {
       float ms = 0.f;
       if (k_pending[t] && hipEventElapsedTime(&ms, k_begin[t], k_end[t]) == hipSuccess) st.kernel_ms += ms;

@@ -246,3 +246,23 @@ def test_malformed_graph_keeps_the_rotation_inside_its_slots(offsets64):
                 got[where] = M.numpy().copy()
     assert np.array_equal(got["host"], got["device"])
     assert not np.array_equal(got["host"], M0)
+
+
+def test_a_slot_larger_than_the_device_is_an_allocation_failure():
+    """One part of 2^28 rows of 512 floats is 550 GB: the first slot cannot be allocated, the
+    call reports GOSH_ENOMEM (not a generic runtime failure), releases what it had and leaves
+    the device usable.  No kernel runs and the matrix pointer is never followed."""
+    import ctypes as C
+
+    n, d = 1 << 28, 512
+    xadj = torch.zeros(n + 1, dtype=torch.int32)  # an edgeless graph, untouched pages
+    adj = torch.zeros(1, dtype=torch.int32)
+    g = G.gosh_csr(n, 0, xadj.data_ptr(), adj.data_ptr(), 0)
+    M = torch.zeros(16, d, dtype=torch.float32).pin_memory()
+    rc = G.lib().gosh_train_parts(C.byref(g), M.data_ptr(), d, 3, 1, C.c_float(0.1), 1, 0, 0, 3, 4, 5, 1, 0, None)
+    assert rc == -2, (rc, G.gosh_last_error())
+    assert "part slot" in G.gosh_last_error()
+    c = graph(500, 2000, 1, "er")
+    M = torch.from_numpy(O.init_embedding(500, 32, 1, 0)).pin_memory()
+    G.gosh_train_parts(500, c.xadj, c.adj, M, 3, 10, 0.05, 1, force_K=3)
+    assert np.isfinite(M.numpy()).all()
