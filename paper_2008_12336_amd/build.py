@@ -9,6 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgosh.so")
+EXAMPLE_SRC = os.path.join(HERE, "examples", "embed_example.cpp")
+EXAMPLE = os.path.join(HERE, "examples", "embed_example")
 
 SOURCES = ["gosh_host.cpp", "gosh_coarsen.cpp", "gosh_sampler.cpp", "gosh_coarsen_gpu.hip", "gosh_train.hip", "gosh_embed.hip", "gosh_parts.hip"]
 
@@ -42,7 +44,20 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+    build_example(verbose)
     return LIB
+
+
+def build_example(verbose: bool = False) -> str:
+    """The C++ program that uses the library through include/gosh.h alone."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I" + os.path.join(ROOT, "include"), EXAMPLE_SRC, "-L" + HERE, "-lgosh",
+           "-Wl,-rpath,$ORIGIN/..", "-o", EXAMPLE]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return EXAMPLE
 
 
 if __name__ == "__main__":

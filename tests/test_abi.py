@@ -113,3 +113,19 @@ def test_header_is_plain_c():
                      "gosh_csr g; (void)s; (void)p; (void)g; return gosh_hierarchy_levels(0); }\n")
         subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
                         "-I", os.path.join(root, "include"), src], check=True)
+
+
+def test_cxx_example_links_against_the_header_and_runs_its_host_part():
+    """paper_2008_12336_amd/examples/embed_example.cpp uses the library through include/gosh.h
+    alone; its --host-only mode (validate, coarsen on the host, epoch split) needs no GPU."""
+    import subprocess
+
+    from paper_2008_12336_amd import build as B
+
+    exe = B.EXAMPLE if os.path.exists(B.EXAMPLE) else B.build_example()
+    out = subprocess.run([exe, "--host-only"], capture_output=True, text=True, check=True).stdout
+    lines = out.strip().splitlines()
+    assert lines[0].startswith("hierarchy: ") and " 4000/" in lines[0]
+    levels = int(lines[0].split()[1])
+    epochs = [int(x) for x in lines[1].split(":")[1].split()]
+    assert len(epochs) == levels and sum(epochs) == 600

@@ -150,3 +150,18 @@ def test_budgeted_vcycle_with_blocked_order_matches_oracle():
     say(f"[budget blocked] modes {modes} err {err:.2e}")
     assert err <= 1e-5
     assert rel_err(plain, want) > 1e-4
+
+
+def test_cxx_example_embeds_through_the_c_abi_alone():
+    """The C++ example (no Python, no torch: hipMalloc + include/gosh.h) coarsens on the device,
+    runs Alg. 2 and must find edges scoring higher than random pairs (its exit status)."""
+    import os
+    import subprocess
+
+    from paper_2008_12336_amd import build as B
+
+    assert os.path.exists(B.EXAMPLE), "build the library first (python -c 'import __graft_entry__ as g; g.build()')"
+    run = subprocess.run([B.EXAMPLE], capture_output=True, text=True, timeout=100)
+    print(run.stdout, run.stderr, flush=True)
+    assert run.returncode == 0
+    assert "mean dot over edges" in run.stdout
