@@ -329,7 +329,8 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
  * what gosh_embed_host passes for a level of a device-built hierarchy): the pools of
  * positives are then filled by a kernel on the device, with the same values, and no host
  * sampler runs -- on this hardware the graph usually fits the device where the matrix
- * does not.  The graph is outside device_budget_bytes either way.
+ * does not (one pool is enough then: S_gpu = 1 leaves more of the budget to the parts).
+ * The graph is outside device_budget_bytes either way.
  * M_host: host matrix n x d, updated in place; pinned memory makes the
  * transfers asynchronous.  device_budget_bytes: cap for slots + pools + bitmap (0 only
  * together with force_K > 0).  P_gpu >= 2 (paper: 3), S_gpu >= 1 (paper: 4), B >= 1
