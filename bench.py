@@ -154,27 +154,38 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     release_generator_memory(torch)
     M_dev = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     G.gosh_init_embedding(M_dev, args.seed, 0)
-    M_host = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
-    M_host.copy_(M_dev)
-    del M_dev
-    release_generator_memory(torch)
-    print("[bench] matrix on the pinned host", file=sys.stderr, flush=True)
-    if "budget" in w and args.log2n is None:
-        budget = int(w["budget"])
+    if args.matrix == "device":
+        # every part trained where it is: the pair order and sampling rule of Alg. 5 without
+        # its copies (the budget then only covers the pools)
+        M_host, budget = M_dev, 0
+        K = args.parts if args.parts > 0 else 16
+        st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, B * K, w["lr0"], args.seed, S_gpu=args.s_gpu,
+                                B=B, force_K=K, flags=args.flags)
+        torch.cuda.synchronize()
     else:
-        budget = int(n * d * 4 / args.budget_ratio)
-    print(f"[bench] parts: n={n} budget={budget}", file=sys.stderr, flush=True)
-    plan = G.gosh_parts_plan(n, d, 1, budget, args.p_gpu, args.s_gpu, B)
-    epochs = B * plan["K"]  # exactly one rotation
-    st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, epochs, w["lr0"], args.seed,
-                            device_budget_bytes=budget, P_gpu=args.p_gpu, S_gpu=args.s_gpu, B=B,
-                            flags=args.flags)
+        M_host = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
+        M_host.copy_(M_dev)
+        del M_dev
+        release_generator_memory(torch)
+        print("[bench] matrix on the pinned host", file=sys.stderr, flush=True)
+        if "budget" in w and args.log2n is None:
+            budget = int(w["budget"])
+        else:
+            budget = int(n * d * 4 / args.budget_ratio)
+        print(f"[bench] parts: n={n} budget={budget}", file=sys.stderr, flush=True)
+        plan = G.gosh_parts_plan(n, d, 1, budget, args.p_gpu, args.s_gpu, B)
+        epochs = B * plan["K"]  # exactly one rotation
+        st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, epochs, w["lr0"], args.seed,
+                                device_budget_bytes=budget, P_gpu=args.p_gpu, S_gpu=args.s_gpu, B=B,
+                                flags=args.flags)
     out = {"metric": "training samples/sec and achieved HBM GB/s (% of peak) at d=128, 1 GPU",
            "value": st["updates"] / (st["wall_ms"] / 1e3), "unit": "samples/s", "n_gpus": 1,
            "steps": 1, "warmup": 0, "ms_per_step": st["wall_ms"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": args.workload + "_parts", "desc": w["desc"], "n": n,
-                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "graph": args.graph, "flags": args.flags, "P_gpu": args.p_gpu,
+                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "graph": args.graph, "matrix": args.matrix,
+                      "ms_per_epoch_worth_of_samples": st["wall_ms"] / (B * st["K"] * st["rotations"]),
+                      "flags": args.flags, "P_gpu": args.p_gpu,
                       "S_gpu": args.s_gpu, "device_budget_bytes": budget, "matrix_bytes": n * d * 4,
                       "graph_build_s": t_graph, "finite": bool(torch.isfinite(M_host[::4097]).all()),
                       **st,
@@ -204,6 +215,9 @@ def main() -> int:
                     help="--mode levels: where the coarse graphs are rebuilt")
     ap.add_argument("--graph", default="host", choices=["host", "device"],
                     help="--mode levels with --coarsen device, --mode parts: where G_0 is handed over")
+    ap.add_argument("--matrix", default="host", choices=["host", "device"],
+                    help="--mode parts: where the matrix lives (device: parts trained in place, no copies)")
+    ap.add_argument("--parts", type=int, default=0, help="--mode parts --matrix device: part count (default 16)")
     ap.add_argument("--epochs", type=int, default=40, help="total epochs of --mode levels")
     ap.add_argument("--p-gpu", type=int, default=3, help="--mode parts: device slots for parts")
     ap.add_argument("--s-gpu", type=int, default=4, help="--mode parts: device sample pools")

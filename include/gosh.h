@@ -332,8 +332,15 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
  * does not (one pool is enough then: S_gpu = 1 leaves more of the budget to the parts).
  * The graph is outside device_budget_bytes either way.
  * M_host: host matrix n x d, updated in place; pinned memory makes the
- * transfers asynchronous.  device_budget_bytes: cap for slots + pools + bitmap (0 only
- * together with force_K > 0).  P_gpu >= 2 (paper: 3), S_gpu >= 1 (paper: 4), B >= 1
+ * transfers asynchronous.  A matrix in the current device's memory (detected from the
+ * pointer) is trained where it is: every part is its own slot, nothing is copied, P_gpu
+ * only shapes the blocked pair order, the part count is force_K or else 16, and the budget
+ * covers the pools and the bitmap alone.  What is left of Alg. 5 then is its visiting
+ * order and its sampling rule, which on this hardware make an epoch's worth of samples
+ * 1.2-1.4x cheaper than an epoch of Alg. 3 (a source row is loaded once per B rounds, and
+ * the negatives of a visit fall into one part).
+ * device_budget_bytes: cap for slots + pools + bitmap (0 only together with force_K > 0,
+ * or with a device matrix).  P_gpu >= 2 (paper: 3), S_gpu >= 1 (paper: 4), B >= 1
  * (paper: 5).  force_K > 0 overrides the part count.  flags as for gosh_train_epoch
  * (GOSH_FLAG_SEQUENTIAL: every pair kernel runs on one wavefront, sources in order), plus
  * GOSH_FLAG_BLOCKED_ORDER.

@@ -425,14 +425,13 @@ def gosh_train_parts(n: int, xadj: torch.Tensor, adj: torch.Tensor, M_host: torc
                      k_neg: int, epochs: int, lr0: float, seed: int, level: int = 0,
                      device_budget_bytes: int = 0, P_gpu: int = 3, S_gpu: int = 4, B: int = 5,
                      force_K: int = 0, flags: int = 0):
-    """Train a HOST matrix (ideally pinned) in place with the part-pair rotation.  The graph
-    may be CPU tensors (positives are drawn by a host sampler) or tensors on the current
-    device (positives are drawn there)."""
+    """Train a matrix in place with the part-pair rotation: a HOST matrix (ideally pinned),
+    whose parts rotate through the device, or a matrix on the current device, whose parts are
+    trained where they are.  The graph may be CPU tensors (positives are drawn by a host
+    sampler) or tensors on the current device (positives are drawn there)."""
     if xadj.is_cuda != adj.is_cuda:
         raise TypeError("xadj and adj must live on the same side")
     g = csr_view(n, xadj, adj) if xadj.is_cuda else _host_csr(n, xadj, adj)
-    if M_host.is_cuda:
-        raise TypeError("M_host must be a host tensor (the rotation moves its parts itself)")
     ptr, rows, d = _matrix(M_host, "M_host")
     if rows != n:
         raise ValueError("M_host must have one row per vertex")

@@ -234,22 +234,30 @@ int check_parts_args(const gosh_csr *g, const float *M, int32_t d, int32_t k_neg
 }
 
 constexpr int32_t kMaxParts = 4096;
+// Parts of a matrix that is trained in device memory, unless the caller names a count: with
+// 16 the pair kernels ran fastest on a 2^24-vertex graph (11.3 ms per epoch's worth of
+// samples; 13.2 ms with 2 parts, 11.9 with 32, 22.7 with 64).
+constexpr int32_t kResidentParts = 16;
 
 // What a call of gosh_train_parts is asked to do, after planning.
 struct RotationPlan {
   const gosh_csr *g;  // host or device arrays
-  float *M_host;
+  float *M_host;      // the matrix: on the host, or (matrix_on_device) in device memory
+  bool matrix_on_device;
   int32_t d, k_neg, B;
   float lr0;
   uint64_t seed;
   uint32_t level, flags;
-  int32_t K, P, S;
+  int32_t K, P, S;    // parts, slots (K when the matrix is on the device), pools
+  int32_t order_P;    // the slot count the blocked pair order is laid out for
   int64_t rotations;
 };
 
 // One call of gosh_train_parts: owns the device slots and pools, the three streams, the
 // events that order them and the sampler thread; the destructor waits for everything that
 // is queued, stops the thread and frees it all, on every path.
+// With the matrix in device memory every part is its own slot, in place (P = K): nothing is
+// copied, and what remains of Alg. 5 is its visiting order and its sampling rule.
 class Rotation {
  public:
   explicit Rotation(const RotationPlan &plan)
@@ -261,7 +269,7 @@ class Rotation {
         pool_ints(static_cast<size_t>(2) * L.part_rows * plan.B) {
     // the blocked order keeps all slots but two for a block; the two take turns receiving
     // the streamed parts
-    if (pl.flags & GOSH_FLAG_BLOCKED_ORDER) pair_order_blocked(pl.K, std::max(1, P - 2), pa, pb);
+    if (pl.flags & GOSH_FLAG_BLOCKED_ORDER) pair_order_blocked(pl.K, std::max(1, pl.order_P - 2), pa, pb);
     else pair_order(pl.K, pa, pb);
     npairs = static_cast<int64_t>(pa.size());
     visits = pl.rotations * npairs;
@@ -293,7 +301,8 @@ class Rotation {
       for (hipEvent_t e : *events)
         if (e) (void)hipEventDestroy(e);
     if (arrived) (void)hipEventDestroy(arrived);
-    for (auto p : slot) if (p) (void)hipFree(p);
+    if (!pl.matrix_on_device)
+      for (auto p : slot) if (p) (void)hipFree(p);
     for (auto p : dpool) if (p) (void)hipFree(p);
     for (auto p : staging) if (p) (void)hipHostFree(p);
     if (hot_bits_dev) (void)hipFree(hot_bits_dev);
@@ -309,9 +318,10 @@ class Rotation {
     dpool.assign(S, nullptr);
     staging.assign(NS, nullptr);
     slot_part.assign(P, -1);
-    chunk_flushed.assign(static_cast<size_t>(P) * kSwapChunks, nullptr);
-    slot_ready.assign(P, nullptr);
-    slot_used.assign(P, nullptr);
+    const int moving = pl.matrix_on_device ? 0 : P;  // slots whose content changes
+    chunk_flushed.assign(static_cast<size_t>(moving) * kSwapChunks, nullptr);
+    slot_ready.assign(moving, nullptr);
+    slot_used.assign(moving, nullptr);
     pool_ready.assign(S, nullptr);
     pool_used.assign(S, nullptr);
     staging_done.assign(NS, nullptr);
@@ -321,8 +331,14 @@ class Rotation {
     GOSH_TRY_HIP(hipStreamCreateWithFlags(&compute, hipStreamNonBlocking), "hipStreamCreate");
     GOSH_TRY_HIP(hipStreamCreateWithFlags(&copy, hipStreamNonBlocking), "hipStreamCreate");
     GOSH_TRY_HIP(hipStreamCreateWithFlags(&copy_out, hipStreamNonBlocking), "hipStreamCreate");
-    for (int s = 0; s < P; ++s)
-      GOSH_TRY_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * pl.d * 4), "hipMalloc part slot");
+    for (int s = 0; s < P; ++s) {
+      if (pl.matrix_on_device) {
+        slot[s] = pl.M_host + static_cast<int64_t>(L.lo(s)) * pl.d;
+        slot_part[s] = s;
+      } else {
+        GOSH_TRY_HIP(hipMalloc(&slot[s], static_cast<size_t>(L.part_rows) * pl.d * 4), "hipMalloc part slot");
+      }
+    }
     for (int s = 0; s < S; ++s) GOSH_TRY_HIP(hipMalloc(&dpool[s], pool_ints * 4), "hipMalloc pool");
     for (int s = 0; s < NS && !graph_on_device; ++s)
       GOSH_TRY_HIP(hipHostMalloc(reinterpret_cast<void **>(&staging[s]), pool_ints * 4, hipHostMallocDefault),
@@ -348,7 +364,7 @@ class Rotation {
       // 1. the two parts of this visit (nothing is running that they could disturb: the
       //    copy stream waits for the last kernel of any slot it overwrites)
       keep.clear();
-      if (ensure_parts(vi, keep) == kError) return error;
+      if (!pl.matrix_on_device && ensure_parts(vi, keep) == kError) return error;
       const int sa = slot_of(v.a), sb = slot_of(v.b);
       if (sa < 0 || sb < 0) return gosh::fail(GOSH_EHIP, "internal: part not resident");
       // 2. the pool of this visit
@@ -360,10 +376,12 @@ class Rotation {
       //    the fetch runs as far ahead as slots that none of the visits in between uses can
       //    be found; in the paper's order fetching further ahead evicts parts the next row
       //    would have reused (measured: 376 GB instead of 309 GB per rotation at 5 slots).
-      keep.assign({v.a, v.b});
-      int got = kPlaced;
-      for (int64_t ahead = 1; ahead <= max_ahead && got == kPlaced; ++ahead) got = ensure_parts(vi + ahead, keep);
-      if (got == kError) return error;
+      if (!pl.matrix_on_device) {
+        keep.assign({v.a, v.b});
+        int got = kPlaced;
+        for (int64_t ahead = 1; ahead <= max_ahead && got == kPlaced; ++ahead) got = ensure_parts(vi + ahead, keep);
+        if (got == kError) return error;
+      }
       // 5. keep the host from running ahead
       if (graph_on_device) {
         // it continues once the parts of this visit have arrived, as it does with a host
@@ -532,6 +550,7 @@ class Rotation {
     return visits + npairs;
   }
   int slot_of(int32_t p) const {
+    if (pl.matrix_on_device) return p;
     for (int s = 0; s < P; ++s)
       if (slot_part[s] == p) return s;
     return -1;
@@ -679,8 +698,10 @@ class Rotation {
 
   int launch_pair(int64_t vi, const Visit &v, int sa, int sb) {
     const int ps = static_cast<int>(vi % S);
-    GOSH_TRY_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
-    GOSH_TRY_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
+    if (!pl.matrix_on_device) {
+      GOSH_TRY_HIP(hipStreamWaitEvent(compute, slot_ready[sa], 0), "hipStreamWaitEvent");
+      GOSH_TRY_HIP(hipStreamWaitEvent(compute, slot_ready[sb], 0), "hipStreamWaitEvent");
+    }
     GOSH_TRY_HIP(hipStreamWaitEvent(compute, pool_ready[ps], 0), "hipStreamWaitEvent");
     PairWork w{};
     w.a_lo = L.lo(v.a); w.a_n = L.size(v.a); w.b_lo = L.lo(v.b); w.b_n = L.size(v.b);
@@ -710,15 +731,17 @@ class Rotation {
     GOSH_TRY_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
     k_pending[timer] = 1;
     st.updates += w.count() * samples;
-    GOSH_TRY_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
-    GOSH_TRY_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
+    if (!pl.matrix_on_device) {
+      GOSH_TRY_HIP(hipEventRecord(slot_used[sa], compute), "hipEventRecord");
+      GOSH_TRY_HIP(hipEventRecord(slot_used[sb], compute), "hipEventRecord");
+    }
     GOSH_TRY_HIP(hipEventRecord(pool_used[ps], compute), "hipEventRecord");
     return GOSH_OK;
   }
 
   // Writes every resident part back and waits for all three streams.
   int write_back_all() {
-    for (int s = 0; s < P; ++s) {
+    for (int s = 0; s < P && !pl.matrix_on_device; ++s) {
       if (slot_part[s] < 0) continue;
       const int32_t old = slot_part[s];
       const size_t bytes = static_cast<size_t>(L.size(old)) * pl.d * 4;
@@ -847,21 +870,31 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   int32_t K = 0;
   int64_t rotations = 0;
   uint64_t planned_bytes = 0;
-  if (force_K > 0) {
+  // A matrix in device memory is trained where it is: every part its own slot, no copies.
+  const bool matrix_on_device = gosh::is_device_pointer(M_host);
+  if (matrix_on_device) {
+    if (int rc = gosh::check_device_span(M_host, static_cast<size_t>(n) * d * 4, "M")) return rc;
+    if (force_K > kMaxParts || force_K > n) return gosh::fail(GOSH_EINVAL, "force_K = %d too large", force_K);
+    K = force_K > 0 ? force_K : static_cast<int32_t>(std::min<int64_t>(n, kResidentParts));
+    planned_bytes = device_bytes_for(n, K, d, 0, S_gpu, B);
+    if (device_budget_bytes != 0 && planned_bytes > device_budget_bytes)
+      return gosh::fail(GOSH_EBUDGET, "the pools of K = %d parts need %llu device bytes, budget is %llu", K,
+                        (unsigned long long)planned_bytes, (unsigned long long)device_budget_bytes);
+  } else if (force_K > 0) {
     if (force_K > kMaxParts || force_K > n) return gosh::fail(GOSH_EINVAL, "force_K = %d too large", force_K);
     K = force_K;
-    rotations = std::max<int64_t>(1, (epochs + static_cast<int64_t>(B) * K - 1) / (static_cast<int64_t>(B) * K));
     planned_bytes = device_bytes_for(n, K, d, std::min(P_gpu, K), S_gpu, B);
     if (device_budget_bytes != 0 && planned_bytes > device_budget_bytes)
       return gosh::fail(GOSH_EBUDGET, "K = %d needs %llu device bytes, budget is %llu", K,
                         (unsigned long long)planned_bytes, (unsigned long long)device_budget_bytes);
-  } else if (int rc = gosh_parts_plan(n, d, epochs, device_budget_bytes, P_gpu, S_gpu, B, &K, &rotations,
+  } else if (int rc = gosh_parts_plan(n, d, epochs, device_budget_bytes, P_gpu, S_gpu, B, &K, nullptr,
                                       &planned_bytes)) {
     return rc;
   }
+  rotations = std::max<int64_t>(1, (epochs + static_cast<int64_t>(B) * K - 1) / (static_cast<int64_t>(B) * K));
   const auto wall0 = std::chrono::steady_clock::now();
-  const RotationPlan plan{g_host, M_host, d, k_neg, B, lr0, seed, level, flags, K, std::min(P_gpu, K), S_gpu,
-                          rotations};
+  const RotationPlan plan{g_host, M_host, matrix_on_device, d,     k_neg, B, lr0, seed, level, flags, K,
+                          matrix_on_device ? K : std::min(P_gpu, K), S_gpu, std::min(P_gpu, K), rotations};
   gosh_parts_stats st{};
   int rc = GOSH_OK;
   {

@@ -266,3 +266,37 @@ def test_a_slot_larger_than_the_device_is_an_allocation_failure():
     M = torch.from_numpy(O.init_embedding(500, 32, 1, 0)).pin_memory()
     G.gosh_train_parts(500, c.xadj, c.adj, M, 3, 10, 0.05, 1, force_K=3)
     assert np.isfinite(M.numpy()).all()
+
+
+@pytest.mark.parametrize("graph_on_device", [False, True])
+@pytest.mark.parametrize("order_flag", [0, G.GOSH_FLAG_BLOCKED_ORDER])
+def test_matrix_in_device_memory_is_trained_in_place(graph_on_device, order_flag):
+    """With the matrix on the device every part is its own slot and nothing is copied: the
+    sequential rotation is bit for bit the one of the host-matrix path (same kernels, same
+    order, same pools) and within the bar of the oracle's; the part count defaults to 16."""
+    n, d, K, P, S, B, k, epochs = 1500, 32, 6, 4, 2, 3, 3, 40
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 5 * n, 9))
+    xadj = c.xadj.to(DEV) if graph_on_device else c.xadj
+    adj = c.adj.to(DEV) if graph_on_device else c.adj
+    M0 = (O.init_embedding(n, d, 3, 0).astype(np.float64) * d * 0.8).astype(np.float32)
+    want = M0.copy()
+    O.train_parts(c.xadj.numpy(), c.adj.numpy(), want, k, epochs, 0.1, 7, 2, K, B,
+                  block=O.blocked_block_size(P, K) if order_flag else 0)
+    M_host = torch.from_numpy(M0.copy()).pin_memory()
+    G.gosh_train_parts(n, xadj, adj, M_host, k, epochs, 0.1, 7, level=2, P_gpu=P, S_gpu=S, B=B, force_K=K,
+                       flags=G.GOSH_FLAG_SEQUENTIAL | order_flag)
+    M_dev = torch.from_numpy(M0.copy()).to(DEV)
+    st = G.gosh_train_parts(n, xadj, adj, M_dev, k, epochs, 0.1, 7, level=2, P_gpu=P, S_gpu=S, B=B, force_K=K,
+                            flags=G.GOSH_FLAG_SEQUENTIAL | order_flag)
+    torch.cuda.synchronize()
+    assert np.array_equal(M_dev.cpu().numpy(), M_host.numpy())
+    assert rel_err(M_dev.cpu().numpy(), want) <= 1e-5
+    assert st["bytes_d2h"] == 0 and st["K"] == K
+    if graph_on_device:
+        assert st["bytes_h2d"] == 0
+    # concurrent kernels, default part count: nothing moves at lr = 0, and training stays finite
+    M_dev = torch.from_numpy(M0.copy()).to(DEV)
+    st = G.gosh_train_parts(n, xadj, adj, M_dev, k, epochs, 0.0, 7, flags=order_flag)
+    assert st["K"] == 16 and np.array_equal(M_dev.cpu().numpy(), M0)
+    G.gosh_train_parts(n, xadj, adj, M_dev, k, epochs, 0.05, 7, flags=order_flag)
+    assert torch.isfinite(M_dev).all()
