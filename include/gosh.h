@@ -67,6 +67,15 @@ typedef struct {
                                      |E_i| = nnz_i / 2, and the learning rate decays over all
                                      of them */
 
+#define GOSH_FLAG_PAIR_LEVELS 32u /* a level that fits the device is trained in place with the
+                                     pair scheme of Alg. 5 instead of Alg. 3 -- gosh_train_parts
+                                     on the device matrix, B = 5 -- on the largest K of 16, 8,
+                                     4, 2, 1 whose parts keep 2^22 vertices (GOSH_PAIR_LEVEL_MIN_N
+                                     in the environment overrides the figure) and whose whole
+                                     rotations overshoot the level's epochs by at most an
+                                     eighth; a level for which no K does keeps Alg. 3.  Not the
+                                     paper's choice: see gosh_train_parts for what it buys */
+
 /* gosh_train_parts / gosh_embed_host only */
 #define GOSH_FLAG_BLOCKED_ORDER 16u /* visit the part pairs in the blocked order of
                                        gosh_pair_order_blocked (block = P_gpu - 2 parts, at
@@ -245,7 +254,7 @@ typedef struct {
  * counter, then (i > 0) project to level i-1 with map_{i-1}.  The paper prints the loop
  * as "D-1 to 1"; the text trains until M_0 is obtained, which is what is done here.
  * h: hierarchy (host).  M0_dev: device matrix n_0 x d, receives the embedding of G_0.
- * flags: as for gosh_train_epoch, plus GOSH_FLAG_EDGE_EPOCHS.  device_budget_bytes: if non-zero and the graph plus
+ * flags: as for gosh_train_epoch, plus GOSH_FLAG_EDGE_EPOCHS and GOSH_FLAG_PAIR_LEVELS.  device_budget_bytes: if non-zero and the graph plus
  * matrix of level 0 exceed it, the call is refused with GOSH_EBUDGET (use gosh_embed_host,
  * which keeps such levels on the host).  stats: NULL or host array of D entries, filled per level.
  * Blocking: returns after the last level finished; intermediate device buffers are

@@ -267,12 +267,29 @@ def passes_per_epoch(xadj, adj):
     return passes
 
 
+def pair_level_parts(epochs, n, min_n, B=5):
+    """READING (not the paper's: an option of the multilevel drivers): a level is trained with
+    the pair scheme of Alg. 5 on K parts, all resident, for the largest K in 16, 8, 4, 2, 1
+    whose parts keep at least min_n vertices (K * min_n <= n) and whose whole rotations
+    overshoot the level's epochs by at most an eighth -- rotations * B * K - epochs <=
+    epochs / 8; 0 means "train with Alg. 3"."""
+    for K in (16, 8, 4, 2, 1):
+        if K * min_n > n:
+            continue
+        per = B * K
+        run = -(-epochs // per) * per
+        if (run - epochs) * 8 <= epochs:
+            return K
+    return 0
+
+
 def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, max_levels=64,
-          edge_epochs=False):
+          edge_epochs=False, pair_levels_min_n=None):
     """Alg. 2: coarsen, initialise M_{D-1}, then for i = D-1..0 train e_i epochs on G_i and
     (i > 0) project to G_{i-1}.  READING: the printed loop bound "D-1 to 1" would never
     train G_0; the text trains until M_0 is obtained.  With edge_epochs an epoch is the
     experiments' (Sec. 4.3): level i runs e_i * passes_per_epoch(G_i) passes of Alg. 3.
+    With pair_levels_min_n, levels that pair_level_parts() accepts run Alg. 5 (B = 5).
     Returns (M_0, graphs, maps, passes run per level)."""
     graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink, max_levels)
     D = len(graphs)
@@ -281,7 +298,13 @@ def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, 
         e_i = np.array([int(e_i[i]) * passes_per_epoch(*graphs[i]) for i in range(D)], dtype=np.int64)
     M = init_embedding(graphs[-1][0].size - 1, d, seed, D - 1)
     for i in range(D - 1, -1, -1):
-        train_level(graphs[i][0], graphs[i][1], M, k, lr0, int(e_i[i]), seed, i)
+        K = 0
+        if pair_levels_min_n is not None:
+            K = pair_level_parts(int(e_i[i]), graphs[i][0].size - 1, pair_levels_min_n)
+        if K:
+            train_parts(graphs[i][0], graphs[i][1], M, k, int(e_i[i]), lr0, seed, i, K, 5)
+        else:
+            train_level(graphs[i][0], graphs[i][1], M, k, lr0, int(e_i[i]), seed, i)
         if i > 0:
             M = project(M, maps[i - 1])
     return M, graphs, maps, e_i

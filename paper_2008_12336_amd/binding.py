@@ -19,6 +19,7 @@ GOSH_FLAG_PLAIN_STORES = 2
 GOSH_FLAG_ATOMIC_ADDS = 4
 GOSH_FLAG_EDGE_EPOCHS = 8
 GOSH_FLAG_BLOCKED_ORDER = 16
+GOSH_FLAG_PAIR_LEVELS = 32
 GOSH_MAX_DIM = 512
 GOSH_MAX_NEG = 15
 

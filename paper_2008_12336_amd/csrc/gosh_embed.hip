@@ -10,6 +10,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -92,6 +93,7 @@ struct Plan {
   uint32_t flags;  // for the epoch kernel calls
   uint32_t parts_flags;  // for the rotation calls: the same plus GOSH_FLAG_BLOCKED_ORDER if asked
   bool edge_epochs;
+  bool pair_levels;  // resident levels large enough run Alg. 5 in place
   uint64_t budget;
   bool budget_is_free_memory;  // measured, not given: graphs already on the device are outside it
   int32_t P_gpu, S_gpu, B;
@@ -143,7 +145,11 @@ class MultilevelRun {
       }
       if (i == D - 1)
         if (int rc = init_coarsest(i)) return rc;
-      if (int rc = cur_dev ? train_on_device(i, ls) : train_by_rotation(i, ls)) return rc;
+      const int32_t in_place_parts = (cur_dev && pl.pair_levels) ? pair_level_parts(ls.epochs, g.n) : 0;
+      if (int rc = !cur_dev         ? train_by_rotation(i, ls)
+                   : in_place_parts ? train_in_place(i, ls, in_place_parts)
+                                    : train_on_device(i, ls))
+        return rc;
       if (i > 0)
         if (int rc = project(i, ls)) return rc;
       if (stats) stats[i] = ls;
@@ -158,6 +164,7 @@ class MultilevelRun {
   }
 
  private:
+  static constexpr int32_t kPairLevelB = 5;
   const gosh_hierarchy *h;
   const Plan &pl;
   const int32_t d;
@@ -215,30 +222,38 @@ class MultilevelRun {
     return GOSH_OK;
   }
 
-  // CopyToDevice(G_i) + TrainInGPU
-  int train_on_device(int i, gosh_level_stats &ls) {
+  // CopyToDevice(G_i): the arrays of level i in device memory -- where the hierarchy keeps
+  // them, else uploaded into the two buffers.
+  int graph_on_device(int i, DeviceBuffer &xadj_dev, DeviceBuffer &adj_dev, gosh_csr *dev) {
     gosh_csr &g = G[static_cast<size_t>(i)];
+    *dev = g;
+    if (const gosh::DeviceLevel *dl = resident(i)) {
+      dev->xadj = dl->xadj;
+      dev->adj = dl->adj;
+      dev->xadj_is64 = dl->xadj_is64;
+      return GOSH_OK;
+    }
+    if (int rc = gosh_hierarchy_graph(h, i, &g)) return rc;
+    const size_t off_bytes = static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4);
+    const size_t adj_bytes = static_cast<size_t>(g.nnz) * 4;
+    if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
+    if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
+    GOSH_TRY_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
+    if (adj_bytes)
+      GOSH_TRY_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
+    GOSH_TRY_HIP(hipStreamSynchronize(st), "upload graph");
+    *dev = g;
+    dev->xadj = xadj_dev.ptr;
+    dev->adj = static_cast<const int32_t *>(adj_dev.ptr);
+    return GOSH_OK;
+  }
+
+  // TrainInGPU
+  int train_on_device(int i, gosh_level_stats &ls) {
     auto t0 = std::chrono::steady_clock::now();
     DeviceBuffer xadj_dev, adj_dev;
-    gosh_csr dev = g;
-    if (const gosh::DeviceLevel *dl = resident(i)) {
-      dev.xadj = dl->xadj;
-      dev.adj = dl->adj;
-      dev.xadj_is64 = dl->xadj_is64;
-    } else {
-      if (int rc = gosh_hierarchy_graph(h, i, &g)) return rc;
-      const size_t off_bytes = static_cast<size_t>(g.n + 1) * (g.xadj_is64 ? 8 : 4);
-      const size_t adj_bytes = static_cast<size_t>(g.nnz) * 4;
-      if (int rc = xadj_dev.alloc(off_bytes, "xadj")) return rc;
-      if (int rc = adj_dev.alloc(adj_bytes, "adj")) return rc;
-      GOSH_TRY_HIP(hipMemcpyAsync(xadj_dev.ptr, g.xadj, off_bytes, hipMemcpyHostToDevice, st), "copy xadj");
-      if (adj_bytes)
-        GOSH_TRY_HIP(hipMemcpyAsync(adj_dev.ptr, g.adj, adj_bytes, hipMemcpyHostToDevice, st), "copy adj");
-      GOSH_TRY_HIP(hipStreamSynchronize(st), "upload graph");
-      dev = g;
-      dev.xadj = xadj_dev.ptr;
-      dev.adj = static_cast<const int32_t *>(adj_dev.ptr);
-    }
+    gosh_csr dev{};
+    if (int rc = graph_on_device(i, xadj_dev, adj_dev, &dev)) return rc;
     ls.upload_ms = ms_since(t0);
     GOSH_TRY_HIP(hipEventRecord(ev0, st), "hipEventRecord");
     for (int64_t j = 0; j < ls.epochs; ++j) {
@@ -252,6 +267,43 @@ class MultilevelRun {
     float ms = 0.f;
     GOSH_TRY_HIP(hipEventElapsedTime(&ms, ev0, ev1), "hipEventElapsedTime");
     ls.train_ms = ms;
+    return GOSH_OK;
+  }
+
+  // Parts for training a resident level of n vertices for `epochs` epochs with the pair
+  // scheme in place (GOSH_FLAG_PAIR_LEVELS), 0 for "use Alg. 3": the largest K of 16, 8, 4,
+  // 2, 1 whose parts keep 2^22 vertices (on smaller parts the scheme gains little or loses:
+  // 2.4 M vertices in 16 parts trained at half the rate of Alg. 3, in 2 parts a fifth
+  // slower) and whose whole rotations of B = 5 rounds overshoot the epochs by at most an
+  // eighth.
+  static int32_t pair_level_parts(int64_t epochs, int64_t n) {
+    int64_t min_n = int64_t{1} << 22;
+    if (const char *e = getenv("GOSH_PAIR_LEVEL_MIN_N")) min_n = atoll(e);  // read per call: tests set it
+    if (min_n < 1) min_n = 1;
+    for (int32_t K = 16; K >= 1; K /= 2) {
+      if (K * min_n > n) continue;
+      const int64_t per = int64_t{kPairLevelB} * K;
+      const int64_t run = (epochs + per - 1) / per * per;
+      if ((run - epochs) * 8 <= epochs) return K;
+    }
+    return 0;
+  }
+
+  // The same level trained in place with the pair order and the sampling rule of Alg. 5
+  // (no part moves: the matrix is on the device); the streams are the rotation's own.
+  int train_in_place(int i, gosh_level_stats &ls, int32_t K) {
+    auto t0 = std::chrono::steady_clock::now();
+    DeviceBuffer xadj_dev, adj_dev;
+    gosh_csr dev{};
+    if (int rc = graph_on_device(i, xadj_dev, adj_dev, &dev)) return rc;
+    ls.upload_ms = ms_since(t0);
+    GOSH_TRY_HIP(hipStreamSynchronize(st), "before the rotation");
+    gosh_parts_stats ps{};
+    if (int rc = gosh_train_parts(&dev, cur_dev, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed, static_cast<uint32_t>(i),
+                                  0, pl.P_gpu, 1, kPairLevelB, K, pl.parts_flags, &ps))
+      return rc;
+    ls.parts_K = ps.K;
+    ls.train_ms = ps.wall_ms;
     return GOSH_OK;
   }
 
@@ -411,9 +463,9 @@ int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs
     if (int rc = gosh::check_device_span(M0_dev, static_cast<size_t>(g0.n) * d * 4, "M0")) return rc;
   }
   // A level above level 0 can only exceed the budget if level 0 does too, which is refused.
-  const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
+  const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER | GOSH_FLAG_PAIR_LEVELS);
   const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags, (flags & GOSH_FLAG_EDGE_EPOCHS) != 0,
-                device_budget_bytes, false, 3, 4, 5};
+                (flags & GOSH_FLAG_PAIR_LEVELS) != 0, device_budget_bytes, false, 3, 4, 5};
   return embed_impl(h, pl, epochs, p, M0_dev, nullptr, stats, gosh::as_stream(hip_stream));
 }
 
@@ -425,7 +477,7 @@ int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t e
   if (int rc = gosh::check_matrix(M0_host, d, "M0")) return rc;
   if (P_gpu < 2 || S_gpu < 1 || B < 1)
     return gosh::fail(GOSH_EINVAL, "need P_gpu >= 2, S_gpu >= 1, B >= 1");
-  const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER);
+  const uint32_t train_flags = flags & ~(GOSH_FLAG_EDGE_EPOCHS | GOSH_FLAG_BLOCKED_ORDER | GOSH_FLAG_PAIR_LEVELS);
   // No budget given: Alg. 2's "fits into the GPU" is asked of the device itself -- what it has
   // free now, less a sixteenth for the staging buffers and pools of the calls below.
   const bool measure = device_budget_bytes == 0;
@@ -436,7 +488,8 @@ int gosh_embed_host(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t e
     if (device_budget_bytes == 0) return gosh::fail(GOSH_ENOMEM, "the device has no free memory");
   }
   const Plan pl{d, k_neg, lr0, seed, train_flags, train_flags | (flags & GOSH_FLAG_BLOCKED_ORDER),
-                (flags & GOSH_FLAG_EDGE_EPOCHS) != 0, device_budget_bytes, measure, P_gpu, S_gpu, B};
+                (flags & GOSH_FLAG_EDGE_EPOCHS) != 0, (flags & GOSH_FLAG_PAIR_LEVELS) != 0, device_budget_bytes, measure,
+                P_gpu, S_gpu, B};
   return embed_impl(h, pl, epochs, p, nullptr, M0_host, stats, gosh::as_stream(hip_stream));
 }
 

@@ -169,3 +169,35 @@ def test_cxx_example_embeds_through_the_c_abi_alone():
     print(run.stdout, run.stderr, flush=True)
     assert run.returncode == 0
     assert "mean dot over edges" in run.stdout
+
+
+@pytest.mark.parametrize("host_matrix", [False, True])
+def test_pair_levels_vcycle_matches_the_oracle(host_matrix, monkeypatch):
+    """GOSH_FLAG_PAIR_LEVELS: resident levels above a size (lowered here through the
+    environment) train in place with Alg. 5, K by the rule the oracle states; the sequential
+    V-cycle must match the oracle's composition level by level."""
+    monkeypatch.setenv("GOSH_PAIR_LEVEL_MIN_N", "300")
+    n, d, k, epochs = 3000, 32, 3, 260
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 24000, 4))
+    xadj, adj = c.xadj.numpy(), c.adj.numpy()
+    want, graphs, maps, e_i = O.embed(xadj, adj, d, k, epochs, 0.3, 0.05, 5, threshold=100, min_shrink=0.8,
+                                      pair_levels_min_n=300)
+    want_K = [O.pair_level_parts(int(e_i[i]), graphs[i][0].size - 1, 300) for i in range(len(graphs))]
+    assert any(want_K) and not all(want_K), want_K  # both kinds of level occur
+    h = G.gosh_coarsen_device(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
+    flags = G.GOSH_FLAG_SEQUENTIAL | G.GOSH_FLAG_PAIR_LEVELS
+    if host_matrix:
+        M0 = torch.zeros(n, d, dtype=torch.float32).pin_memory()
+        stats = G.gosh_embed_host(h, M0, k, epochs, 0.3, 0.05, 5, flags=flags)
+        got = M0.numpy()
+    else:
+        M0 = torch.zeros(n, d, dtype=torch.float32, device=DEV)
+        stats = G.gosh_embed(h, M0, k, epochs, 0.3, 0.05, 5, flags=flags)
+        torch.cuda.synchronize()
+        got = M0.cpu().numpy()
+    assert [s["parts_K"] for s in sorted(stats, key=lambda s: s["level"])] == want_K
+    assert rel_err(got, want) <= 1e-5
+    h.free()
+    # without the flag the same call trains every level with Alg. 3
+    plain, *_ = O.embed(xadj, adj, d, k, epochs, 0.3, 0.05, 5, threshold=100, min_shrink=0.8)
+    assert rel_err(got, plain) > 1e-3
