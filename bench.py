@@ -263,10 +263,7 @@ def main() -> int:
     d, k = w["d"], w["k"]
     dev = "cuda:0"
 
-    # Allocated before the generator churns through device memory.  (Where a big, randomly
-    # accessed array lands matters under memory pressure: the 33 GB matrix of cfg5 trains at
-    # 56 ms per epoch when allocated before the coarsening takes its 100 GB of scratch and
-    # at 67 ms when allocated after it; the 8.6 GB matrix here shows no difference.)
+    # the output matrix first, then the generator's temporaries
     M = torch.empty(n, d, dtype=torch.float32, device=dev) if args.mode == "epoch" else None
 
     t0 = time.time()

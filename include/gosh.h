@@ -254,8 +254,6 @@ typedef struct {
  * counter, then (i > 0) project to level i-1 with map_{i-1}.  The paper prints the loop
  * as "D-1 to 1"; the text trains until M_0 is obtained, which is what is done here.
  * h: hierarchy (host).  M0_dev: device matrix n_0 x d, receives the embedding of G_0.
- * (For matrices of tens of GB: allocate M0_dev before building the hierarchy on the same
- * device; memory handed out after the coarsening's scratch traffic trained 20 % slower.)
  * flags: as for gosh_train_epoch, plus GOSH_FLAG_EDGE_EPOCHS and GOSH_FLAG_PAIR_LEVELS.  device_budget_bytes: if non-zero and the graph plus
  * matrix of level 0 exceed it, the call is refused with GOSH_EBUDGET (use gosh_embed_host,
  * which keeps such levels on the host).  stats: NULL or host array of D entries, filled per level.
