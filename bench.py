@@ -263,9 +263,6 @@ def main() -> int:
     d, k = w["d"], w["k"]
     dev = "cuda:0"
 
-    # the output matrix first, then the generator's temporaries
-    M = torch.empty(n, d, dtype=torch.float32, device=dev) if args.mode == "epoch" else None
-
     t0 = time.time()
     if w["gen"] == "chung_lu":
         edges = graphgen.chung_lu(n, m, args.seed, gamma=2.1, device=dev)
@@ -284,6 +281,7 @@ def main() -> int:
     if args.mode == "parts":
         return run_parts(args, w, csr, n, n_edges, t_graph)
 
+    M = torch.empty(n, d, dtype=torch.float32, device=dev)
     G.gosh_init_embedding(M, args.seed, 0)
     torch.cuda.synchronize()
 
