@@ -216,6 +216,9 @@ def main() -> int:
                     help="--mode levels: where the coarse graphs are rebuilt")
     ap.add_argument("--graph", default="host", choices=["host", "device"],
                     help="--mode levels with --coarsen device, --mode parts: where G_0 is handed over")
+    ap.add_argument("--placement", default="search", choices=["search", "plain"],
+                    help="--mode epoch: where the matrix lies (search: the fastest window of a large "
+                         "arena, which straddles two HBM ranks; plain: an allocation of its own)")
     ap.add_argument("--matrix", default="host", choices=["host", "device"],
                     help="--mode parts: where the matrix lives (device: parts trained in place, no copies)")
     ap.add_argument("--parts", type=int, default=0, help="--mode parts --matrix device: part count (default 16)")
@@ -281,7 +284,15 @@ def main() -> int:
     if args.mode == "parts":
         return run_parts(args, w, csr, n, n_edges, t_graph)
 
-    M = torch.empty(n, d, dtype=torch.float32, device=dev)
+    placement = {"mode": "plain"}
+    arena = None
+    if args.placement == "search":
+        release_generator_memory(torch)
+        from paper_2008_12336_amd.placement import place_matrix
+
+        M, arena, placement = place_matrix(g, n, d, k, args.seed)
+    else:
+        M = torch.empty(n, d, dtype=torch.float32, device=dev)
     G.gosh_init_embedding(M, args.seed, 0)
     torch.cuda.synchronize()
 
@@ -365,7 +376,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": args.workload + ("_scaled" if scaled else ""), "desc": w["desc"],
                    "n": n, "undirected_edges": n_edges, "nnz": int(csr.adj.numel()), "d": d,
-                   "k_neg": k, "seed": args.seed, "flags": args.flags, "graph_build_s": round(t_graph, 2),
+                   "k_neg": k, "seed": args.seed, "flags": args.flags, "placement": placement, "graph_build_s": round(t_graph, 2),
                    "finite": finite},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,

@@ -355,3 +355,27 @@ def test_projection_through_a_map_with_invalid_entries():
     valid = (m >= 0) & (m < n_coarse)
     want[valid] = Mc[m[valid]]
     assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_place_matrix_returns_a_window_of_its_arena_or_a_plain_matrix():
+    """paper_2008_12336_amd.placement: the matrix handed back is a contiguous n x d window of
+    the arena (or a plain allocation when no arena of three times its size is allowed), and
+    training on it gives what training on any other matrix gives."""
+    from paper_2008_12336_amd.placement import place_matrix
+
+    n, d, k = 1 << 16, 128, 3
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 1 << 19, 2))
+    xd, ad = c.xadj.to(DEV), c.adj.to(DEV)
+    g = G.csr_view(n, xd, ad)
+    M, arena, info = place_matrix(g, n, d, k, seed=1, arena_bytes=10 << 30, keep_free_bytes=8 << 30)
+    assert info["mode"] == "search" and info["windows_timed"] >= 3
+    assert M.shape == (n, d) and M.is_contiguous() and arena is not None
+    first = (M.data_ptr() - arena.data_ptr()) // (d * 4)
+    assert 0 <= first <= arena.shape[0] - n and (M.data_ptr() - arena.data_ptr()) % (d * 4) == 0
+    plain, no_arena, info2 = place_matrix(g, n, d, k, seed=1, arena_bytes=2 * n * d * 4)
+    assert no_arena is None and info2["mode"].startswith("plain") and plain.shape == (n, d)
+    for X in (M, plain):
+        G.gosh_init_embedding(X, 5, 0)
+        G.gosh_train_epoch(g, X, k, 0.05, 5, 0, 0, G.GOSH_FLAG_SEQUENTIAL)
+    torch.cuda.synchronize()
+    assert torch.equal(M, plain)
