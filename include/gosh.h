@@ -220,6 +220,9 @@ int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint3
  * first use), so concurrent-mode calls on one device must not overlap on different
  * streams.
  * g_dev: CSR arrays on the device.  M_dev: device matrix, updated in place.
+ * (Where M_dev lies matters on this device: random row traffic inside one of the three HBM
+ * ranks runs at about 5.2 TB/s, across two at about 6.2 TB/s; a window of a large allocation
+ * that straddles two ranks can be found by timing, as the package's placement helper does.)
  * lr_epoch: the already decayed learning rate (gosh_lr).  0 <= k_neg <= GOSH_MAX_NEG. */
 int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg,
                      float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
