@@ -94,8 +94,17 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     if args.budget_gb is not None:
         budget = int(args.budget_gb * (1 << 30))
     # the output matrix is allocated before the coarsening takes its scratch
-    M0 = (torch.empty(n, d, dtype=torch.float32, pin_memory=True) if budget
-          else torch.empty(n, d, dtype=torch.float32, device="cuda:0"))
+    placement, arena = {"mode": "plain"}, None
+    if budget:
+        M0 = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
+    elif args.placement == "search" and xadj_h.is_cuda:
+        from paper_2008_12336_amd.placement import place_matrix
+
+        # leave room for the coarsening (up to 64 bytes of scratch per CSR entry with the levels)
+        M0, arena, placement = place_matrix(G.csr_view(n, xadj_h, adj_h), n, d, k, args.seed,
+                                            keep_free_bytes=(24 << 30) + 64 * int(adj_h.numel()))
+    else:
+        M0 = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     t0 = time.perf_counter()
     coarsen = G.gosh_coarsen_device if args.coarsen == "device" else G.gosh_coarsen
     h = coarsen(n, xadj_h, adj_h, threshold=w.get("threshold", 100),
@@ -134,7 +143,7 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
            "config": {"workload": args.workload + "_levels", "desc": w["desc"], "n": n,
                       "device_budget_bytes": budget, "finite": bool(torch.isfinite(M0[::4097]).all()),
                       "undirected_edges": n_edges, "d": d, "k_neg": k, "total_epochs": args.epochs,
-                      "coarsen": args.coarsen, "graph": args.graph, "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
+                      "coarsen": args.coarsen, "graph": args.graph, "placement": placement, "coarsen_s": t_coarsen, "coarsen_stages": coarsen_stages, "embed_wall_s": t_embed, "graph_build_s": t_graph,
                       "levels": levels}}
     print(json.dumps(out))
     return 0
@@ -147,6 +156,7 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     import paper_2008_12336_amd as G
 
     d, k, B = w["d"], w["k"], 5
+    placement, arena = {"mode": "plain"}, None
     if args.graph == "device":
         xadj_h, adj_h = csr.xadj, csr.adj  # sampled where the generator left it
     else:
@@ -159,6 +169,12 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
         # every part trained where it is: the pair order and sampling rule of Alg. 5 without
         # its copies (the budget then only covers the pools)
         M_host, budget = M_dev, 0
+        if args.placement == "search" and xadj_h.is_cuda:
+            from paper_2008_12336_amd.placement import place_matrix
+
+            del M_dev, M_host
+            M_host, arena, placement = place_matrix(G.csr_view(n, xadj_h, adj_h), n, d, k, args.seed)
+            G.gosh_init_embedding(M_host, args.seed, 0)
         K = args.parts if args.parts > 0 else 16
         st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, B * K, w["lr0"], args.seed, S_gpu=args.s_gpu,
                                 B=B, force_K=K, flags=args.flags)
@@ -184,7 +200,7 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
            "steps": 1, "warmup": 0, "ms_per_step": st["wall_ms"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": args.workload + "_parts", "desc": w["desc"], "n": n,
-                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "graph": args.graph, "matrix": args.matrix,
+                      "undirected_edges": n_edges, "d": d, "k_neg": k, "B": B, "graph": args.graph, "matrix": args.matrix, "placement": placement,
                       "ms_per_epoch_worth_of_samples": st["wall_ms"] / (B * st["K"] * st["rotations"]),
                       "flags": args.flags, "P_gpu": args.p_gpu,
                       "S_gpu": args.s_gpu, "device_budget_bytes": budget, "matrix_bytes": n * d * 4,
