@@ -97,11 +97,11 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     placement, arena = {"mode": "plain"}, None
     if budget:
         M0 = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
-    elif args.placement == "search" and xadj_h.is_cuda:
+    elif args.placement == "search":
         from paper_2008_12336_amd.placement import place_matrix
 
         # leave room for the coarsening (up to 64 bytes of scratch per CSR entry with the levels)
-        M0, arena, placement = place_matrix(G.csr_view(n, xadj_h, adj_h), n, d, k, args.seed,
+        M0, arena, placement = place_matrix(n, d, args.seed,
                                             keep_free_bytes=(24 << 30) + 64 * int(adj_h.numel()))
     else:
         M0 = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
@@ -169,11 +169,11 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
         # every part trained where it is: the pair order and sampling rule of Alg. 5 without
         # its copies (the budget then only covers the pools)
         M_host, budget = M_dev, 0
-        if args.placement == "search" and xadj_h.is_cuda:
+        if args.placement == "search":
             from paper_2008_12336_amd.placement import place_matrix
 
             del M_dev, M_host
-            M_host, arena, placement = place_matrix(G.csr_view(n, xadj_h, adj_h), n, d, k, args.seed)
+            M_host, arena, placement = place_matrix(n, d, args.seed)
             G.gosh_init_embedding(M_host, args.seed, 0)
         K = args.parts if args.parts > 0 else 16
         st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, B * K, w["lr0"], args.seed, S_gpu=args.s_gpu,
@@ -306,7 +306,7 @@ def main() -> int:
         release_generator_memory(torch)
         from paper_2008_12336_amd.placement import place_matrix
 
-        M, arena, placement = place_matrix(g, n, d, k, args.seed)
+        M, arena, placement = place_matrix(n, d, args.seed)
     else:
         M = torch.empty(n, d, dtype=torch.float32, device=dev)
     G.gosh_init_embedding(M, args.seed, 0)

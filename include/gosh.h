@@ -228,6 +228,17 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
                      float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
                      uint32_t flags, void *hip_stream);
 
+/* Placement probe (no passage of the paper: the memory of the device, not the method).
+ * Reads `accesses` uniformly random rows of the n x d device matrix and writes each back
+ * unchanged (zero is added to one element), one wavefront per row: the row traffic of the
+ * training kernels without their arithmetic.  The caller times it (HIP events on the
+ * stream) to compare candidate locations for a matrix: on this device random row traffic
+ * inside one of the three HBM ranks is slower than traffic that spans two (see
+ * gosh_train_epoch).  The matrix keeps its values, provided nothing else writes it
+ * meanwhile.  Asynchronous on the stream. */
+int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed,
+                   void *hip_stream);
+
 /* "ExpandEmbedding" (Alg. 2; Sec. 3: the row of a vertex of G_{i-1} is the row of its
  * super vertex in G_i): M_fine[v,:] = M_coarse[map[v],:] for v < n_fine.  All pointers
  * are device memory; map holds n_fine ids in [0, n_coarse); an entry outside that range

@@ -97,6 +97,7 @@ EXPORTS = {
                                   C.c_void_p, C.POINTER(gosh_level_stats), C.c_void_p]),
     "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                C.c_void_p, C.c_void_p]),
+    "gosh_row_probe": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_void_p]),
 }
 
 _lib = None
@@ -189,6 +190,12 @@ def gosh_project(M_coarse: torch.Tensor, map_: torch.Tensor, M_fine: torch.Tenso
     if d != d2 or map_.dtype != torch.int32 or map_.numel() != nf or not map_.is_contiguous():
         raise TypeError("map must be int32 with one entry per fine vertex; dims must agree")
     _check(lib().gosh_project(cptr, nc, map_.data_ptr(), nf, d, fptr, _stream(stream)))
+
+
+def gosh_row_probe(M: torch.Tensor, accesses: int, seed: int = 1, stream=None) -> None:
+    """Random row read-write-backs over M (values unchanged); time it to compare locations."""
+    ptr, n, d = _matrix(M, "M")
+    _check(lib().gosh_row_probe(ptr, n, d, accesses, seed, _stream(stream)))
 
 
 def gosh_csr_validate(g: gosh_csr) -> None:

@@ -152,6 +152,25 @@ __global__ __launch_bounds__(256) void project_kernel(const float4 *__restrict__
   }
 }
 
+// Placement probe: `accesses` random rows are read and written back with `nothing` (zero)
+// added, one wavefront per row -- the access pattern of the training kernels without their
+// arithmetic, leaving the matrix as it is.
+__global__ __launch_bounds__(256) void row_probe_kernel(float4 *__restrict__ M, uint64_t n, int32_t d4,
+                                                        uint64_t accesses, uint32_t key0, uint32_t key1,
+                                                        float nothing) {
+  const uint64_t wave = (blockIdx.x * 256ull + threadIdx.x) >> 6, waves = (gridDim.x * 256ull) >> 6;
+  const int lane = threadIdx.x & 63;
+  for (uint64_t i = wave; i < accesses; i += waves) {
+    const uint64_t draw = philox_draw(static_cast<uint32_t>(i), static_cast<uint32_t>(i >> 32), 0xFFFFFFFEu, 0, key0, key1);
+    const uint64_t row = scale_draw(draw, static_cast<uint32_t>(n));
+    for (int c = lane; c < d4; c += 64) {
+      float4 v = M[row * d4 + c];
+      v.x += nothing;
+      M[row * d4 + c] = v;
+    }
+  }
+}
+
 int grid_for(int64_t items, int per_block, int max_blocks) {
   int64_t b = (items + per_block - 1) / per_block;
   if (b < 1) b = 1;
@@ -289,6 +308,19 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
   if (g_dev->xadj_is64)
     return launch_epoch<int64_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, st);
   return launch_epoch<int32_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, st);
+}
+
+int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, void *hip_stream) {
+  if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
+  if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
+  if (accesses < 0) return gosh::fail(GOSH_EINVAL, "accesses = %lld is negative", (long long)accesses);
+  if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(n) * d * 4, "M")) return rc;
+  if (accesses == 0) return GOSH_OK;
+  const int blocks = grid_for(accesses, 4, 1 << 13);  // four wavefronts per block
+  hipLaunchKernelGGL(row_probe_kernel, dim3(blocks), dim3(256), 0, gosh::as_stream(hip_stream),
+                     reinterpret_cast<float4 *>(M_dev), static_cast<uint64_t>(n), d / 4, static_cast<uint64_t>(accesses),
+                     static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), 0.0f);
+  return gosh::check_launch("row_probe_kernel");
 }
 
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev, int64_t n_fine,

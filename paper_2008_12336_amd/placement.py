@@ -4,10 +4,10 @@ The HBM of an MI355X answers in three classes of addresses -- its stacks are twe
 high, three ranks of four, 96 GB per rank over the eight stacks -- and random 512-byte row
 traffic confined to one class runs at about 5.2 TB/s, spread over two at about 6.2 TB/s (a
 probe of plain random row read-modify-writes: 4.7 against 5.35 TB/s).  An allocation of a few
-GB lies inside one class.  `place_matrix` takes a large arena, times one epoch of the real
-kernel on windows of it and hands back the fastest window, in practice one that straddles
-the border between two classes.  Nothing here computes anything of the method: it calls the
-library's entry points and compares their times.
+GB lies inside one class.  `place_matrix` takes a large arena, times the library's row probe
+(random rows read and written back unchanged: the training kernels' traffic without their
+arithmetic) on windows of it and hands back the fastest window, in practice one that
+straddles the border between two classes.  Nothing here computes anything of the method.
 """
 from __future__ import annotations
 
@@ -18,13 +18,12 @@ import torch
 from . import binding as G
 
 
-def place_matrix(g, n: int, d: int, k_neg: int, seed: int, arena_bytes: int = 120 << 30,
+def place_matrix(n: int, d: int, seed: int = 1, arena_bytes: int = 120 << 30,
                  keep_free_bytes: int = 24 << 30):
     """Returns (M, arena, info): M is an n x d float32 window of `arena` (keep `arena` alive
     as long as M is used), or a plain allocation with arena None if no arena of at least three
-    times the matrix can be had.  g: device-resident graph (gosh_csr) the matrix will be
-    trained on; the windows are timed with one epoch of gosh_train_epoch on it (4 GiB apart,
-    then 1 GiB apart around the best), so M comes back holding arbitrary values."""
+    times the matrix can be had.  The windows are timed with gosh_row_probe, 4n accesses each
+    (4 GiB apart, then 1 GiB apart around the best); M comes back uninitialised."""
     row_bytes = d * 4
     need = n * row_bytes
     free_bytes, _ = torch.cuda.mem_get_info()
@@ -40,9 +39,8 @@ def place_matrix(g, n: int, d: int, k_neg: int, seed: int, arena_bytes: int = 12
 
     def epoch_ms(first_row: int) -> float:
         window = arena[first_row:first_row + n]
-        G.gosh_init_embedding(window, seed, 0)
         start.record()
-        G.gosh_train_epoch(g, window, k_neg, 0.01, seed, 0, 0, 0)
+        G.gosh_row_probe(window, 4 * n, seed)
         stop.record()
         torch.cuda.synchronize()
         return start.elapsed_time(stop)
@@ -55,6 +53,17 @@ def place_matrix(g, n: int, d: int, k_neg: int, seed: int, arena_bytes: int = 12
         if r not in timed:
             timed[r] = epoch_ms(r)
     best = min(timed, key=timed.get)
+    # The gain falls off linearly on both sides of the best position (a window sliding off a
+    # border between two classes): the centre of gravity of the gains around the fastest
+    # window is a steadier estimate of that position than the fastest single timing.
+    median = sorted(timed.values())[len(timed) // 2]
+    near = {r: median - t for r, t in timed.items() if abs(r - best) <= 4 * rows_per_gib and t < median}
+    if near and sum(near.values()) > 0:
+        centre = int(sum(r * w for r, w in near.items()) / sum(near.values()))
+        centre = max(0, min(last, centre))
+        timed[centre] = epoch_ms(centre)
+        if timed[centre] <= timed[best] * 1.01:
+            best = centre
     info = {"mode": "search", "arena_GiB": arena_bytes / (1 << 30), "window_at_GiB": best / rows_per_gib,
             "probe_ms_best": timed[best], "probe_ms_median": sorted(timed.values())[len(timed) // 2],
             "windows_timed": len(timed), "search_s": time.perf_counter() - t0}

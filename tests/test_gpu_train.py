@@ -367,15 +367,27 @@ def test_place_matrix_returns_a_window_of_its_arena_or_a_plain_matrix():
     c = graphgen.to_csr(n, graphgen.chung_lu(n, 1 << 19, 2))
     xd, ad = c.xadj.to(DEV), c.adj.to(DEV)
     g = G.csr_view(n, xd, ad)
-    M, arena, info = place_matrix(g, n, d, k, seed=1, arena_bytes=10 << 30, keep_free_bytes=8 << 30)
+    M, arena, info = place_matrix(n, d, seed=1, arena_bytes=10 << 30, keep_free_bytes=8 << 30)
     assert info["mode"] == "search" and info["windows_timed"] >= 3
     assert M.shape == (n, d) and M.is_contiguous() and arena is not None
     first = (M.data_ptr() - arena.data_ptr()) // (d * 4)
     assert 0 <= first <= arena.shape[0] - n and (M.data_ptr() - arena.data_ptr()) % (d * 4) == 0
-    plain, no_arena, info2 = place_matrix(g, n, d, k, seed=1, arena_bytes=2 * n * d * 4)
+    plain, no_arena, info2 = place_matrix(n, d, seed=1, arena_bytes=2 * n * d * 4)
     assert no_arena is None and info2["mode"].startswith("plain") and plain.shape == (n, d)
     for X in (M, plain):
         G.gosh_init_embedding(X, 5, 0)
         G.gosh_train_epoch(g, X, k, 0.05, 5, 0, 0, G.GOSH_FLAG_SEQUENTIAL)
     torch.cuda.synchronize()
     assert torch.equal(M, plain)
+
+
+def test_row_probe_leaves_the_matrix_as_it_is():
+    """gosh_row_probe reads random rows and writes them back with zero added: the values stay,
+    for every d (one or two passes of the wavefront over a row) and with rows hit many times."""
+    for n, d in ((1000, 128), (37, 512), (5000, 4), (300, 260)):
+        M0 = torch.randn(n, d, dtype=torch.float32, device=DEV)
+        M = M0.clone()
+        G.gosh_row_probe(M, 8 * n, seed=3)
+        torch.cuda.synchronize()
+        assert torch.equal(M, M0)
+    G.gosh_row_probe(M, 0)  # nothing to do
