@@ -23,7 +23,8 @@ def place_matrix(n: int, d: int, seed: int = 1, arena_bytes: int = 120 << 30,
     """Returns (M, arena, info): M is an n x d float32 window of `arena` (keep `arena` alive
     as long as M is used), or a plain allocation with arena None if no arena of at least three
     times the matrix can be had.  The windows are timed with gosh_row_probe, 4n accesses each
-    (4 GiB apart, then 1 GiB apart around the best); M comes back uninitialised."""
+    (half a window apart but at most 4 GiB, then four times finer around the best); M comes
+    back uninitialised."""
     row_bytes = d * 4
     need = n * row_bytes
     free_bytes, _ = torch.cuda.mem_get_info()
@@ -47,9 +48,14 @@ def place_matrix(n: int, d: int, seed: int = 1, arena_bytes: int = 120 << 30,
 
     rows_per_gib = max(1, (1 << 30) // row_bytes)
     last = arena.shape[0] - n
-    timed = {r: epoch_ms(r) for r in range(0, last + 1, 4 * rows_per_gib)}
+    # a window gains only while it straddles a border, i.e. within its own length of one: scan
+    # at half the window's length (at most 4 GiB, at most about a thousand windows), then at
+    # an eighth around the best
+    coarse = max(1, min(4 * rows_per_gib, max(n // 2, last // 1000)))
+    fine = max(1, coarse // 4)
+    timed = {r: epoch_ms(r) for r in range(0, last + 1, coarse)}
     best = min(timed, key=timed.get)
-    for r in range(max(0, best - 3 * rows_per_gib), min(last, best + 3 * rows_per_gib) + 1, rows_per_gib):
+    for r in range(max(0, best - 3 * fine), min(last, best + 3 * fine) + 1, fine):
         if r not in timed:
             timed[r] = epoch_ms(r)
     best = min(timed, key=timed.get)
@@ -57,7 +63,7 @@ def place_matrix(n: int, d: int, seed: int = 1, arena_bytes: int = 120 << 30,
     # border between two classes): the centre of gravity of the gains around the fastest
     # window is a steadier estimate of that position than the fastest single timing.
     median = sorted(timed.values())[len(timed) // 2]
-    near = {r: median - t for r, t in timed.items() if abs(r - best) <= 4 * rows_per_gib and t < median}
+    near = {r: median - t for r, t in timed.items() if abs(r - best) <= coarse and t < median}
     if near and sum(near.values()) > 0:
         centre = int(sum(r * w for r, w in near.items()) / sum(near.values()))
         centre = max(0, min(last, centre))
