@@ -24,7 +24,9 @@ def place_matrix(n: int, d: int, seed: int = 1, arena_bytes: int = 120 << 30,
     as long as M is used), or a plain allocation with arena None if no arena of at least three
     times the matrix can be had.  The windows are timed with gosh_row_probe, 4n accesses each
     (half a window apart but at most 4 GiB, then four times finer around the best); M comes
-    back uninitialised."""
+    back uninitialised.  The whole arena stays allocated while M is in use -- the price of the
+    placement; a smaller arena_bytes holds less but may contain no border (borders were seen
+    16 to 64 GiB apart), in which case the first window comes back and nothing is gained."""
     row_bytes = d * 4
     need = n * row_bytes
     free_bytes, _ = torch.cuda.mem_get_info()
