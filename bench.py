@@ -77,6 +77,13 @@ def release_generator_memory(torch) -> None:
     time.sleep(0.5 + freed / 25e9)
 
 
+def settle_after_placement(placement) -> None:
+    """The arena pieces the placement gave back are being cleared by the driver: wait for that
+    before the large allocations that follow (see release_generator_memory)."""
+    if placement.get("mode") == "search":
+        time.sleep(0.5 + (placement["arena_bytes"] - placement["kept_bytes"]) / 25e9)
+
+
 def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     """Coarsening (timed separately) + Alg. 2 over all levels, per-level rates."""
     import torch
@@ -94,15 +101,14 @@ def run_levels(args, w, csr, n, n_edges, t_graph) -> int:
     if args.budget_gb is not None:
         budget = int(args.budget_gb * (1 << 30))
     # the output matrix is allocated before the coarsening takes its scratch
-    placement, arena = {"mode": "plain"}, None
+    placement = {"mode": "plain"}
     if budget:
         M0 = torch.empty(n, d, dtype=torch.float32, pin_memory=True)
     elif args.placement == "search":
         from paper_2008_12336_amd.placement import place_matrix
 
-        # leave room for the coarsening (up to 64 bytes of scratch per CSR entry with the levels)
-        M0, arena, placement = place_matrix(n, d, args.seed,
-                                            keep_free_bytes=(24 << 30) + 64 * int(adj_h.numel()))
+        M0, placement = place_matrix(n, d)
+        settle_after_placement(placement)
     else:
         M0 = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
     t0 = time.perf_counter()
@@ -156,7 +162,7 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     import paper_2008_12336_amd as G
 
     d, k, B = w["d"], w["k"], 5
-    placement, arena = {"mode": "plain"}, None
+    placement = {"mode": "plain"}
     if args.graph == "device":
         xadj_h, adj_h = csr.xadj, csr.adj  # sampled where the generator left it
     else:
@@ -173,7 +179,8 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
             from paper_2008_12336_amd.placement import place_matrix
 
             del M_dev, M_host
-            M_host, arena, placement = place_matrix(n, d, args.seed)
+            M_host, placement = place_matrix(n, d)
+            settle_after_placement(placement)
             G.gosh_init_embedding(M_host, args.seed, 0)
         K = args.parts if args.parts > 0 else 16
         st = G.gosh_train_parts(n, xadj_h, adj_h, M_host, k, B * K, w["lr0"], args.seed, S_gpu=args.s_gpu,
@@ -301,12 +308,11 @@ def main() -> int:
         return run_parts(args, w, csr, n, n_edges, t_graph)
 
     placement = {"mode": "plain"}
-    arena = None
     if args.placement == "search":
         release_generator_memory(torch)
         from paper_2008_12336_amd.placement import place_matrix
 
-        M, arena, placement = place_matrix(n, d, args.seed)
+        M, placement = place_matrix(n, d)
     else:
         M = torch.empty(n, d, dtype=torch.float32, device=dev)
     G.gosh_init_embedding(M, args.seed, 0)

@@ -221,8 +221,8 @@ int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint3
  * streams.
  * g_dev: CSR arrays on the device.  M_dev: device matrix, updated in place.
  * (Where M_dev lies matters on this device: random row traffic inside one of the three HBM
- * ranks runs at about 5.2 TB/s, across two at about 6.2 TB/s; a window of a large allocation
- * that straddles two ranks can be found by timing, as the package's placement helper does.)
+ * ranks runs at about 5.2 TB/s, across two at about 6.2 TB/s; gosh_matrix_place allocates a
+ * matrix that lies across two.)
  * lr_epoch: the already decayed learning rate (gosh_lr).  0 <= k_neg <= GOSH_MAX_NEG. */
 int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg,
                      float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
@@ -238,6 +238,28 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
  * meanwhile.  Asynchronous on the stream. */
 int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed,
                    void *hip_stream);
+
+/* What gosh_matrix_place found (all sizes in bytes). */
+typedef struct {
+  uint64_t arena_bytes;          /* physical memory mapped for the search */
+  uint64_t window_offset_bytes;  /* where in the arena the matrix starts */
+  uint64_t kept_bytes;           /* what stays allocated: the 1 GiB pieces under the matrix */
+  int32_t probes;                /* windows timed */
+  float probe_ms_best, probe_ms_median;
+  double search_ms;
+} gosh_placement_info;
+
+/* Allocates an n x d device matrix where random row traffic is fastest (no passage of the
+ * paper: the memory of the device).  Maps an arena of arena_bytes (0: 120 GiB; never more
+ * than what is free less 8 GiB; at least three times the matrix, else GOSH_ENOMEM) out of
+ * 1 GiB pieces with the virtual-memory API, times gosh_row_probe on windows of it, returns
+ * the fastest window in *M_dev -- in practice one that lies across two of the three HBM
+ * ranks -- and gives the pieces outside it back before returning.  The matrix is
+ * uninitialised.  Blocking; uses the null stream.  Free it with gosh_matrix_release (not
+ * hipFree), after the work that uses it is done.  info may be NULL. */
+int gosh_matrix_place(int64_t n, int32_t d, uint64_t arena_bytes, float **M_dev,
+                      gosh_placement_info *info);
+int gosh_matrix_release(float *M_dev);
 
 /* "ExpandEmbedding" (Alg. 2; Sec. 3: the row of a vertex of G_{i-1} is the row of its
  * super vertex in G_i): M_fine[v,:] = M_coarse[map[v],:] for v < n_fine.  All pointers

@@ -48,6 +48,12 @@ class gosh_parts_stats(C.Structure):
                 ("sampler_ms", C.c_double), ("sampler_wait_ms", C.c_double)]
 
 
+class gosh_placement_info(C.Structure):
+    _fields_ = [("arena_bytes", C.c_uint64), ("window_offset_bytes", C.c_uint64), ("kept_bytes", C.c_uint64),
+                ("probes", C.c_int32), ("probe_ms_best", C.c_float), ("probe_ms_median", C.c_float),
+                ("search_ms", C.c_double)]
+
+
 EXPORTS = {
     "gosh_last_error": (C.c_char_p, []),
     "gosh_lr": (C.c_float, [C.c_float, C.c_int64, C.c_int64]),
@@ -98,6 +104,9 @@ EXPORTS = {
     "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                C.c_void_p, C.c_void_p]),
     "gosh_row_probe": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_void_p]),
+    "gosh_matrix_place": (C.c_int, [C.c_int64, C.c_int32, C.c_uint64, C.POINTER(C.c_void_p),
+                                    C.POINTER(gosh_placement_info)]),
+    "gosh_matrix_release": (C.c_int, [C.c_void_p]),
 }
 
 _lib = None
@@ -196,6 +205,32 @@ def gosh_row_probe(M: torch.Tensor, accesses: int, seed: int = 1, stream=None) -
     """Random row read-write-backs over M (values unchanged); time it to compare locations."""
     ptr, n, d = _matrix(M, "M")
     _check(lib().gosh_row_probe(ptr, n, d, accesses, seed, _stream(stream)))
+
+
+class _DeviceArray:
+    """A raw device pointer presented through __cuda_array_interface__ (no ownership)."""
+
+    def __init__(self, ptr: int, rows: int, cols: int):
+        self.__cuda_array_interface__ = {"shape": (rows, cols), "typestr": "<f4", "data": (ptr, False),
+                                         "version": 2, "strides": None}
+
+
+def gosh_matrix_place(n: int, d: int, arena_bytes: int = 0):
+    """An n x d float32 CUDA tensor placed where random row traffic is fastest, and what the
+    search found.  The memory belongs to the library: call gosh_matrix_release(tensor) when
+    nothing uses the tensor any more (not before), or leave it to the end of the process."""
+    ptr = C.c_void_p()
+    info = gosh_placement_info()
+    _check(lib().gosh_matrix_place(n, d, arena_bytes, C.byref(ptr), C.byref(info)))
+    M = torch.as_tensor(_DeviceArray(ptr.value, n, d), device="cuda")
+    if M.data_ptr() != ptr.value:  # a copy would defeat the purpose
+        lib().gosh_matrix_release(ptr)
+        raise RuntimeError("torch copied the placed matrix instead of wrapping it")
+    return M, {name: getattr(info, name) for name, _ in gosh_placement_info._fields_}
+
+
+def gosh_matrix_release(M: torch.Tensor) -> None:
+    _check(lib().gosh_matrix_release(M.data_ptr()))
 
 
 def gosh_csr_validate(g: gosh_csr) -> None:

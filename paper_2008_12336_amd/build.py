@@ -13,7 +13,7 @@ EXAMPLE_SRC = os.path.join(HERE, "examples", "embed_example.cpp")
 EXAMPLE = os.path.join(HERE, "examples", "embed_example")
 RANK_PROBE = os.path.join(HERE, "examples", "hbm_rank_probe")
 
-SOURCES = ["gosh_host.cpp", "gosh_coarsen.cpp", "gosh_sampler.cpp", "gosh_coarsen_gpu.hip", "gosh_train.hip", "gosh_embed.hip", "gosh_parts.hip"]
+SOURCES = ["gosh_host.cpp", "gosh_coarsen.cpp", "gosh_sampler.cpp", "gosh_coarsen_gpu.hip", "gosh_train.hip", "gosh_embed.hip", "gosh_parts.hip", "gosh_place.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950",

@@ -62,6 +62,12 @@ int resident_waves();
 int init_rows(float *rows_dev, int64_t first_row, int64_t count, int32_t d, uint64_t seed,
               uint32_t level, hipStream_t st);
 
+// True if [p, p + bytes) lies inside the mapped part of a matrix of gosh_matrix_place.
+bool inside_placed_matrix(const void *p, size_t bytes);
+
+// The launch behind gosh_row_probe, without its argument checks (the caller has made them).
+int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, hipStream_t st);
+
 // Per-device scratch for the hot-row bitmap (one bit per vertex), grown on demand and
 // kept until the process ends.  Calls on one device must not overlap on different
 // streams.

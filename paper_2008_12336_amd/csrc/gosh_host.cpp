@@ -45,6 +45,9 @@ int check_csr(const gosh_csr *g) {
 }
 
 int check_device_span(const void *p, size_t bytes, const char *what) {
+  // A matrix of gosh_matrix_place is stitched from several mappings, which the runtime
+  // reports one by one: the library knows its extent itself.
+  if (inside_placed_matrix(p, bytes)) return GOSH_OK;
   // The runtime answers for every address: memory it does not know (pageable host memory,
   // a stale or made-up pointer) comes back as "unregistered", not as an error.
   hipPointerAttribute_t attr;

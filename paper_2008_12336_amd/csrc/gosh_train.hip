@@ -249,6 +249,15 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
 
 namespace gosh {
 
+int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, hipStream_t st) {
+  if (accesses <= 0) return GOSH_OK;
+  const int blocks = grid_for(accesses, 4, 1 << 13);  // four wavefronts per block
+  hipLaunchKernelGGL(row_probe_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<float4 *>(M_dev),
+                     static_cast<uint64_t>(n), d / 4, static_cast<uint64_t>(accesses), static_cast<uint32_t>(seed),
+                     static_cast<uint32_t>(seed >> 32), 0.0f);
+  return check_launch("row_probe_kernel");
+}
+
 int init_rows(float *rows_dev, int64_t first_row, int64_t count, int32_t d, uint64_t seed,
               uint32_t level, hipStream_t st) {
   const int64_t total4 = count * (d / 4);
@@ -315,12 +324,7 @@ int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_
   if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
   if (accesses < 0) return gosh::fail(GOSH_EINVAL, "accesses = %lld is negative", (long long)accesses);
   if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(n) * d * 4, "M")) return rc;
-  if (accesses == 0) return GOSH_OK;
-  const int blocks = grid_for(accesses, 4, 1 << 13);  // four wavefronts per block
-  hipLaunchKernelGGL(row_probe_kernel, dim3(blocks), dim3(256), 0, gosh::as_stream(hip_stream),
-                     reinterpret_cast<float4 *>(M_dev), static_cast<uint64_t>(n), d / 4, static_cast<uint64_t>(accesses),
-                     static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), 0.0f);
-  return gosh::check_launch("row_probe_kernel");
+  return gosh::row_probe(M_dev, n, d, accesses, seed, gosh::as_stream(hip_stream));
 }
 
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev, int64_t n_fine,

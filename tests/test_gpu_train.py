@@ -357,28 +357,48 @@ def test_projection_through_a_map_with_invalid_entries():
     assert np.array_equal(out.cpu().numpy(), want)
 
 
-def test_place_matrix_returns_a_window_of_its_arena_or_a_plain_matrix():
-    """paper_2008_12336_amd.placement: the matrix handed back is a contiguous n x d window of
-    the arena (or a plain allocation when no arena of three times its size is allowed), and
-    training on it gives what training on any other matrix gives."""
-    from paper_2008_12336_amd.placement import place_matrix
-
+def test_matrix_place_gives_usable_memory_and_takes_it_back():
+    """gosh_matrix_place: the matrix is an ordinary n x d device array to every entry point
+    (training on it gives bit for bit what training on a plain tensor gives), only the pieces
+    under it stay allocated, release returns them, and a second release is refused."""
     n, d, k = 1 << 16, 128, 3
     c = graphgen.to_csr(n, graphgen.chung_lu(n, 1 << 19, 2))
     xd, ad = c.xadj.to(DEV), c.adj.to(DEV)
     g = G.csr_view(n, xd, ad)
-    M, arena, info = place_matrix(n, d, seed=1, arena_bytes=10 << 30, keep_free_bytes=8 << 30)
-    assert info["mode"] == "search" and info["windows_timed"] >= 3
-    assert M.shape == (n, d) and M.is_contiguous() and arena is not None
-    first = (M.data_ptr() - arena.data_ptr()) // (d * 4)
-    assert 0 <= first <= arena.shape[0] - n and (M.data_ptr() - arena.data_ptr()) % (d * 4) == 0
-    plain, no_arena, info2 = place_matrix(n, d, seed=1, arena_bytes=2 * n * d * 4)
-    assert no_arena is None and info2["mode"].startswith("plain") and plain.shape == (n, d)
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    M, info = G.gosh_matrix_place(n, d, arena_bytes=6 << 30)
+    assert M.shape == (n, d) and M.dtype == torch.float32 and M.is_cuda and M.is_contiguous()
+    assert info["arena_bytes"] == 6 << 30 and info["probes"] >= 3
+    assert n * d * 4 <= info["kept_bytes"] <= n * d * 4 + (2 << 30)
+    assert free_before - torch.cuda.mem_get_info()[0] <= info["kept_bytes"] + (64 << 20)
+    plain = torch.empty(n, d, dtype=torch.float32, device=DEV)
     for X in (M, plain):
         G.gosh_init_embedding(X, 5, 0)
         G.gosh_train_epoch(g, X, k, 0.05, 5, 0, 0, G.GOSH_FLAG_SEQUENTIAL)
+        G.gosh_row_probe(X, 1000)
     torch.cuda.synchronize()
     assert torch.equal(M, plain)
+    # the rotation in place and the projection take it too
+    G.gosh_train_parts(n, xd, ad, M, k, 10, 0.0, 1, force_K=4)
+    out = torch.empty(100, d, dtype=torch.float32, device=DEV)
+    G.gosh_project(M, torch.arange(100, dtype=torch.int32, device=DEV), out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain[:100])
+    G.gosh_matrix_release(M)
+    with pytest.raises(G.GoshError):
+        G.gosh_matrix_release(M)
+    del M
+    # too little room for an arena of three times the matrix: refused, and the helper falls back
+    with pytest.raises(G.GoshError):
+        G.gosh_matrix_place(n, d, arena_bytes=1 << 30)
+    from paper_2008_12336_amd.placement import place_matrix
+
+    P, info2 = place_matrix(n, d, arena_bytes=1 << 30)
+    assert info2["mode"].startswith("plain") and P.shape == (n, d)
+    Q, info3 = place_matrix(n, d, arena_bytes=6 << 30)
+    assert info3["mode"] == "search"
+    G.gosh_matrix_release(Q)
 
 
 def test_row_probe_leaves_the_matrix_as_it_is():
