@@ -98,6 +98,15 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.gosh_project(ok_ptr, 0, 0x3000, 5, 32, ok_ptr * 2, None) == -1  # empty coarse level
     assert lib.gosh_project(ok_ptr, 5, 0, 10, 32, ok_ptr * 2, None) == -1
     assert lib.gosh_epoch_split(10, 0.5, 3, None) == -1
+    # the placement entry points check their arguments before they touch the device too
+    out = C.c_void_p()
+    assert lib.gosh_matrix_place(10, 6, 0, C.byref(out), None) == -1 and out.value is None
+    assert lib.gosh_matrix_place(0, 32, 0, C.byref(out), None) == -1
+    assert lib.gosh_matrix_place(10, 32, 0, None, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 10, 30, 5, 1, None) == -1
+    assert lib.gosh_row_probe(ok_ptr + 4, 10, 32, 5, 1, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 0, 32, 5, 1, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 10, 32, -1, 1, None) == -1
 
 
 def test_header_is_plain_c():
