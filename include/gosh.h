@@ -35,7 +35,10 @@ typedef enum {
   GOSH_EINVAL = -1,  /* an argument violates a documented precondition */
   GOSH_ENOMEM = -2,  /* host or device allocation failed */
   GOSH_EHIP = -3,    /* a HIP runtime call failed */
-  GOSH_EBUDGET = -4  /* device budget too small for the requested part layout */
+  GOSH_EBUDGET = -4, /* device budget too small for the requested part layout */
+  GOSH_EDIVERGED = -5 /* training finished, but the matrix it leaves holds non-finite values
+                         (nothing in Alg. 1 bounds a row; a learning rate too large for the
+                         graph's hubs makes rows grow until fp32 overflows) */
 } gosh_status;
 
 /* Borrowed view of a CSR graph.  All three arrays live on the same side (host or
@@ -60,6 +63,15 @@ typedef struct {
 #define GOSH_FLAG_ATOMIC_ADDS 4u  /* concurrent mode: apply every update as atomic adds of
                                      the step (no update is ever lost; about 2x the cost) */
 
+#define GOSH_FLAG_CONCURRENT_LAYOUT 64u /* debug, with GOSH_FLAG_SEQUENTIAL: the one lane group
+                                     that walks the sources runs the concurrent kernel as it
+                                     is shipped -- its lane-to-column layout, its device-scope
+                                     row accesses, its hot-row rule with the atomic-add and the
+                                     plain-store write paths -- instead of the plain 128-bit
+                                     layout, so that exactly that code can be compared with a
+                                     sequential reference.  No effect without
+                                     GOSH_FLAG_SEQUENTIAL */
+
 /* gosh_embed / gosh_embed_host only */
 #define GOSH_FLAG_EDGE_EPOCHS 8u  /* an epoch is |E_i| sampled sources, the definition of the
                                      paper's experiments (Sec. 4.3), not the |V_i| of Alg. 3:
@@ -70,8 +82,8 @@ typedef struct {
 #define GOSH_FLAG_PAIR_LEVELS 32u /* a level that fits the device is trained in place with the
                                      pair scheme of Alg. 5 instead of Alg. 3 -- gosh_train_parts
                                      on the device matrix, B = 5 -- on the largest K of 16, 8,
-                                     4, 2, 1 whose parts keep 2^22 vertices (GOSH_PAIR_LEVEL_MIN_N
-                                     in the environment overrides the figure) and whose whole
+                                     4, 2, 1 whose parts keep 2^22 vertices (pair_level_min_n of
+                                     gosh_set_tuning) and whose whole
                                      rotations overshoot the level's epochs by at most an
                                      eighth; a level for which no K does keeps Alg. 3.  Not the
                                      paper's choice: see gosh_train_parts for what it buys */
@@ -83,6 +95,34 @@ typedef struct {
                                        per rotation, fewer parts over the host link */
 
 const char *gosh_last_error(void);
+
+/* ---- tuning record ------------------------------------------------------------------ */
+
+/* Constants of this implementation that the paper does not have (Sec. 3.1 accepts lost
+ * updates and only notes that too many of them hurt): how the training kernels are launched
+ * and which rows count as "hot" (updated with atomic adds instead of plain stores, see
+ * gosh_train_epoch).  One record per process, read at the start of every training call;
+ * the library never reads the environment.  Meant for experiments and tests. */
+typedef struct {
+  int32_t plain_rows;        /* non-zero: plain 128-bit row accesses also in the concurrent
+                                kernels (coherent inside one XCD only).  Default 0 */
+  int64_t max_waves;         /* cap on the wavefronts that share the sources of one launch.
+                                Default 2^22 */
+  int64_t hot_inv_eps;       /* a vertex is hot if deg * C / nnz > 1 / hot_inv_eps, C = sources
+                                in flight.  Default 64 */
+  int64_t hot_all_inv_eps;   /* every row is hot if (k_neg + 1) * C / n > 1 / hot_all_inv_eps;
+                                0 switches that rule off.  Default 4 */
+  int64_t hot_min_degree;    /* > 0: skip both rules; a vertex is hot iff its degree is at
+                                least this.  Default 0 */
+  int64_t pair_level_min_n;  /* GOSH_FLAG_PAIR_LEVELS: smallest part, in vertices.
+                                Default 2^22 */
+} gosh_tuning;
+
+void gosh_tuning_defaults(gosh_tuning *t);
+/* NULL restores the defaults.  GOSH_EINVAL for a value outside its range (max_waves,
+ * hot_inv_eps, pair_level_min_n >= 1; the others >= 0); the record is unchanged then. */
+int gosh_set_tuning(const gosh_tuning *t);
+int gosh_get_tuning(gosh_tuning *t);
 
 /* ---- schedule helpers (host, pure) ------------------------------------------------ */
 
@@ -98,6 +138,13 @@ float gosh_lr(float lr0, int64_t j, int64_t e_i);
  * e_i: host array of D entries (written).  GOSH_EINVAL if D < 1, D > 62, p outside
  * [0,1] or e cannot give every level one epoch. */
 int gosh_epoch_split(int64_t e, double p, int32_t D, int64_t *e_i);
+
+/* The rule of GOSH_FLAG_PAIR_LEVELS (host, pure; not the paper's): parts for training a
+ * resident level of n vertices for `epochs` epochs with the pair scheme in place -- the
+ * largest K of 16, 8, 4, 2, 1 with K * min_n <= n whose whole rotations of B rounds overshoot
+ * the epochs by at most an eighth (ceil(epochs / (B*K)) * B*K - epochs <= epochs / 8); 0 =
+ * "train the level with Alg. 3". */
+int32_t gosh_pair_level_parts(int64_t epochs, int64_t n, int64_t min_n, int32_t B);
 
 /* ---- coarsening (host) -------------------------------------------------------------- */
 
@@ -228,6 +275,15 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
                      float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
                      uint32_t flags, void *hip_stream);
 
+/* Divergence check (no passage of the paper: nothing in Alg. 1 bounds a row, and a learning
+ * rate too large for a graph's hubs makes rows grow until fp32 overflows; the training calls
+ * themselves are asynchronous and cannot tell).  Reads the n x d device matrix once and
+ * returns the largest finite |entry| in *max_abs and the number of non-finite entries in
+ * *nonfinite (either may be NULL).  Blocking: waits for the stream.  Uses a 16-byte
+ * per-device result buffer owned by the library, so calls on one device must not overlap. */
+int gosh_matrix_check(const float *M_dev, int64_t n, int32_t d, float *max_abs, int64_t *nonfinite,
+                      void *hip_stream);
+
 /* Placement probe (no passage of the paper: the memory of the device, not the method).
  * Reads `accesses` uniformly random rows of the n x d device matrix and writes each back
  * unchanged (zero is added to one element), one wavefront per row: the row traffic of the
@@ -281,6 +337,9 @@ typedef struct {
   double project_ms; /* map upload + projection to level i-1 (wall clock; 0 at level 0) */
   int32_t parts_K;   /* 0: trained with the epoch kernel; K > 0: trained with the part-pair
                         rotation on K parts (train_ms is then the wall time of that call) */
+  float max_abs;     /* largest finite |entry| of M_i after training (levels trained by the
+                        rotation on a host matrix: as met when parts were written back) */
+  int64_t nonfinite; /* non-finite entries of M_i after training; 0 unless training diverged */
 } gosh_level_stats;
 
 /* Alg. 2 ("GOSH") for levels that fit the device: with D = levels of h and
@@ -294,7 +353,9 @@ typedef struct {
  * matrix of level 0 exceed it, the call is refused with GOSH_EBUDGET (use gosh_embed_host,
  * which keeps such levels on the host).  stats: NULL or host array of D entries, filled per level.
  * Blocking: returns after the last level finished; intermediate device buffers are
- * allocated and freed inside the call. */
+ * allocated and freed inside the call.  Every level is checked after its training
+ * (gosh_matrix_check: one more read of the matrix): if any level ends with non-finite
+ * entries the run is still completed, stats are filled, and GOSH_EDIVERGED is returned. */
 int gosh_embed(const gosh_hierarchy *h, int32_t d, int32_t k_neg, int64_t epochs, double p,
                float lr0, uint64_t seed, uint32_t flags, uint64_t device_budget_bytes,
                float *M0_dev, gosh_level_stats *stats, void *hip_stream);
@@ -328,6 +389,10 @@ typedef struct {
   double wall_ms;        /* whole call, host wall clock */
   double sampler_ms;     /* time the host sampler spent drawing positives (its own clock) */
   double sampler_wait_ms; /* time the driving thread waited for a pool of positives */
+  float max_abs;         /* largest finite |entry| met when parts were written back (device
+                            matrix: of the matrix after the last rotation) */
+  int64_t nonfinite;     /* non-finite entries met there (a part that leaves the device several
+                            times is counted each time); 0 unless training diverged */
 } gosh_parts_stats;
 
 /* Visiting order of the part pairs in one rotation (Sec. 3.3.1): (0,0), (1,0), (1,1),
@@ -390,7 +455,10 @@ int gosh_parts_sample_pair(const gosh_csr *g_host, int32_t K, int32_t pa, int32_
  * (GOSH_FLAG_SEQUENTIAL: every pair kernel runs on one wavefront, sources in order), plus
  * GOSH_FLAG_BLOCKED_ORDER.
  * The library owns its streams, device buffers and sampler thread for the duration of
- * the call, which blocks until the matrix is back on the host.  stats_out may be NULL. */
+ * the call, which blocks until the matrix is back on the host.  stats_out may be NULL.
+ * Every part is checked for non-finite entries on the device before it is written back (the
+ * whole matrix at the end, if it lives on the device): GOSH_EDIVERGED, with the matrix as
+ * training left it, if there were any. */
 int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k_neg,
                      int64_t epochs, float lr0, uint64_t seed, uint32_t level,
                      uint64_t device_budget_bytes, int32_t P_gpu, int32_t S_gpu, int32_t B,

@@ -21,12 +21,18 @@
 //   bounded index     pinned (brute force 128-bit product, edge values)
 //   update            pinned (hand-worked values, finite-difference gradient)
 //   sampling          pinned (membership, chi-square uniformity, degenerate cases)
-//   epoch / schedule  pinned (closed form, composition of single updates)
+//   epoch / schedule  pinned (closed form; an epoch and the e_i-epoch loop replayed as
+//                     single updates over the recorded streams, with hand-typed rates)
+//   initial matrix    pinned (entries worked out from an independent Philox's words)
 //   coarsening        pinned (worked examples, invariants, dense brute force)
 //   projection/split  pinned (closed form)
-//   pair order/parts  pinned (closed form, coverage invariants); the host/device
+//   pair order/parts  pinned (closed form, coverage invariants; a pair visit and the
+//                     rotation loop replayed from draws, candidate lists and single
+//                     updates; chi-square of the in-part positive); the host/device
 //                     overlap of the parts driver has no numeric oracle:
 //                     "parity unpinned" for scheduling, pinned for results.
+//   level loop        (gosh_oracle.py: embed, embed_budget, parts_split) pinned (a
+//                     three-level toy composed by hand, budgets worked out by hand)
 //   hogwild slice     the one multi-threaded function (orc_train_sources_hogwild): the
 //                     sequential loop under a parallel-for, for timing the paper's
 //                     multi-core CPU baseline; no expected value is ever taken from it

@@ -267,29 +267,15 @@ def passes_per_epoch(xadj, adj):
     return passes
 
 
-def pair_level_parts(epochs, n, min_n, B=5):
-    """READING (not the paper's: an option of the multilevel drivers): a level is trained with
-    the pair scheme of Alg. 5 on K parts, all resident, for the largest K in 16, 8, 4, 2, 1
-    whose parts keep at least min_n vertices (K * min_n <= n) and whose whole rotations
-    overshoot the level's epochs by at most an eighth -- rotations * B * K - epochs <=
-    epochs / 8; 0 means "train with Alg. 3"."""
-    for K in (16, 8, 4, 2, 1):
-        if K * min_n > n:
-            continue
-        per = B * K
-        run = -(-epochs // per) * per
-        if (run - epochs) * 8 <= epochs:
-            return K
-    return 0
-
-
 def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, max_levels=64,
-          edge_epochs=False, pair_levels_min_n=None):
+          edge_epochs=False, parts_K=None):
     """Alg. 2: coarsen, initialise M_{D-1}, then for i = D-1..0 train e_i epochs on G_i and
     (i > 0) project to G_{i-1}.  READING: the printed loop bound "D-1 to 1" would never
     train G_0; the text trains until M_0 is obtained.  With edge_epochs an epoch is the
     experiments' (Sec. 4.3): level i runs e_i * passes_per_epoch(G_i) passes of Alg. 3.
-    With pair_levels_min_n, levels that pair_level_parts() accepts run Alg. 5 (B = 5).
+    parts_K (not the paper's: Alg. 2 trains a level that fits with Alg. 3): one entry per
+    level, given by the caller; level i runs Alg. 5 on parts_K[i] parts with B = 5 where the
+    entry is non-zero, Alg. 3 otherwise.
     Returns (M_0, graphs, maps, passes run per level)."""
     graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink, max_levels)
     D = len(graphs)
@@ -298,9 +284,7 @@ def embed(xadj, adj, d, k, epochs, p, lr0, seed, threshold=100, min_shrink=1.0, 
         e_i = np.array([int(e_i[i]) * passes_per_epoch(*graphs[i]) for i in range(D)], dtype=np.int64)
     M = init_embedding(graphs[-1][0].size - 1, d, seed, D - 1)
     for i in range(D - 1, -1, -1):
-        K = 0
-        if pair_levels_min_n is not None:
-            K = pair_level_parts(int(e_i[i]), graphs[i][0].size - 1, pair_levels_min_n)
+        K = int(parts_K[i]) if parts_K is not None else 0
         if K:
             train_parts(graphs[i][0], graphs[i][1], M, k, int(e_i[i]), lr0, seed, i, K, 5)
         else:
@@ -326,12 +310,12 @@ def parts_split(n, d, budget, P_gpu, S_gpu, B):
 
 
 def embed_budget(xadj, adj, d, k, epochs, p, lr0, seed, budget, P_gpu=3, S_gpu=4, B=5,
-                 threshold=100, min_shrink=1.0, offsets64=False, blocked=False):
+                 threshold=100, min_shrink=1.0, offsets64=False, blocked=False, max_levels=64):
     """Alg. 2 with its "fits into GPU" test: a level whose graph (offsets + adj) and matrix
     exceed `budget` bytes is trained with the rotation of Alg. 5, the others with Alg. 3.
     Coarse levels have 64-bit offsets; level 0 as given.  Returns (M_0, modes) where
     modes[i] is 0 or the K used."""
-    graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink)
+    graphs, maps, _ = coarsen(xadj, adj, threshold, min_shrink, max_levels)
     D = len(graphs)
     e_i = epoch_split(epochs, p, D)
     M = init_embedding(graphs[-1][0].size - 1, d, seed, D - 1)

@@ -20,6 +20,8 @@ GOSH_FLAG_ATOMIC_ADDS = 4
 GOSH_FLAG_EDGE_EPOCHS = 8
 GOSH_FLAG_BLOCKED_ORDER = 16
 GOSH_FLAG_PAIR_LEVELS = 32
+GOSH_FLAG_CONCURRENT_LAYOUT = 64
+GOSH_EDIVERGED = -5
 GOSH_MAX_DIM = 512
 GOSH_MAX_NEG = 15
 
@@ -38,14 +40,21 @@ class gosh_csr(C.Structure):
 class gosh_level_stats(C.Structure):
     _fields_ = [("level", C.c_int32), ("n", C.c_int64), ("nnz", C.c_int64), ("epochs", C.c_int64),
                 ("upload_ms", C.c_double), ("train_ms", C.c_double), ("project_ms", C.c_double),
-                ("parts_K", C.c_int32)]
+                ("parts_K", C.c_int32), ("max_abs", C.c_float), ("nonfinite", C.c_int64)]
 
 
 class gosh_parts_stats(C.Structure):
     _fields_ = [("K", C.c_int32), ("rotations", C.c_int64), ("pair_visits", C.c_int64),
                 ("updates", C.c_int64), ("device_bytes", C.c_uint64), ("bytes_h2d", C.c_uint64),
                 ("bytes_d2h", C.c_uint64), ("kernel_ms", C.c_double), ("wall_ms", C.c_double),
-                ("sampler_ms", C.c_double), ("sampler_wait_ms", C.c_double)]
+                ("sampler_ms", C.c_double), ("sampler_wait_ms", C.c_double), ("max_abs", C.c_float),
+                ("nonfinite", C.c_int64)]
+
+
+class gosh_tuning(C.Structure):
+    _fields_ = [("plain_rows", C.c_int32), ("max_waves", C.c_int64), ("hot_inv_eps", C.c_int64),
+                ("hot_all_inv_eps", C.c_int64), ("hot_min_degree", C.c_int64),
+                ("pair_level_min_n", C.c_int64)]
 
 
 class gosh_placement_info(C.Structure):
@@ -56,6 +65,12 @@ class gosh_placement_info(C.Structure):
 
 EXPORTS = {
     "gosh_last_error": (C.c_char_p, []),
+    "gosh_tuning_defaults": (None, [C.POINTER(gosh_tuning)]),
+    "gosh_set_tuning": (C.c_int, [C.POINTER(gosh_tuning)]),
+    "gosh_get_tuning": (C.c_int, [C.POINTER(gosh_tuning)]),
+    "gosh_pair_level_parts": (C.c_int32, [C.c_int64, C.c_int64, C.c_int64, C.c_int32]),
+    "gosh_matrix_check": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_float),
+                                    C.POINTER(C.c_int64), C.c_void_p]),
     "gosh_lr": (C.c_float, [C.c_float, C.c_int64, C.c_int64]),
     "gosh_epoch_split": (C.c_int, [C.c_int64, C.c_double, C.c_int32, C.POINTER(C.c_int64)]),
     "gosh_csr_validate": (C.c_int, [C.POINTER(gosh_csr)]),
@@ -158,6 +173,45 @@ def _matrix(M: torch.Tensor, name: str):
 
 def gosh_last_error() -> str:
     return lib().gosh_last_error().decode()
+
+
+def gosh_tuning_defaults() -> dict:
+    t = gosh_tuning()
+    lib().gosh_tuning_defaults(C.byref(t))
+    return {name: getattr(t, name) for name, _ in gosh_tuning._fields_}
+
+
+def gosh_get_tuning() -> dict:
+    t = gosh_tuning()
+    _check(lib().gosh_get_tuning(C.byref(t)))
+    return {name: getattr(t, name) for name, _ in gosh_tuning._fields_}
+
+
+def gosh_set_tuning(**fields) -> None:
+    """Set the named fields of the process-wide tuning record; the others return to their
+    defaults.  No arguments: everything back to the defaults."""
+    if not fields:
+        _check(lib().gosh_set_tuning(None))
+        return
+    t = gosh_tuning()
+    lib().gosh_tuning_defaults(C.byref(t))
+    for name, value in fields.items():
+        if name not in dict(gosh_tuning._fields_):
+            raise TypeError(f"gosh_tuning has no field {name!r}")
+        setattr(t, name, value)
+    _check(lib().gosh_set_tuning(C.byref(t)))
+
+
+def gosh_pair_level_parts(epochs: int, n: int, min_n: int, B: int = 5) -> int:
+    return int(lib().gosh_pair_level_parts(epochs, n, min_n, B))
+
+
+def gosh_matrix_check(M: torch.Tensor, stream=None):
+    """(largest finite |entry|, number of non-finite entries) of a device matrix."""
+    ptr, n, d = _matrix(M, "M")
+    top, bad = C.c_float(), C.c_int64()
+    _check(lib().gosh_matrix_check(ptr, n, d, C.byref(top), C.byref(bad), _stream(stream)))
+    return float(top.value), int(bad.value)
 
 
 def gosh_lr(lr0: float, j: int, e_i: int) -> float:
@@ -397,7 +451,8 @@ def gosh_embed(h: Hierarchy, M0: torch.Tensor, k_neg: int, epochs: int, p: float
 
 def _level_stats(stats):
     return [dict(level=s.level, n=s.n, nnz=s.nnz, epochs=s.epochs, upload_ms=s.upload_ms,
-                 train_ms=s.train_ms, project_ms=s.project_ms, parts_K=s.parts_K) for s in stats]
+                 train_ms=s.train_ms, project_ms=s.project_ms, parts_K=s.parts_K, max_abs=s.max_abs,
+                 nonfinite=s.nonfinite) for s in stats]
 
 
 def gosh_embed_host(h: Hierarchy, M0_host: torch.Tensor, k_neg: int, epochs: int, p: float,

@@ -11,7 +11,6 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgosh.so")
 EXAMPLE_SRC = os.path.join(HERE, "examples", "embed_example.cpp")
 EXAMPLE = os.path.join(HERE, "examples", "embed_example")
-RANK_PROBE = os.path.join(HERE, "examples", "hbm_rank_probe")
 
 SOURCES = ["gosh_host.cpp", "gosh_coarsen.cpp", "gosh_sampler.cpp", "gosh_coarsen_gpu.hip", "gosh_train.hip", "gosh_embed.hip", "gosh_parts.hip", "gosh_place.hip"]
 
@@ -58,12 +57,6 @@ def build_example(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    probe = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall",
-             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             os.path.join(HERE, "examples", "hbm_rank_probe.cpp"), "-o", RANK_PROBE]
-    if verbose:
-        print(" ".join(probe))
-    subprocess.run(probe, check=True)
     return EXAMPLE
 
 

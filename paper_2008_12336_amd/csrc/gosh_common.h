@@ -40,19 +40,9 @@ int hip_fail(hipError_t e, const char *what);
     if (e_ != hipSuccess) return gosh::hip_fail(e_, what);       \
   } while (0)
 
-// Tuning / experiment overrides, read once from the environment.
-//   GOSH_ROW_POLICY=0      plain 128-bit row accesses also in the concurrent kernels
-//                          (coherent inside one XCD only)
-//   GOSH_MAX_WAVES         cap on the wavefronts that share the sources of a launch
-//   GOSH_HOT_INV_EPS       1/eps of the hot-row degree rule (default 64)
-//   GOSH_HOT_ALL_INV_EPS   1/eps of the "every row is hot" rule (default 4)
-struct Tuning {
-  int row_policy;
-  int64_t max_waves;
-  int64_t hot_inv_eps;
-  int64_t hot_all_inv_eps;
-};
-const Tuning &tuning();
+// The process-wide tuning record behind gosh_set_tuning / gosh_get_tuning (fields documented
+// in gosh.h).  Read at the start of every call that launches a training kernel.
+gosh_tuning tuning();
 
 // Wavefronts the device keeps resident (8 on each of the 4 SIMDs of every CU).
 int resident_waves();
@@ -67,6 +57,21 @@ bool inside_placed_matrix(const void *p, size_t bytes);
 
 // The launch behind gosh_row_probe, without its argument checks (the caller has made them).
 int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, hipStream_t st);
+
+// Divergence check: largest finite |entry| (as the bits of the float) and the number of
+// non-finite entries, accumulated on the device.  clear, then add any number of row ranges
+// (all on one stream, or ordered by events), then read (copies the result and waits for the
+// stream).
+struct CheckResult {
+  uint32_t max_bits;
+  uint32_t pad;
+  unsigned long long nonfinite;
+};
+int matrix_check_clear(CheckResult *result_dev, hipStream_t st);
+int matrix_check_add(const float *rows_dev, int64_t floats, CheckResult *result_dev, hipStream_t st);
+int matrix_check_read(const CheckResult *result_dev, float *max_abs, int64_t *nonfinite, hipStream_t st);
+// A per-device CheckResult owned by the library (allocated on first use, kept).
+int check_scratch(CheckResult **out);
 
 // Per-device scratch for the hot-row bitmap (one bit per vertex), grown on demand and
 // kept until the process ends.  Calls on one device must not overlap on different

@@ -183,7 +183,10 @@ constexpr int kChunk = 4;  // sample rows in flight per source
 //   Sample t of a source is a positive iff t % (k_neg + 1) == 0.
 //   P: row access policy; LPG lanes per source, UPL units per lane (LPG*UPL*P::F >= d).
 //   SEQ: a single lane group walks all sources in ascending index (the sequential-order
-//   result); otherwise lane groups stride over the sources.
+//   result), with whatever policy, geometry and hot-row mode it is instantiated and called
+//   with: every address is then read and written by one lane in program order, so stores and
+//   atomic adds alike take effect in the order of Alg. 3.  Otherwise lane groups stride over
+//   the sources.
 //
 // The body is written without branches around memory reads: a sample that does not
 // exist, or a column beyond d, reads a harmless valid address and is masked afterwards
@@ -206,8 +209,8 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   const int64_t first = SEQ ? 0 : wave * kGroupsPerWave + lane / LPG;
   const int32_t d = a.d;
   const int32_t per_round = a.k_neg + 1;
-  const bool use_bitmap = !SEQ && a.hot.mode == kHotBitmap;
-  const bool all_hot = !SEQ && a.hot.mode == kHotAll;
+  const bool use_bitmap = a.hot.mode == kHotBitmap;
+  const bool all_hot = a.hot.mode == kHotAll;
   const uint32_t *const bits = a.hot.bits;  // always a readable word, also without a bitmap
 
   // Lane gl owns floats [(gl + i*LPG)*F, +F) of a row, i < UPL: consecutive lanes touch
@@ -345,11 +348,13 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 }
 
 // Launches sgd_kernel for a given dimension.  Geometry:
-//   sequential mode        plain 128-bit units, LPG = pow2ceil(d/4) lanes (<= 64)
-//   concurrent, d <= 64    64-bit agent-scope units, LPG = pow2ceil(d/2) lanes, one unit
+//   plain_rows             plain 128-bit units, LPG = pow2ceil(d/4) lanes (<= 64): the layout
+//                          of the sequential-order debug mode
+//   otherwise, d <= 64     64-bit agent-scope units, LPG = pow2ceil(d/2) lanes, one unit
 //                          per lane (2..32 sources per wavefront)
-//   concurrent, d  > 64    32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
+//   otherwise, d  > 64     32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
 //                          lanes (<= 64), four or eight units per lane
+// Each of them runs concurrently (seq = false) or as one lane group (seq = true).
 // `a.active_waves` is filled in here from `count`.
 template <class W>
 struct SgdLauncher {
@@ -381,7 +386,7 @@ struct SgdLauncher {
   static void launch(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
                      int64_t max_waves, hipStream_t st) {
     const int d = a.d;
-    if (seq || plain_rows) {
+    if (plain_rows) {
       if (d > 256) return run<RowPlain128, 64, 2>(w, a, count, seq, max_waves, st);
       switch (pow2_lanes(d / 4)) {
         case 64: return run<RowPlain128, 64, 1>(w, a, count, seq, max_waves, st);

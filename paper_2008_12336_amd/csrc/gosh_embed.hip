@@ -145,11 +145,21 @@ class MultilevelRun {
       }
       if (i == D - 1)
         if (int rc = init_coarsest(i)) return rc;
-      const int32_t in_place_parts = (cur_dev && pl.pair_levels) ? pair_level_parts(ls.epochs, g.n) : 0;
+      const int32_t in_place_parts = (cur_dev && pl.pair_levels)
+                                         ? gosh_pair_level_parts(ls.epochs, g.n, gosh::tuning().pair_level_min_n, kPairLevelB)
+                                         : 0;
       if (int rc = !cur_dev         ? train_by_rotation(i, ls)
                    : in_place_parts ? train_in_place(i, ls, in_place_parts)
                                     : train_on_device(i, ls))
         return rc;
+      if (cur_dev) {
+        gosh::CheckResult *result = nullptr;
+        if (int rc = gosh::check_scratch(&result)) return rc;
+        if (int rc = gosh::matrix_check_clear(result, st)) return rc;
+        if (int rc = gosh::matrix_check_add(cur_dev, g.n * d, result, st)) return rc;
+        if (int rc = gosh::matrix_check_read(result, &ls.max_abs, &ls.nonfinite, st)) return rc;
+      }
+      if (ls.nonfinite > 0 && diverged_level < 0) diverged_level = i;
       if (i > 0)
         if (int rc = project(i, ls)) return rc;
       if (stats) stats[i] = ls;
@@ -160,6 +170,9 @@ class MultilevelRun {
                "download M_0");
       GOSH_TRY_HIP(hipStreamSynchronize(st), "download M_0");
     }
+    if (diverged_level >= 0)
+      return gosh::fail(GOSH_EDIVERGED, "training diverged: the matrix of level %d holds non-finite values",
+                        diverged_level);
     return GOSH_OK;
   }
 
@@ -176,6 +189,7 @@ class MultilevelRun {
   DeviceBuffer dev_own, dev_next;
   PinnedBuffer host_own, host_next;
   float *cur_dev = nullptr, *cur_host = nullptr;
+  int diverged_level = -1;  // first (coarsest) level whose training left non-finite entries
 
   // The device-resident arrays of level i, if the hierarchy holds them on this device.
   const gosh::DeviceLevel *resident(int i) const {
@@ -270,27 +284,11 @@ class MultilevelRun {
     return GOSH_OK;
   }
 
-  // Parts for training a resident level of n vertices for `epochs` epochs with the pair
-  // scheme in place (GOSH_FLAG_PAIR_LEVELS), 0 for "use Alg. 3": the largest K of 16, 8, 4,
-  // 2, 1 whose parts keep 2^22 vertices (on smaller parts the scheme gains little or loses:
-  // 2.4 M vertices in 16 parts trained at half the rate of Alg. 3, in 2 parts a fifth
-  // slower) and whose whole rotations of B = 5 rounds overshoot the epochs by at most an
-  // eighth.
-  static int32_t pair_level_parts(int64_t epochs, int64_t n) {
-    int64_t min_n = int64_t{1} << 22;
-    if (const char *e = getenv("GOSH_PAIR_LEVEL_MIN_N")) min_n = atoll(e);  // read per call: tests set it
-    if (min_n < 1) min_n = 1;
-    for (int32_t K = 16; K >= 1; K /= 2) {
-      if (K * min_n > n) continue;
-      const int64_t per = int64_t{kPairLevelB} * K;
-      const int64_t run = (epochs + per - 1) / per * per;
-      if ((run - epochs) * 8 <= epochs) return K;
-    }
-    return 0;
-  }
-
   // The same level trained in place with the pair order and the sampling rule of Alg. 5
   // (no part moves: the matrix is on the device); the streams are the rotation's own.
+  // The part count comes from gosh_pair_level_parts: parts of at least 2^22 vertices by
+  // default, because on smaller parts the scheme gains little or loses (2.4 M vertices in 16
+  // parts trained at half the rate of Alg. 3, in 2 parts a fifth slower).
   int train_in_place(int i, gosh_level_stats &ls, int32_t K) {
     auto t0 = std::chrono::steady_clock::now();
     DeviceBuffer xadj_dev, adj_dev;
@@ -299,9 +297,9 @@ class MultilevelRun {
     ls.upload_ms = ms_since(t0);
     GOSH_TRY_HIP(hipStreamSynchronize(st), "before the rotation");
     gosh_parts_stats ps{};
-    if (int rc = gosh_train_parts(&dev, cur_dev, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed, static_cast<uint32_t>(i),
-                                  0, pl.P_gpu, 1, kPairLevelB, K, pl.parts_flags, &ps))
-      return rc;
+    const int rc = gosh_train_parts(&dev, cur_dev, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed, static_cast<uint32_t>(i),
+                                    0, pl.P_gpu, 1, kPairLevelB, K, pl.parts_flags, &ps);
+    if (rc != GOSH_OK && rc != GOSH_EDIVERGED) return rc;  // divergence is reported at the end of the run
     ls.parts_K = ps.K;
     ls.train_ms = ps.wall_ms;
     return GOSH_OK;
@@ -319,11 +317,13 @@ class MultilevelRun {
       return rc;
     }
     gosh_parts_stats ps{};
-    if (int rc = gosh_train_parts(&g, cur_host, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed, static_cast<uint32_t>(i),
-                                  pl.budget, pl.P_gpu, pl.S_gpu, pl.B, 0, pl.parts_flags, &ps))
-      return rc;
+    const int rc = gosh_train_parts(&g, cur_host, d, pl.k_neg, ls.epochs, pl.lr0, pl.seed, static_cast<uint32_t>(i),
+                                    pl.budget, pl.P_gpu, pl.S_gpu, pl.B, 0, pl.parts_flags, &ps);
+    if (rc != GOSH_OK && rc != GOSH_EDIVERGED) return rc;  // divergence is reported at the end of the run
     ls.parts_K = ps.K;
     ls.train_ms = ps.wall_ms;
+    ls.max_abs = ps.max_abs;
+    ls.nonfinite = ps.nonfinite;
     return GOSH_OK;
   }
 

@@ -88,16 +88,15 @@ int check_launch(const char *kernel) {
   return GOSH_OK;
 }
 
-static long env_long(const char *name, long fallback) {
-  const char *e = getenv(name);
-  return e ? atol(e) : fallback;
-}
+namespace {
+std::mutex g_tuning_mutex;
+constexpr gosh_tuning kDefaultTuning{0, int64_t{1} << 22, 64, 4, 0, int64_t{1} << 22};
+gosh_tuning g_tuning = kDefaultTuning;
+}  // namespace
 
-const Tuning &tuning() {
-  static const Tuning t{static_cast<int>(env_long("GOSH_ROW_POLICY", 1)),
-                        env_long("GOSH_MAX_WAVES", 1L << 22), env_long("GOSH_HOT_INV_EPS", 64),
-                        env_long("GOSH_HOT_ALL_INV_EPS", 4)};
-  return t;
+gosh_tuning tuning() {
+  std::lock_guard<std::mutex> lock(g_tuning_mutex);
+  return g_tuning;
 }
 
 int resident_waves() {
@@ -144,11 +143,66 @@ int hot_scratch(size_t bytes, void **out) {
   return GOSH_OK;
 }
 
+int check_scratch(CheckResult **out) {
+  static CheckResult *table[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(GOSH_EHIP, "cannot identify the current device");
+  std::lock_guard<std::mutex> lock(g_hot_scratch_mutex);
+  if (table[dev] == nullptr) {
+    void *p = nullptr;
+    if (hipMalloc(&p, sizeof(CheckResult)) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(GOSH_ENOMEM, "cannot allocate the result of the divergence check");
+    }
+    table[dev] = static_cast<CheckResult *>(p);
+  }
+  *out = table[dev];
+  return GOSH_OK;
+}
+
 }  // namespace gosh
 
 extern "C" {
 
 const char *gosh_last_error(void) { return gosh::g_error; }
+
+void gosh_tuning_defaults(gosh_tuning *t) {
+  if (t) *t = gosh::kDefaultTuning;
+}
+
+int gosh_set_tuning(const gosh_tuning *t) {
+  const gosh_tuning v = t ? *t : gosh::kDefaultTuning;
+  if (v.max_waves < 1) return gosh::fail(GOSH_EINVAL, "max_waves = %lld: must be positive", (long long)v.max_waves);
+  if (v.hot_inv_eps < 1) return gosh::fail(GOSH_EINVAL, "hot_inv_eps = %lld: must be positive", (long long)v.hot_inv_eps);
+  if (v.hot_all_inv_eps < 0)
+    return gosh::fail(GOSH_EINVAL, "hot_all_inv_eps = %lld: must not be negative", (long long)v.hot_all_inv_eps);
+  if (v.hot_min_degree < 0)
+    return gosh::fail(GOSH_EINVAL, "hot_min_degree = %lld: must not be negative", (long long)v.hot_min_degree);
+  if (v.pair_level_min_n < 1)
+    return gosh::fail(GOSH_EINVAL, "pair_level_min_n = %lld: must be positive", (long long)v.pair_level_min_n);
+  std::lock_guard<std::mutex> lock(gosh::g_tuning_mutex);
+  gosh::g_tuning = v;
+  return GOSH_OK;
+}
+
+int gosh_get_tuning(gosh_tuning *t) {
+  if (t == nullptr) return gosh::fail(GOSH_EINVAL, "tuning record is null");
+  *t = gosh::tuning();
+  return GOSH_OK;
+}
+
+int32_t gosh_pair_level_parts(int64_t epochs, int64_t n, int64_t min_n, int32_t B) {
+  if (epochs < 1 || n < 1 || B < 1) return 0;
+  if (min_n < 1) min_n = 1;
+  for (int32_t K = 16; K >= 1; K /= 2) {
+    if (K * min_n > n) continue;
+    const int64_t per = static_cast<int64_t>(B) * K;
+    const int64_t run = (epochs + per - 1) / per * per;
+    if ((run - epochs) * 8 <= epochs) return K;
+  }
+  return 0;
+}
 
 float gosh_lr(float lr0, int64_t j, int64_t e_i) {
   if (e_i <= 0) return 0.0f;

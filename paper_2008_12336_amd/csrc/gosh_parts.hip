@@ -226,7 +226,8 @@ int check_parts_args(const gosh_csr *g, const float *M, int32_t d, int32_t k_neg
   if (P < 2 || P > 64) return gosh::fail(GOSH_EINVAL, "P_gpu = %d: must be in [2, 64]", P);
   if (S < 1 || S > 64) return gosh::fail(GOSH_EINVAL, "S_gpu = %d: must be in [1, 64]", S);
   if (B < 1 || B > 64) return gosh::fail(GOSH_EINVAL, "B = %d: must be in [1, 64]", B);
-  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS | GOSH_FLAG_BLOCKED_ORDER))
+  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS | GOSH_FLAG_BLOCKED_ORDER |
+                GOSH_FLAG_CONCURRENT_LAYOUT))
     return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
   if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
     return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
@@ -263,7 +264,8 @@ class Rotation {
   explicit Rotation(const RotationPlan &plan)
       : pl(plan), L{plan.g->n, plan.K, (plan.g->n + plan.K - 1) / plan.K}, P(plan.P), S(plan.S), NS(plan.S + 1),
         per_round(plan.k_neg + 1), samples(plan.B * (plan.k_neg + 1)),
-        seq((plan.flags & GOSH_FLAG_SEQUENTIAL) != 0), key0(static_cast<uint32_t>(plan.seed)),
+        seq((plan.flags & GOSH_FLAG_SEQUENTIAL) != 0),
+        concurrent_paths(!seq || (plan.flags & GOSH_FLAG_CONCURRENT_LAYOUT) != 0), tune(gosh::tuning()), key0(static_cast<uint32_t>(plan.seed)),
         key1(static_cast<uint32_t>(plan.seed >> 32)), host_threads(std::max(1, omp_get_max_threads())),
         graph_on_device(gosh::is_device_pointer(plan.g->xadj)),
         pool_ints(static_cast<size_t>(2) * L.part_rows * plan.B) {
@@ -306,6 +308,7 @@ class Rotation {
     for (auto p : dpool) if (p) (void)hipFree(p);
     for (auto p : staging) if (p) (void)hipHostFree(p);
     if (hot_bits_dev) (void)hipFree(hot_bits_dev);
+    if (check) (void)hipFree(check);
     for (hipStream_t s : {compute, copy, copy_out})
       if (s) (void)hipStreamDestroy(s);
   }
@@ -350,6 +353,8 @@ class Rotation {
       GOSH_TRY_HIP(hipEventCreate(&k_begin[t]), "hipEventCreate");
       GOSH_TRY_HIP(hipEventCreate(&k_end[t]), "hipEventCreate");
     }
+    GOSH_TRY_HIP(hipMalloc(reinterpret_cast<void **>(&check), sizeof(gosh::CheckResult)), "hipMalloc check result");
+    if (int rc = gosh::matrix_check_clear(check, copy_out)) return rc;
     if (int rc = build_hot_set()) return rc;
     if (!graph_on_device) sampler = std::thread([this] { sampler_loop(); });
     return GOSH_OK;
@@ -423,6 +428,8 @@ class Rotation {
   const int32_t P, S, NS;  // slots, device pools, host staging buffers for pools
   const int32_t per_round, samples;
   const bool seq;
+  const bool concurrent_paths;  // the concurrent kernel's layout and write paths are in use
+  const gosh_tuning tune;
   const uint32_t key0, key1;
   const int host_threads;
   const bool graph_on_device;  // then it is sampled there: no sampler thread, no pool uploads
@@ -435,6 +442,7 @@ class Rotation {
   std::vector<int32_t> slot_part;
   uint32_t *hot_bits_dev = nullptr;
   gosh::HotSet hot{nullptr, gosh::kHotNone};
+  gosh::CheckResult *check = nullptr;  // divergence check, accumulated on the outbound stream
   hipStream_t compute = nullptr, copy = nullptr, copy_out = nullptr;
   std::vector<hipEvent_t> chunk_flushed, slot_ready, slot_used, pool_ready, pool_used, staging_done, k_begin, k_end;
   std::vector<char> k_pending;
@@ -458,20 +466,22 @@ class Rotation {
   // Hot rows: the degree rule evaluated once, where the graph lives.
   int build_hot_set() {
     const int64_t n = pl.g->n;
-    if (!seq) {
+    if (concurrent_paths) {
       const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(pl.d);
       const int64_t pair_sources = 2 * L.part_rows;
-      const int64_t waves = std::min<int64_t>((pair_sources + gpw - 1) / gpw, gosh::tuning().max_waves);
+      const int64_t waves = std::min<int64_t>((pair_sources + gpw - 1) / gpw, tune.max_waves);
       const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;
       // per visit a row takes about B*k_neg uniform hits plus its own turn
-      int mode = ((static_cast<int64_t>(pl.B) * pl.k_neg + 1) * in_flight * gosh::tuning().hot_all_inv_eps >
-                  pair_sources)
+      int mode = (tune.hot_min_degree == 0 &&
+                  (static_cast<int64_t>(pl.B) * pl.k_neg + 1) * in_flight * tune.hot_all_inv_eps > pair_sources)
                      ? gosh::kHotAll
                      : gosh::kHotBitmap;
       if (pl.flags & GOSH_FLAG_PLAIN_STORES) mode = gosh::kHotNone;
       if (pl.flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
       if (mode == gosh::kHotBitmap) {
-        const int64_t min_degree = pl.g->nnz / (gosh::tuning().hot_inv_eps * in_flight * pl.B) + 1;
+        const int64_t min_degree = tune.hot_min_degree > 0
+                                       ? tune.hot_min_degree
+                                       : pl.g->nnz / (tune.hot_inv_eps * in_flight * pl.B) + 1;
         const int64_t words = (n + 63) / 64;
         GOSH_TRY_HIP(hipMalloc(&hot_bits_dev, static_cast<size_t>(words) * 8), "hipMalloc hot bitmap");
         if (graph_on_device) {
@@ -596,6 +606,8 @@ class Rotation {
       // part brought in ahead of time may leave again before any kernel has used it)
       GOSH_TRY_HIP(hipStreamWaitEvent(copy_out, slot_used[victim], 0), "hipStreamWaitEvent");
       GOSH_TRY_HIP(hipStreamWaitEvent(copy_out, slot_ready[victim], 0), "hipStreamWaitEvent");
+      // the part as training leaves it, checked where it still is (read-only, ahead of the copies)
+      if (int rc = gosh::matrix_check_add(slot[victim], static_cast<int64_t>(L.size(old)) * d, check, copy_out)) return rc;
       char *slot_bytes = reinterpret_cast<char *>(slot[victim]);
       int c = 0;
       for (size_t off = 0; off < longest; off += piece, ++c) {
@@ -725,8 +737,8 @@ class Rotation {
       k_pending[timer] = 0;
     }
     GOSH_TRY_HIP(hipEventRecord(k_begin[timer], compute), "hipEventRecord");
-    gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, gosh::tuning().row_policy == 0,
-                                        gosh::tuning().max_waves, compute);
+    gosh::SgdLauncher<PairWork>::launch(w, args, w.count(), seq, tune.plain_rows != 0 || !concurrent_paths,
+                                        tune.max_waves, compute);
     if (int rc = gosh::check_launch("sgd_kernel (pair)")) return rc;
     GOSH_TRY_HIP(hipEventRecord(k_end[timer], compute), "hipEventRecord");
     k_pending[timer] = 1;
@@ -746,6 +758,7 @@ class Rotation {
       const int32_t old = slot_part[s];
       const size_t bytes = static_cast<size_t>(L.size(old)) * pl.d * 4;
       GOSH_TRY_HIP(hipStreamWaitEvent(copy_out, slot_used[s], 0), "hipStreamWaitEvent");
+      if (int rc = gosh::matrix_check_add(slot[s], static_cast<int64_t>(L.size(old)) * pl.d, check, copy_out)) return rc;
       GOSH_TRY_HIP(hipMemcpyAsync(pl.M_host + static_cast<int64_t>(L.lo(old)) * pl.d, slot[s], bytes,
                              hipMemcpyDeviceToHost, copy_out),
               "part write-back");
@@ -753,7 +766,9 @@ class Rotation {
     }
     GOSH_TRY_HIP(hipStreamSynchronize(compute), "hipStreamSynchronize");
     GOSH_TRY_HIP(hipStreamSynchronize(copy), "hipStreamSynchronize");
-    GOSH_TRY_HIP(hipStreamSynchronize(copy_out), "hipStreamSynchronize");
+    if (pl.matrix_on_device)  // every kernel is done: one pass over the matrix where it lives
+      if (int rc = gosh::matrix_check_add(pl.M_host, pl.g->n * pl.d, check, copy_out)) return rc;
+    if (int rc = gosh::matrix_check_read(check, &st.max_abs, &st.nonfinite, copy_out)) return rc;
     for (int t = 0; t < kTimers; ++t) {
       float ms = 0.f;
       if (k_pending[t] && hipEventElapsedTime(&ms, k_begin[t], k_end[t]) == hipSuccess) st.kernel_ms += ms;
@@ -907,6 +922,9 @@ int gosh_train_parts(const gosh_csr *g_host, float *M_host, int32_t d, int32_t k
   st.device_bytes = planned_bytes;
   st.wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   if (stats_out) *stats_out = st;
+  if (rc == GOSH_OK && st.nonfinite > 0)
+    return gosh::fail(GOSH_EDIVERGED, "training diverged: %lld non-finite entries met in the trained parts",
+                      (long long)st.nonfinite);
   return rc;
 }
 

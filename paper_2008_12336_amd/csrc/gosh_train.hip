@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <mutex>
 
 #include "gosh_common.h"
 #include "gosh_device.h"
@@ -171,6 +172,40 @@ __global__ __launch_bounds__(256) void row_probe_kernel(float4 *__restrict__ M, 
   }
 }
 
+// Largest finite |x| and the number of non-finite entries of `total4` float4s, accumulated
+// into *out (which the caller has cleared).  The bits of a non-negative finite float order
+// like the float, so the maximum is taken on them.
+__global__ __launch_bounds__(256) void matrix_check_kernel(const float4 *__restrict__ M, int64_t total4,
+                                                           gosh::CheckResult *__restrict__ out) {
+  uint32_t top = 0, bad = 0;
+  for (int64_t i = blockIdx.x * 256LL + threadIdx.x; i < total4; i += gridDim.x * 256LL) {
+    const float4 x = M[i];
+    const float e[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t mag = __float_as_uint(e[c]) & 0x7FFFFFFFu;
+      const bool finite = mag < 0x7F800000u;
+      top = finite ? max(top, mag) : top;
+      bad += finite ? 0u : 1u;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    top = max(top, static_cast<uint32_t>(__shfl_xor(static_cast<int>(top), off, 64)));
+    bad += static_cast<uint32_t>(__shfl_xor(static_cast<int>(bad), off, 64));
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (top) atomicMax(&out->max_bits, top);
+    if (bad) atomicAdd(&out->nonfinite, static_cast<unsigned long long>(bad));
+  }
+}
+
+__global__ void clear_check_kernel(gosh::CheckResult *out) {
+  out->max_bits = 0;
+  out->pad = 0;
+  out->nonfinite = 0;
+}
+
 int grid_for(int64_t items, int per_block, int max_blocks) {
   int64_t b = (items + per_block - 1) / per_block;
   if (b < 1) b = 1;
@@ -191,10 +226,16 @@ SamplerArgs sampler_args(const gosh_csr *g, uint64_t seed, uint32_t epoch, uint3
   return s;
 }
 
+// bits_override: the hot-row bitmap to use instead of the library's grown-on-demand scratch
+// (at least (n + 63) / 64 * 8 bytes), or null.
 template <typename OffT>
 int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr, uint64_t seed,
-                 uint32_t epoch, uint32_t level, uint32_t flags, hipStream_t st) {
+                 uint32_t epoch, uint32_t level, uint32_t flags, void *bits_override, hipStream_t st) {
   const bool seq = (flags & GOSH_FLAG_SEQUENTIAL) != 0;
+  // the write paths of the concurrent kernel: in concurrent mode, and in the sequential walk
+  // that is asked to use them
+  const bool concurrent_paths = !seq || (flags & GOSH_FLAG_CONCURRENT_LAYOUT) != 0;
+  const gosh_tuning tune = gosh::tuning();
   const int64_t n = g->n;
   EpochWork<OffT> w;
   w.s = sampler_args(g, seed, epoch, level);
@@ -206,26 +247,28 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
   a.samples = k_neg + 1;
   a.lr = lr;
   a.hot = gosh::HotSet{nullptr, gosh::kHotNone};
-  const int64_t max_waves = gosh::tuning().max_waves;
-  if (!seq) {
+  const int64_t max_waves = tune.max_waves;
+  if (concurrent_paths) {
     // Sources in flight C, and the hot-row rule.  A vertex is hot if its expected
     // positive hits per epoch, deg/avg_deg, give more than eps = 1/64 concurrent holders:
     // deg * C / nnz > eps.  On graphs so small that even the k+1 uniform touches of
     // every row overlap ((k+1)*C/n > 1/4, i.e. fewer than 16 rounds at k = 3) all rows
     // are hot.  Both constants come from link-prediction AUCROC against the sequential
-    // reference on R-MAT graphs of 2^12..2^18 vertices: with them the concurrent kernel
+    // reference on R-MAT graphs of 2^12..2^20 vertices: with them the concurrent kernel
     // stays within 0.001..0.005 of the reference, without them it drops by up to 0.4.
     const int gpw = gosh::SgdLauncher<EpochWork<OffT>>::groups_per_wave(d);
     int64_t waves = std::min<int64_t>((n + gpw - 1) / gpw, max_waves);
     const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;
-    int mode = ((k_neg + 1) * in_flight * gosh::tuning().hot_all_inv_eps > n) ? gosh::kHotAll
-                                                                             : gosh::kHotBitmap;
+    int mode = gosh::kHotBitmap;
+    if (tune.hot_min_degree == 0 && (k_neg + 1) * in_flight * tune.hot_all_inv_eps > n) mode = gosh::kHotAll;
     if (flags & GOSH_FLAG_PLAIN_STORES) mode = gosh::kHotNone;
     if (flags & GOSH_FLAG_ATOMIC_ADDS) mode = gosh::kHotAll;
     if (mode == gosh::kHotBitmap) {
-      const int64_t min_degree = g->nnz / (gosh::tuning().hot_inv_eps * in_flight) + 1;
-      void *bits = nullptr;
-      if (int rc = gosh::hot_scratch(static_cast<size_t>((n + 63) / 64) * 8, &bits)) return rc;
+      const int64_t min_degree =
+          tune.hot_min_degree > 0 ? tune.hot_min_degree : g->nnz / (tune.hot_inv_eps * in_flight) + 1;
+      void *bits = bits_override;
+      if (bits == nullptr)
+        if (int rc = gosh::hot_scratch(static_cast<size_t>((n + 63) / 64) * 8, &bits)) return rc;
       const int blocks = static_cast<int>(std::min<int64_t>(((n + 63) / 64 + 3) / 4, 1 << 16));
       hipLaunchKernelGGL(mark_hot_kernel<OffT>, dim3(blocks), dim3(256), 0, st,
                          static_cast<const OffT *>(g->xadj), n, min_degree,
@@ -237,17 +280,61 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
   }
   if (a.hot.bits == nullptr) {
     // the kernel reads word 0 of the bitmap unconditionally
-    void *bits = nullptr;
-    if (int rc = gosh::hot_scratch(8, &bits)) return rc;
+    void *bits = bits_override;
+    if (bits == nullptr)
+      if (int rc = gosh::hot_scratch(8, &bits)) return rc;
     a.hot.bits = static_cast<const uint32_t *>(bits);
   }
-  gosh::SgdLauncher<EpochWork<OffT>>::launch(w, a, n, seq, gosh::tuning().row_policy == 0, max_waves, st);
+  const bool plain_rows = tune.plain_rows != 0 || (seq && !concurrent_paths);
+  gosh::SgdLauncher<EpochWork<OffT>>::launch(w, a, n, seq, plain_rows, max_waves, st);
   return gosh::check_launch("sgd_kernel (epoch)");
+}
+
+int check_epoch_args(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg, float lr_epoch,
+                     uint32_t flags) {
+  if (int rc = gosh::check_csr(g_dev)) return rc;
+  if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
+  if (k_neg < 0 || k_neg > GOSH_MAX_NEG)
+    return gosh::fail(GOSH_EINVAL, "k_neg = %d: must be in [0, %d]", k_neg, GOSH_MAX_NEG);
+  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS | GOSH_FLAG_CONCURRENT_LAYOUT))
+    return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
+  if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
+    return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
+  if (!(lr_epoch == lr_epoch)) return gosh::fail(GOSH_EINVAL, "lr is NaN");
+  if (int rc = gosh::check_device_csr(g_dev)) return rc;
+  return gosh::check_device_span(M_dev, static_cast<size_t>(g_dev->n) * d * 4, "M");
 }
 
 }  // namespace
 
 namespace gosh {
+
+int matrix_check_clear(CheckResult *result_dev, hipStream_t st) {
+  hipLaunchKernelGGL(clear_check_kernel, dim3(1), dim3(1), 0, st, result_dev);
+  return check_launch("clear_check_kernel");
+}
+
+int matrix_check_add(const float *rows_dev, int64_t floats, CheckResult *result_dev, hipStream_t st) {
+  const int64_t total4 = floats / 4;
+  if (total4 <= 0) return GOSH_OK;
+  hipLaunchKernelGGL(matrix_check_kernel, dim3(grid_for(total4, 1024, 1 << 13)), dim3(256), 0, st,
+                     reinterpret_cast<const float4 *>(rows_dev), total4, result_dev);
+  return check_launch("matrix_check_kernel");
+}
+
+int matrix_check_read(const CheckResult *result_dev, float *max_abs, int64_t *nonfinite, hipStream_t st) {
+  CheckResult host{};
+  GOSH_TRY_HIP(hipMemcpyAsync(&host, result_dev, sizeof(host), hipMemcpyDeviceToHost, st), "read matrix check");
+  GOSH_TRY_HIP(hipStreamSynchronize(st), "matrix check");
+  if (max_abs) {
+    float f;
+    static_assert(sizeof(f) == sizeof(host.max_bits), "fp32");
+    __builtin_memcpy(&f, &host.max_bits, 4);
+    *max_abs = f;
+  }
+  if (nonfinite) *nonfinite = static_cast<int64_t>(host.nonfinite);
+  return GOSH_OK;
+}
 
 int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, hipStream_t st) {
   if (accesses <= 0) return GOSH_OK;
@@ -301,22 +388,24 @@ int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint3
 int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg, float lr_epoch,
                      uint64_t seed, uint32_t epoch, uint32_t level, uint32_t flags,
                      void *hip_stream) {
-  if (int rc = gosh::check_csr(g_dev)) return rc;
-  if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
-  if (k_neg < 0 || k_neg > GOSH_MAX_NEG)
-    return gosh::fail(GOSH_EINVAL, "k_neg = %d: must be in [0, %d]", k_neg, GOSH_MAX_NEG);
-  if (flags & ~(GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_PLAIN_STORES | GOSH_FLAG_ATOMIC_ADDS))
-    return gosh::fail(GOSH_EINVAL, "unknown flags 0x%x", flags);
-  if ((flags & GOSH_FLAG_PLAIN_STORES) && (flags & GOSH_FLAG_ATOMIC_ADDS))
-    return gosh::fail(GOSH_EINVAL, "flags ask for plain stores and atomic adds at once");
-  if (!(lr_epoch == lr_epoch)) return gosh::fail(GOSH_EINVAL, "lr is NaN");
-  if (int rc = gosh::check_device_csr(g_dev)) return rc;
-  if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(g_dev->n) * d * 4, "M")) return rc;
-
+  if (int rc = check_epoch_args(g_dev, M_dev, d, k_neg, lr_epoch, flags)) return rc;
   hipStream_t st = gosh::as_stream(hip_stream);
   if (g_dev->xadj_is64)
-    return launch_epoch<int64_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, st);
-  return launch_epoch<int32_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, st);
+    return launch_epoch<int64_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, nullptr, st);
+  return launch_epoch<int32_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, nullptr, st);
+}
+
+int gosh_matrix_check(const float *M_dev, int64_t n, int32_t d, float *max_abs, int64_t *nonfinite,
+                      void *hip_stream) {
+  if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
+  if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
+  if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(n) * d * 4, "M")) return rc;
+  hipStream_t st = gosh::as_stream(hip_stream);
+  gosh::CheckResult *result = nullptr;
+  if (int rc = gosh::check_scratch(&result)) return rc;
+  if (int rc = gosh::matrix_check_clear(result, st)) return rc;
+  if (int rc = gosh::matrix_check_add(M_dev, n * d, result, st)) return rc;
+  return gosh::matrix_check_read(result, max_abs, nonfinite, st);
 }
 
 int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, void *hip_stream) {

@@ -171,19 +171,30 @@ def test_cxx_example_embeds_through_the_c_abi_alone():
     assert "mean dot over edges" in run.stdout
 
 
+@pytest.fixture
+def small_pair_levels():
+    """Lowers the smallest part of GOSH_FLAG_PAIR_LEVELS to 300 vertices for one test."""
+    G.gosh_set_tuning(pair_level_min_n=300)
+    yield 300
+    G.gosh_set_tuning()
+
+
 @pytest.mark.parametrize("host_matrix", [False, True])
-def test_pair_levels_vcycle_matches_the_oracle(host_matrix, monkeypatch):
-    """GOSH_FLAG_PAIR_LEVELS: resident levels above a size (lowered here through the
-    environment) train in place with Alg. 5, K by the rule the oracle states; the sequential
-    V-cycle must match the oracle's composition level by level."""
-    monkeypatch.setenv("GOSH_PAIR_LEVEL_MIN_N", "300")
+def test_pair_levels_vcycle_matches_the_oracle(host_matrix, small_pair_levels):
+    """GOSH_FLAG_PAIR_LEVELS: resident levels above a size (lowered here through the tuning
+    record) train in place with Alg. 5, on the part counts the library's rule gives (its own
+    unit test: tests/test_parts_host.py); the oracle is handed those counts, and the
+    sequential V-cycle must match its composition level by level."""
     n, d, k, epochs = 3000, 32, 3, 260
     c = graphgen.to_csr(n, graphgen.chung_lu(n, 24000, 4))
     xadj, adj = c.xadj.numpy(), c.adj.numpy()
-    want, graphs, maps, e_i = O.embed(xadj, adj, d, k, epochs, 0.3, 0.05, 5, threshold=100, min_shrink=0.8,
-                                      pair_levels_min_n=300)
-    want_K = [O.pair_level_parts(int(e_i[i]), graphs[i][0].size - 1, 300) for i in range(len(graphs))]
+    graphs, _, _ = O.coarsen(xadj, adj, threshold=100, min_shrink=0.8)
+    e_i = O.epoch_split(epochs, 0.3, len(graphs))
+    want_K = [G.gosh_pair_level_parts(int(e_i[i]), graphs[i][0].size - 1, small_pair_levels)
+              for i in range(len(graphs))]
     assert any(want_K) and not all(want_K), want_K  # both kinds of level occur
+    want, graphs, maps, e_i = O.embed(xadj, adj, d, k, epochs, 0.3, 0.05, 5, threshold=100, min_shrink=0.8,
+                                      parts_K=want_K)
     h = G.gosh_coarsen_device(n, c.xadj, c.adj, threshold=100, min_shrink=0.8)
     flags = G.GOSH_FLAG_SEQUENTIAL | G.GOSH_FLAG_PAIR_LEVELS
     if host_matrix:

@@ -155,33 +155,3 @@ def test_blocked_rotation_differs_only_in_order():
     O.train_parts(xadj, adj, c2, 2, 40, 0.05, 2, 0, 4, 5, block=2)
     assert np.array_equal(a, b)
     assert not np.array_equal(a, c2) and np.isfinite(c2).all()
-
-
-def test_pair_level_rule():
-    """The rule by which the multilevel drivers may train a resident level with Alg. 5 in
-    place: largest K of 16, 8, 4, 2, 1 whose parts keep min_n vertices and whose whole
-    rotations (B = 5) overshoot the level's epochs by at most an eighth; epochs that no K
-    fits, and levels below min_n, keep Alg. 3."""
-    unit = 1 << 20
-    big = 16 * unit
-    assert O.pair_level_parts(80, big, unit) == 16      # one rotation of 16 parts, exactly
-    assert O.pair_level_parts(85, big, unit) == 2       # 16 -> 160, 8 -> 120, 4 -> 100; 2 -> 90 (5 over, <= 10)
-    assert O.pair_level_parts(48, big, unit) == 2       # 16, 8 -> 80; 4 -> 60; 2 -> 50 (2 over, <= 6)
-    assert O.pair_level_parts(10, big, unit) == 2
-    assert O.pair_level_parts(8, big, unit) == 0        # K = 1 runs 10: 2 over, more than 8 / 8
-    assert O.pair_level_parts(1000, big, unit) == 16    # 13 rotations = 1040: 40 over, <= 125
-    assert O.pair_level_parts(80, big - 1, unit) == 8   # 16 parts would fall below 2^20 vertices
-    assert O.pair_level_parts(80, 2 * unit, unit) == 2  # 80 epochs = 8 rotations of 2 parts
-    assert O.pair_level_parts(80, unit - 1, unit) == 0  # level too small for even one part
-    assert O.pair_level_parts(80, 3, 1) == 2            # never more parts than vertices
-    for e in range(1, 400):
-        for n in (unit, 5 * unit, big):
-            K = O.pair_level_parts(e, n, unit)
-            if K:
-                assert K * unit <= n
-                run = -(-e // (5 * K)) * 5 * K
-                assert (run - e) * 8 <= e
-            for larger in (16, 8, 4, 2, 1):
-                if larger > K and larger * unit <= n:
-                    over = -(-e // (5 * larger)) * 5 * larger - e
-                    assert over * 8 > e

@@ -1,7 +1,5 @@
 """Pins for the oracle's random draws and index mapping (no GPU)."""
-import os
 import random
-import subprocess
 
 import numpy as np
 import pytest
@@ -9,28 +7,6 @@ import scipy.stats
 
 from oracle import gosh_oracle as O
 from tests.util import csr_from_pairs
-
-HERE = os.path.dirname(os.path.abspath(__file__))
-
-
-@pytest.fixture(scope="module")
-def aten_philox(tmp_path_factory):
-    """Independent Philox4x32-10: ATen's header-only engine compiled into a tiny CLI."""
-    import torch
-
-    inc = os.path.join(os.path.dirname(torch.__file__), "include")
-    exe = str(tmp_path_factory.mktemp("pin") / "pin_philox_aten")
-    subprocess.run(["g++", "-std=c++17", "-O1", "-I" + inc,
-                    os.path.join(HERE, "pin_philox_aten.cpp"), "-o", exe], check=True)
-
-    def run(triples):
-        text = "".join(f"{s} {q} {o}\n" for s, q, o in triples)
-        out = subprocess.run([exe], input=text, capture_output=True, text=True, check=True)
-        rows = [list(map(int, line.split())) for line in out.stdout.strip().splitlines()]
-        assert len(rows) == len(triples)
-        return rows
-
-    return run
 
 
 def test_philox_matches_independent_engine(aten_philox):
