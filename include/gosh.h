@@ -275,6 +275,21 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
                      float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
                      uint32_t flags, void *hip_stream);
 
+/* gosh_train_epoch for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same epoch with the
+ * same arguments, results and error behaviour, except that the hot-row bitmap -- the one
+ * buffer gosh_train_epoch allocates (on first use, and again when a larger graph comes) --
+ * lives in a fixed array inside the library's code object: GOSH_STATIC_MAX_N bits = 8 MiB of
+ * device memory on every GPU the library is loaded on, held until the process ends.  The
+ * call allocates and frees nothing, on the device or the host, and takes graphs of at most
+ * GOSH_STATIC_MAX_N vertices (GOSH_EINVAL beyond).  The bitmap is rewritten by every call
+ * that uses it (nothing of a previous call is relied on), and all calls on one GPU share it:
+ * calls that overlap on one GPU -- different streams, or threads -- race on it. */
+#define GOSH_STATIC_MAX_N 67108864 /* 2^26 vertices */
+int gosh_train_epoch_static(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg,
+                            float lr_epoch, uint64_t seed, uint32_t epoch, uint32_t level,
+                            uint32_t flags, void *hip_stream);
+
 /* Divergence check (no passage of the paper: nothing in Alg. 1 bounds a row, and a learning
  * rate too large for a graph's hubs makes rows grow until fp32 overflows; the training calls
  * themselves are asynchronous and cannot tell).  Reads the n x d device matrix once and

@@ -24,6 +24,7 @@ GOSH_FLAG_CONCURRENT_LAYOUT = 64
 GOSH_EDIVERGED = -5
 GOSH_MAX_DIM = 512
 GOSH_MAX_NEG = 15
+GOSH_STATIC_MAX_N = 1 << 26
 
 
 class GoshError(RuntimeError):
@@ -97,6 +98,9 @@ EXPORTS = {
     "gosh_train_epoch": (C.c_int, [C.POINTER(gosh_csr), C.c_void_p, C.c_int32, C.c_int32,
                                    C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.c_void_p]),
+    "gosh_train_epoch_static": (C.c_int, [C.POINTER(gosh_csr), C.c_void_p, C.c_int32, C.c_int32,
+                                          C.c_float, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
+                                          C.c_void_p]),
     "gosh_embed": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_double, C.c_float,
                              C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p,
                              C.POINTER(gosh_level_stats), C.c_void_p]),
@@ -244,6 +248,16 @@ def gosh_train_epoch(g: gosh_csr, M: torch.Tensor, k_neg: int, lr_epoch: float, 
         raise ValueError("M must have one row per vertex")
     _check(lib().gosh_train_epoch(C.byref(g), ptr, d, k_neg, lr_epoch, seed, epoch, level, flags,
                                   _stream(stream)))
+
+
+def gosh_train_epoch_static(g: gosh_csr, M: torch.Tensor, k_neg: int, lr_epoch: float, seed: int,
+                            epoch: int, level: int = 0, flags: int = 0, stream=None) -> None:
+    """gosh_train_epoch without any allocation (fixed in-library bitmap, n <= 2^26)."""
+    ptr, n, d = _matrix(M, "M")
+    if n != g.n:
+        raise ValueError("M must have one row per vertex")
+    _check(lib().gosh_train_epoch_static(C.byref(g), ptr, d, k_neg, lr_epoch, seed, epoch, level, flags,
+                                         _stream(stream)))
 
 
 def gosh_project(M_coarse: torch.Tensor, map_: torch.Tensor, M_fine: torch.Tensor,

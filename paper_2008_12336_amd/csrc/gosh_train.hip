@@ -290,6 +290,32 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
   return gosh::check_launch("sgd_kernel (epoch)");
 }
 
+// Hot-row bitmap of gosh_train_epoch_static: one bit per vertex, in the code object itself.
+// Host code must not use this name as an address (on the host it is a stand-in, not device
+// memory): static_bitmap() asks the runtime for the array's address on the current device.
+static __device__ __align__(256) unsigned long long scratch[GOSH_STATIC_MAX_N / 64];
+
+int static_bitmap(void **out) {
+  constexpr int kMaxDevices = 64;
+  static void *address[kMaxDevices] = {};  // every device holds its own copy of the array
+  static std::mutex mutex;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return gosh::fail(GOSH_EHIP, "cannot identify the current device");
+  std::lock_guard<std::mutex> lock(mutex);
+  if (address[dev] == nullptr) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return gosh::fail(GOSH_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    }
+    address[dev] = p;
+  }
+  *out = address[dev];
+  return GOSH_OK;
+}
+
 int check_epoch_args(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg, float lr_epoch,
                      uint32_t flags) {
   if (int rc = gosh::check_csr(g_dev)) return rc;
@@ -393,6 +419,21 @@ int gosh_train_epoch(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_n
   if (g_dev->xadj_is64)
     return launch_epoch<int64_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, nullptr, st);
   return launch_epoch<int32_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, nullptr, st);
+}
+
+int gosh_train_epoch_static(const gosh_csr *g_dev, float *M_dev, int32_t d, int32_t k_neg, float lr_epoch,
+                            uint64_t seed, uint32_t epoch, uint32_t level, uint32_t flags,
+                            void *hip_stream) {
+  if (g_dev != nullptr && g_dev->n > GOSH_STATIC_MAX_N)
+    return gosh::fail(GOSH_EINVAL, "n = %lld: gosh_train_epoch_static takes at most %lld vertices (use gosh_train_epoch)",
+                      (long long)g_dev->n, (long long)GOSH_STATIC_MAX_N);
+  if (int rc = check_epoch_args(g_dev, M_dev, d, k_neg, lr_epoch, flags)) return rc;
+  void *bits = nullptr;
+  if (int rc = static_bitmap(&bits)) return rc;
+  hipStream_t st = gosh::as_stream(hip_stream);
+  if (g_dev->xadj_is64)
+    return launch_epoch<int64_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, bits, st);
+  return launch_epoch<int32_t>(g_dev, M_dev, d, k_neg, lr_epoch, seed, epoch, level, flags, bits, st);
 }
 
 int gosh_matrix_check(const float *M_dev, int64_t n, int32_t d, float *max_abs, int64_t *nonfinite,
