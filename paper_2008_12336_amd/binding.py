@@ -28,9 +28,13 @@ GOSH_STATIC_MAX_N = 1 << 26
 
 
 class GoshError(RuntimeError):
-    def __init__(self, code: int, message: str):
+    """A negative status of the library.  `stats` carries the statistics the call filled in
+    before it failed (GOSH_EDIVERGED: all of them), else None."""
+
+    def __init__(self, code: int, message: str, stats=None):
         super().__init__(f"libgosh error {code}: {message}")
         self.code = code
+        self.stats = stats
 
 
 class gosh_csr(C.Structure):
@@ -148,9 +152,9 @@ def lib() -> C.CDLL:
     return _lib
 
 
-def _check(rc: int) -> None:
+def _check(rc: int, stats=None) -> None:
     if rc != 0:
-        raise GoshError(rc, lib().gosh_last_error().decode())
+        raise GoshError(rc, lib().gosh_last_error().decode(), stats() if (stats and rc == GOSH_EDIVERGED) else None)
 
 
 def _stream(stream) -> int:
@@ -459,7 +463,7 @@ def gosh_embed(h: Hierarchy, M0: torch.Tensor, k_neg: int, epochs: int, p: float
     D = h.levels
     stats = (gosh_level_stats * D)()
     _check(lib().gosh_embed(h.handle, d, k_neg, epochs, p, lr0, seed, flags, device_budget_bytes,
-                            ptr, stats, _stream(stream)))
+                            ptr, stats, _stream(stream)), lambda: _level_stats(stats))
     return _level_stats(stats)
 
 
@@ -482,7 +486,8 @@ def gosh_embed_host(h: Hierarchy, M0_host: torch.Tensor, k_neg: int, epochs: int
     D = h.levels
     stats = (gosh_level_stats * D)()
     _check(lib().gosh_embed_host(h.handle, d, k_neg, epochs, p, lr0, seed, flags,
-                                 device_budget_bytes, P_gpu, S_gpu, B, ptr, stats, _stream(stream)))
+                                 device_budget_bytes, P_gpu, S_gpu, B, ptr, stats, _stream(stream)),
+           lambda: _level_stats(stats))
     return _level_stats(stats)
 
 
@@ -548,6 +553,7 @@ def gosh_train_parts(n: int, xadj: torch.Tensor, adj: torch.Tensor, M_host: torc
     if rows != n:
         raise ValueError("M_host must have one row per vertex")
     st = gosh_parts_stats()
+    as_dict = lambda: {name: getattr(st, name) for name, _ in gosh_parts_stats._fields_}
     _check(lib().gosh_train_parts(C.byref(g), ptr, d, k_neg, epochs, lr0, seed, level,
-                                  device_budget_bytes, P_gpu, S_gpu, B, force_K, flags, C.byref(st)))
-    return {name: getattr(st, name) for name, _ in gosh_parts_stats._fields_}
+                                  device_budget_bytes, P_gpu, S_gpu, B, force_K, flags, C.byref(st)), as_dict)
+    return as_dict()
