@@ -9,7 +9,7 @@ import graphgen
 import paper_2008_12336_amd as G
 from oracle import gosh_oracle as O
 from tests.linkpred import aucroc, make_eval_sets
-from tests.util import rel_err
+from tests.util import conditioned_bar, oracle_sensitivity, rel_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -81,6 +81,32 @@ def test_sequential_rotation_matches_oracle(n, d, K, P, S, B, k, epochs):
     assert st["bytes_d2h"] >= part_bytes and st["bytes_h2d"] >= part_bytes
     if K <= P:
         assert st["bytes_d2h"] == part_bytes  # everything stays resident until the end
+
+
+@pytest.mark.parametrize("scale", [2.0, 1.0, 0.6])
+def test_the_randomised_case_that_missed_the_bar(scale):
+    """Chung-Lu, 1,000 vertices, d = 512, k = 5, K = 9, P = 3, S = 3, B = 4, 76 epochs, host
+    graph, paper order: at scale 2 (rows uniform in [-1, 1)) a randomised sweep found the
+    sequential rotation 4.8e-4 from the oracle.  The run is ill-conditioned there in the
+    oracle itself (tests/test_fp32_model.py): the bar is eight times the oracle's own
+    sensitivity to a one-ulp change of its input.  The same case from rows scaled to 1 or
+    0.6 is well-conditioned and meets 1e-5 -- same graph, parts, swaps and pools, so slots,
+    write-backs and ordering are not what differs."""
+    n, d, k, K, P, S, B, epochs, seed, level = 1000, 512, 5, 9, 3, 3, 4, 76, 779413867887070026, 244
+    c = graphgen.to_csr(n, graphgen.chung_lu(n, 5690, 26))
+    xadj, adj = c.xadj.numpy().astype(np.int64), c.adj.numpy()
+    R0 = (O.init_embedding(n, d, seed, 1).astype(np.float64) * d * scale).astype(np.float32)
+    want, sens = oracle_sensitivity(lambda X: O.train_parts(xadj, adj, X, k, epochs, 0.1, seed, level, K, B), R0)
+    bar = conditioned_bar(sens)
+    M = torch.from_numpy(R0.copy()).pin_memory()
+    st = G.gosh_train_parts(n, c.xadj, c.adj, M, k, epochs, 0.1, seed, level=level, P_gpu=P, S_gpu=S, B=B,
+                            force_K=K, flags=G.GOSH_FLAG_SEQUENTIAL)
+    err = rel_err(M.numpy(), want)
+    say(f"[case 445] scale={scale}: oracle sensitivity {sens:.2e}, bar {bar:.2e}, gpu vs oracle {err:.2e}, "
+        f"visits {st['pair_visits']}")
+    assert st["pair_visits"] == 3 * 45
+    assert (bar == 1e-5) == (scale < 2.0)
+    assert err <= bar
 
 
 def test_unpinned_host_matrix_and_forced_split():

@@ -10,7 +10,7 @@ import torch
 import graphgen
 import paper_2008_12336_amd as G
 from oracle import gosh_oracle as O
-from tests.util import rel_err
+from tests.util import conditioned_bar, oracle_sensitivity, rel_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -81,28 +81,40 @@ def test_random_cases_match_the_oracle(sweep_seed):
             h = G.gosh_coarsen_device(n, xd, ad, threshold=thr, min_shrink=shrink)
             assert h.levels == len(graphs)
             for i in range(h.levels - 1):
-                assert np.array_equal(h.map(i), maps[i])
+                got_map = h.map(i)
+                if got_map.shape != maps[i].shape or not np.array_equal(got_map, maps[i]):
+                    # say which side moved: the oracle asked again, and the host coarsening
+                    again = O.coarsen(xadj, adj, thr, shrink)[1]
+                    host = G.gosh_coarsen(n, c.xadj, c.adj, threshold=thr, min_shrink=shrink)
+                    raise AssertionError(
+                        f"map {i} of {h.levels - 1} differs (threshold {thr}, shrink {shrink}):\n device {got_map.tolist()}\n"
+                        f" oracle {maps[i].tolist()}\n oracle asked again {again[i].tolist()}\n"
+                        f" host coarsening {host.map(i).tolist()}")
             Mv = torch.zeros(n, dd, dtype=torch.float32, device=DEV)
             G.gosh_embed(h, Mv, kk, epochs, 0.3, 0.05, seed, flags=G.GOSH_FLAG_SEQUENTIAL)
             torch.cuda.synchronize()
             assert rel_err(Mv.cpu().numpy(), want_m0) <= 1e-5
             h.free()
 
-        # Alg. 5: a sequential rotation (rounding differences add up over the hundreds of
-        # updates a row takes per rotation, so the rows start smaller than above)
+        # Alg. 5: a sequential rotation from rows of the full range of magnitudes.  Where the
+        # drawn rows are so long that the run is ill-conditioned in the oracle itself (it
+        # cannot repeat its own result from an input one ulp away), the bar follows that
+        # measured sensitivity; everywhere else it is 1e-5.
         if n >= 2:
             K, P, S = int(rng.integers(1, min(n, 9) + 1)), int(rng.integers(2, 7)), int(rng.integers(1, 4))
             B = int(rng.integers(1, 5))
             ep = int(rng.integers(1, 3 * B * K + 1))
             blocked, on_device = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
-            print(f"   rotation K={K} P={P} S={S} B={B} epochs={ep} blocked={blocked} device_graph={on_device}",
-                  flush=True)
-            R0 = (O.init_embedding(n, d, seed, 1).astype(np.float64) * d * min(scale, 1.0)).astype(np.float32)
-            want = R0.copy()
-            O.train_parts(xadj, adj, want, kk, ep, 0.1, seed, level, K, B,
-                          block=O.blocked_block_size(P, K) if blocked else 0)
+            R0 = (O.init_embedding(n, d, seed, 1).astype(np.float64) * d * scale).astype(np.float32)
+            block = O.blocked_block_size(P, K) if blocked else 0
+            want, sens = oracle_sensitivity(
+                lambda X: O.train_parts(xadj, adj, X, kk, ep, 0.1, seed, level, K, B, block=block), R0)
+            bar = conditioned_bar(sens)
+            print(f"   rotation K={K} P={P} S={S} B={B} epochs={ep} blocked={blocked} device_graph={on_device} "
+                  f"scale={scale} oracle sensitivity={sens:.1e} bar={bar:.1e}", flush=True)
             Mp = torch.from_numpy(R0.copy()).pin_memory()
             G.gosh_train_parts(n, xd if on_device else c.xadj, ad if on_device else c.adj, Mp, kk, ep, 0.1, seed,
                                level=level, P_gpu=P, S_gpu=S, B=B, force_K=K,
                                flags=G.GOSH_FLAG_SEQUENTIAL | (G.GOSH_FLAG_BLOCKED_ORDER if blocked else 0))
-            assert rel_err(Mp.numpy(), want) <= 1e-5
+            err = rel_err(Mp.numpy(), want)
+            assert err <= bar, (err, bar, sens)

@@ -70,3 +70,33 @@ def corrupt(c, offsets64, seed, stray=0):
     for j in rng.choice(nnz, size=stray, replace=False):
         adj[j] = rng.integers(0, n)
     return xadj, adj, touched
+
+
+def one_ulp_away(M, seed=0):
+    """A copy of the fp32 matrix with every entry moved to a neighbouring fp32 value."""
+    rng = np.random.default_rng(seed)
+    toward = np.where(rng.integers(0, 2, M.shape) == 1, np.float32(np.inf), np.float32(-np.inf)).astype(np.float32)
+    return np.nextafter(M, toward)
+
+
+def oracle_sensitivity(run, M0):
+    """How far the oracle's own result moves (max |diff| / max |M|) when every entry of its
+    input moves by one unit in the last place.  `run(M)` trains M in place with the oracle.
+    A stable run returns about 1e-6 (ten or so times the perturbation); a run whose rows are
+    so long that lr * |row|^2 / 4 exceeds 1 takes SGD steps larger than the curvature of the
+    logistic loss allows and amplifies any difference by orders of magnitude -- there the
+    oracle's value is one of many equally good ones, and no implementation that rounds
+    differently can match it to 1e-5."""
+    a, b = M0.copy(), one_ulp_away(M0)
+    run(a)
+    run(b)
+    return a, rel_err(b, a)
+
+
+def conditioned_bar(sensitivity):
+    """Sequential-order bar for one run: 1e-5 relative (the kernel's fp32 dot product, fp32
+    sigmoid and fused axpys differ from the oracle's fp64 arithmetic by a few units of 2^-24
+    per update); for a run that the oracle itself cannot repeat to 1e-6 from an input moved by
+    one ulp, eight times that sensitivity -- the kernel's differences enter at every update,
+    not once at the start."""
+    return max(1e-5, 8.0 * float(sensitivity))
