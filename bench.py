@@ -221,6 +221,77 @@ def run_parts(args, w, csr, n, n_edges, t_graph) -> int:
     return 0
 
 
+def run_probe(args, w, n) -> int:
+    """What the memory system allows a kernel that moves rows of 4*d bytes at random: the
+    library's row probe (gosh_row_probe: the kernels' traffic without their arithmetic) in its
+    four modes, on a matrix in an allocation of its own and on a placed one, beside a plain
+    streaming copy of the same matrix.  No graph is involved."""
+    import numpy as np
+    import torch
+
+    import paper_2008_12336_amd as G
+
+    d = w["d"]
+    row = 4 * d
+    modes = [("read_write", G.GOSH_PROBE_READ_WRITE, 2, 4 * n), ("read", G.GOSH_PROBE_READ, 1, 8 * n),
+             ("epoch_mix", G.GOSH_PROBE_EPOCH_MIX, 10, n), ("write", G.GOSH_PROBE_WRITE, 1, 8 * n)]
+    results = {}
+    windows = [("plain", None)]
+    if args.placement == "search":
+        windows.append(("placed", None))
+    for where, _ in windows:
+        placement = {"mode": "plain"}
+        if where == "placed":
+            from paper_2008_12336_amd.placement import place_matrix
+
+            M, placement = place_matrix(n, d)
+            settle_after_placement(placement)
+        else:
+            M = torch.empty(n, d, dtype=torch.float32, device="cuda:0")
+        G.gosh_init_embedding(M, args.seed, 0)
+        torch.cuda.synchronize()
+        res = {"placement": placement}
+        for name, mode, transfers, accesses in modes:
+            ms = []
+            for rep in range(args.warmup + args.steps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                G.gosh_row_probe(M, accesses, seed=args.seed + rep, mode=mode)
+                b.record()
+                torch.cuda.synchronize()
+                if rep >= args.warmup:
+                    ms.append(a.elapsed_time(b))
+            med = float(np.median(ms))
+            res[name] = {"ms": med, "accesses": accesses, "row_transfers_per_access": transfers,
+                         "GBps": accesses * transfers * row / med / 1e6,
+                         "G_rows_per_s": accesses * transfers / med / 1e6}
+        if where == "plain":
+            other = torch.empty_like(M)
+            ms = []
+            for rep in range(args.warmup + args.steps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                other.copy_(M)
+                b.record()
+                torch.cuda.synchronize()
+                if rep >= args.warmup:
+                    ms.append(a.elapsed_time(b))
+            med = float(np.median(ms))
+            res["streaming_copy"] = {"ms": med, "GBps": 2 * n * row / med / 1e6}
+            del other
+        results[where] = res
+        if where == "placed" and placement.get("mode") == "search":
+            G.gosh_matrix_release(M)
+        del M
+    out = {"metric": "row probe: random row traffic without arithmetic", "unit": "GB/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"row_probe_n{n}_d{d}", "n": n, "d": d, "row_bytes": row,
+                      "matrix_bytes": n * row},
+           "peak_GBps": HBM_PEAK_GBPS, "probe": results}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,10 +302,12 @@ def main() -> int:
     ap.add_argument("--log2m", type=int, default=None, help="override edge draws (scaled runs)")
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--mode", default="epoch", choices=["epoch", "levels", "parts"],
+    ap.add_argument("--mode", default="epoch", choices=["epoch", "levels", "parts", "probe"],
                     help="epoch: the epoch kernel on one graph (the headline number); levels: "
                          "coarsening + multilevel training with per-level rates; parts: one "
-                         "rotation of the part-pair scheme under a device budget")
+                         "rotation of the part-pair scheme under a device budget; probe: the "
+                         "library's row probe on a matrix of the workload's shape (no graph): "
+                         "what the memory system allows random row traffic of 4*d bytes")
     ap.add_argument("--coarsen", default="device", choices=["device", "host"],
                     help="--mode levels: where the coarse graphs are rebuilt")
     ap.add_argument("--graph", default="host", choices=["host", "device"],
@@ -288,6 +361,8 @@ def main() -> int:
     m = w["m"] if "m" in w and args.log2m is None else 1 << w["log2m"]
     d, k = w["d"], w["k"]
     dev = "cuda:0"
+    if args.mode == "probe":
+        return run_probe(args, w, n)
 
     t0 = time.time()
     if w["gen"] == "chung_lu":

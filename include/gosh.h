@@ -299,15 +299,26 @@ int gosh_train_epoch_static(const gosh_csr *g_dev, float *M_dev, int32_t d, int3
 int gosh_matrix_check(const float *M_dev, int64_t n, int32_t d, float *max_abs, int64_t *nonfinite,
                       void *hip_stream);
 
-/* Placement probe (no passage of the paper: the memory of the device, not the method).
- * Reads `accesses` uniformly random rows of the n x d device matrix and writes each back
- * unchanged (zero is added to one element), one wavefront per row: the row traffic of the
- * training kernels without their arithmetic.  The caller times it (HIP events on the
- * stream) to compare candidate locations for a matrix: on this device random row traffic
- * inside one of the three HBM ranks is slower than traffic that spans two (see
- * gosh_train_epoch).  The matrix keeps its values, provided nothing else writes it
- * meanwhile.  Asynchronous on the stream. */
-int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed,
+/* Row probe (no passage of the paper: the memory of the device, not the method): the row
+ * traffic of the training kernels without their arithmetic, to be timed by the caller (HIP
+ * events on the stream) -- to compare candidate locations for a matrix (on this device
+ * random row traffic inside one of the three HBM ranks is slower than traffic that spans
+ * two, see gosh_train_epoch), and to measure what the memory system allows a kernel that
+ * moves rows of 4*d bytes at random.  A lane group of pow2ceil(d/4) lanes moves one row with
+ * 128-bit accesses.  `accesses` units of work, drawn with Philox from `seed`:
+ *   GOSH_PROBE_READ_WRITE  a uniformly random row is read and written back unchanged
+ *   GOSH_PROBE_READ        a uniformly random row is read
+ *   GOSH_PROBE_WRITE       a uniformly random row is overwritten with zeros
+ *   GOSH_PROBE_EPOCH_MIX   the traffic of one source of Alg. 3 with three negatives: row
+ *                          (i mod n) and four random rows are read, then all five written
+ *                          back unchanged (5 + 5 row transfers per access)
+ * Except in GOSH_PROBE_WRITE mode the matrix keeps its values, provided nothing else writes
+ * it meanwhile.  Asynchronous on the stream. */
+#define GOSH_PROBE_READ_WRITE 0
+#define GOSH_PROBE_READ 1
+#define GOSH_PROBE_WRITE 2
+#define GOSH_PROBE_EPOCH_MIX 3
+int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, int32_t mode,
                    void *hip_stream);
 
 /* What gosh_matrix_place found (all sizes in bytes). */

@@ -126,7 +126,8 @@ EXPORTS = {
                                   C.c_void_p, C.POINTER(gosh_level_stats), C.c_void_p]),
     "gosh_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                C.c_void_p, C.c_void_p]),
-    "gosh_row_probe": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_void_p]),
+    "gosh_row_probe": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_int32,
+                                 C.c_void_p]),
     "gosh_matrix_place": (C.c_int, [C.c_int64, C.c_int32, C.c_uint64, C.POINTER(C.c_void_p),
                                     C.POINTER(gosh_placement_info)]),
     "gosh_matrix_release": (C.c_int, [C.c_void_p]),
@@ -273,10 +274,15 @@ def gosh_project(M_coarse: torch.Tensor, map_: torch.Tensor, M_fine: torch.Tenso
     _check(lib().gosh_project(cptr, nc, map_.data_ptr(), nf, d, fptr, _stream(stream)))
 
 
-def gosh_row_probe(M: torch.Tensor, accesses: int, seed: int = 1, stream=None) -> None:
-    """Random row read-write-backs over M (values unchanged); time it to compare locations."""
+GOSH_PROBE_READ_WRITE, GOSH_PROBE_READ, GOSH_PROBE_WRITE, GOSH_PROBE_EPOCH_MIX = 0, 1, 2, 3
+
+
+def gosh_row_probe(M: torch.Tensor, accesses: int, seed: int = 1, mode: int = GOSH_PROBE_READ_WRITE,
+                   stream=None) -> None:
+    """Random row traffic over M without arithmetic (values unchanged except in write mode);
+    time it to compare locations or to measure what the memory system allows."""
     ptr, n, d = _matrix(M, "M")
-    _check(lib().gosh_row_probe(ptr, n, d, accesses, seed, _stream(stream)))
+    _check(lib().gosh_row_probe(ptr, n, d, accesses, seed, mode, _stream(stream)))
 
 
 class _DeviceArray:

@@ -56,7 +56,7 @@ int init_rows(float *rows_dev, int64_t first_row, int64_t count, int32_t d, uint
 bool inside_placed_matrix(const void *p, size_t bytes);
 
 // The launch behind gosh_row_probe, without its argument checks (the caller has made them).
-int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, hipStream_t st);
+int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, int32_t mode, hipStream_t st);
 
 // Divergence check: largest finite |entry| (as the bits of the float) and the number of
 // non-finite entries, accumulated on the device.  clear, then add any number of row ranges

@@ -168,6 +168,33 @@ struct SgdArgs {
 
 constexpr int kChunk = 4;  // sample rows in flight per source
 
+// Position of a chunk of kChunk samples in the work of one lane group: source index, first
+// sample of the chunk, and the index of the next positive sample at or after it.  All lane
+// groups of a wavefront are at the same (t0, np); only idx differs.
+struct ChunkPos {
+  int64_t idx;
+  int32_t t0, np;
+  // The chunk that follows: the next kChunk samples of the same source, or the first chunk of
+  // the group's next source.
+  __device__ __forceinline__ ChunkPos next(int32_t samples, int32_t per_round, int64_t stride) const {
+    const int32_t end = t0 + kChunk;
+    int32_t p = np;
+#pragma unroll
+    for (int q = 0; q < kChunk; ++q) p = p < end ? p + per_round : p;
+    const bool wrap = end >= samples;
+    return ChunkPos{wrap ? idx + stride : idx, wrap ? 0 : end, wrap ? 0 : p};
+  }
+  // Which of the chunk's samples are positives.
+  __device__ __forceinline__ void positives(int32_t per_round, bool (&is_pos)[kChunk]) const {
+    int32_t p = np;
+#pragma unroll
+    for (int q = 0; q < kChunk; ++q) {
+      is_pos[q] = (t0 + q == p);
+      p = is_pos[q] ? p + per_round : p;
+    }
+  }
+};
+
 // The lock-free SGD kernel.  Every source applies `samples` updates of Alg. 1 in order:
 //   g = lr * (b - sigmoid(M[src] . M[v]));  M[src] += g*M[v];  M[v] += g*M[src]
 // with the source row held in registers for its whole turn.
@@ -175,11 +202,13 @@ constexpr int kChunk = 4;  // sample rows in flight per source
 //     int64_t count()                         number of sources
 //     int32_t source_id(int64_t i)            vertex id of source i (random counter, self test)
 //     float  *source_row(int64_t i)
-//     int32_t sample(int64_t i, int32_t id, int32_t t, bool want, bool positive)
-//                                             vertex id of sample t (-1 = none, or !want);
-//                                             must be free of branches around its memory
-//                                             reads (read a safe address when !want)
+//     Pre     stage1(int64_t i, bool want)    what sampling for source i needs from memory and
+//                                             can be asked for knowing i alone (row offsets)
+//     int32_t stage2(int64_t i, int32_t id, int32_t t, bool want, bool positive, Pre)
+//                                             vertex id of sample t (-1 = none, or !want)
 //     float  *sample_row(int64_t i, int32_t v)
+//     Both stages must be free of branches around their memory reads (read a safe address
+//     when !want).
 //   Sample t of a source is a positive iff t % (k_neg + 1) == 0.
 //   P: row access policy; LPG lanes per source, UPL units per lane (LPG*UPL*P::F >= d).
 //   SEQ: a single lane group walks all sources in ascending index (the sequential-order
@@ -187,6 +216,14 @@ constexpr int kChunk = 4;  // sample rows in flight per source
 //   with: every address is then read and written by one lane in program order, so stores and
 //   atomic adds alike take effect in the order of Alg. 3.  Otherwise lane groups stride over
 //   the sources.
+//
+// Sampling is independent of the matrix (the draws are counter-based), so it runs ahead of
+// the updates as a three-stage pipeline over chunks of kChunk samples: while the rows of
+// chunk c are in flight, the neighbour-list entry (or pool entry) of chunk c+1 is requested
+// with offsets that were requested one chunk earlier, and the offsets of chunk c+2 are
+// requested.  A lane group thus waits for one memory round trip per chunk -- its rows --
+// instead of three in a row (offsets, then neighbour, then rows); for rows of a few hundred
+// bytes or less that chain, not bandwidth, is what bounds the kernel.
 //
 // The body is written without branches around memory reads: a sample that does not
 // exist, or a column beyond d, reads a harmless valid address and is masked afterwards
@@ -196,8 +233,10 @@ constexpr int kChunk = 4;  // sample rows in flight per source
 template <class P, int LPG, int UPL, class W, bool SEQ>
 __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   constexpr int kGroupsPerWave = 64 / LPG;
+  constexpr int kPasses = (kChunk + LPG - 1) / LPG;  // sampler passes per chunk (lane q takes sample q)
   constexpr int F = P::F;
   using U = Unit<F>;
+  using Pre = typename W::Pre;
   const int lane = threadIdx.x & 63;
   const int gl = lane & (LPG - 1);
   if (SEQ && (lane >= LPG || threadIdx.x >= 64 || blockIdx.x != 0)) return;
@@ -225,6 +264,38 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
     col_read[i] = col_ok[i] ? col[i] : d - F;
   }
 
+  // Stage 2 for the chunk at `pos`: lane q of the group evaluates sample pos.t0 + q (in
+  // several passes if the group has fewer than kChunk lanes).
+  auto draw_ids = [&](const ChunkPos &pos, const Pre &pre, int32_t (&mine)[kPasses]) {
+    const bool live = pos.idx < n;
+    const int64_t i = live ? pos.idx : 0;
+    const int32_t id = w.source_id(i);
+    bool is_pos[kChunk];
+    pos.positives(per_round, is_pos);
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int32_t t = pos.t0 + p * LPG + gl;
+      const bool want = live && p * LPG + gl < kChunk && t < a.samples;
+      bool mine_pos = false;
+#pragma unroll
+      for (int q = 0; q < LPG && p * LPG + q < kChunk; ++q) mine_pos = (gl == q) ? is_pos[p * LPG + q] : mine_pos;
+      mine[p] = w.stage2(i, id, want ? t : 0, want, mine_pos, pre);
+    }
+  };
+  auto offsets_for = [&](const ChunkPos &pos) {
+    const bool live = pos.idx < n;
+    return w.stage1(live ? pos.idx : 0, live);
+  };
+
+  // Pipeline prologue: the ids of the group's first chunk and the offsets of its second.
+  int32_t mine[kPasses];
+  Pre pre_next;
+  {
+    const ChunkPos c0{first, 0, 0};
+    draw_ids(c0, offsets_for(c0), mine);
+    pre_next = offsets_for(c0.next(a.samples, per_round, stride));
+  }
+
   // The loop bound is uniform over the wave; groups past the end idle inside.
   const int64_t first_of_wave = SEQ ? 0 : wave * kGroupsPerWave;
   for (int64_t base = first_of_wave; base < n; base += stride) {
@@ -244,29 +315,16 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 #pragma unroll
     for (int i = 0; i < UPL; ++i) s_before[i] = s[i];
 
-    int32_t next_positive = 0;  // sample index of the next positive (one per round)
+    ChunkPos cur{idx, 0, 0};
     for (int32_t t0 = 0; t0 < a.samples; t0 += kChunk) {
-      // Which samples of this chunk are positives (uniform over the wave).
       bool is_pos[kChunk];
-#pragma unroll
-      for (int q = 0; q < kChunk; ++q) {
-        is_pos[q] = (t0 + q == next_positive);
-        if (is_pos[q]) next_positive += per_round;
-      }
-      // Lane q of the group evaluates sample t0+q (in several passes if the group has
-      // fewer than kChunk lanes), then the ids are broadcast inside the group.
+      cur.positives(per_round, is_pos);
+      // The ids of this chunk were drawn one chunk ago; spread them over the group.
       int32_t v[kChunk];
 #pragma unroll
-      for (int p = 0; p < kChunk; p += LPG) {
-        const int32_t t = t0 + p + gl;
-        const bool want = p + gl < kChunk && t < a.samples;
-        bool mine_pos = false;
+      for (int p = 0; p < kPasses; ++p)
 #pragma unroll
-        for (int q = 0; q < LPG && p + q < kChunk; ++q) mine_pos = (gl == q) ? is_pos[p + q] : mine_pos;
-        const int32_t mine = w.sample(idx, src, want ? t : 0, want, mine_pos);
-#pragma unroll
-        for (int q = 0; q < LPG && p + q < kChunk; ++q) v[p + q] = __shfl(mine, q, LPG);
-      }
+        for (int q = 0; q < LPG && p * LPG + q < kChunk; ++q) v[p * LPG + q] = __shfl(mine[p], q, LPG);
 
       // Request every row of the chunk (a missing sample reads the source row instead).
       U r[kChunk][UPL];
@@ -280,6 +338,13 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
         for (int i = 0; i < UPL; ++i) r[q][i] = P::load(row + col_read[i]);
         word[q] = bits[(use_bitmap && valid[q]) ? (v[q] >> 5) : 0];
       }
+      // While they are in flight: the ids of the next chunk (its offsets arrived a chunk
+      // ago) and the offsets of the chunk after it.
+      const ChunkPos ahead1 = cur.next(a.samples, per_round, stride);
+      draw_ids(ahead1, pre_next, mine);
+      pre_next = offsets_for(ahead1.next(a.samples, per_round, stride));
+      cur = ahead1;  // (its idx is this source's again unless this was the last chunk)
+
 #pragma unroll
       for (int q = 0; q < kChunk; ++q)
 #pragma unroll

@@ -57,9 +57,12 @@ struct PairWork {
   __device__ __forceinline__ float *source_row(int64_t i) const {
     return i < a_n ? a_rows + i * d : b_rows + (i - a_n) * d;
   }
+  // Nothing of a pair's sampling depends on memory that the source index alone names.
+  struct Pre {};
+  __device__ __forceinline__ Pre stage1(int64_t, bool) const { return Pre{}; }
   // Branch-free around the pool read: a lane that does not want a positive reads entry 0.
-  __device__ __forceinline__ int32_t sample(int64_t i, int32_t src, int32_t t, bool want,
-                                            bool positive) const {
+  __device__ __forceinline__ int32_t stage2(int64_t i, int32_t src, int32_t t, bool want, bool positive,
+                                            const Pre &) const {
     const int side = i >= a_n;
     const int64_t local = side ? i - a_n : i;
     const int32_t *pool = side ? pool_b : pool_a;
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(256) void pair_stream_kernel(PairWork w, int32_t sa
   for (int64_t x = blockIdx.x * 256LL + threadIdx.x; x < total; x += gridDim.x * 256LL) {
     const int64_t i = x / samples;
     const int32_t t = static_cast<int32_t>(x % samples);
-    out[x] = w.sample(i, w.source_id(i), t, true, t % w.per_round == 0);
+    out[x] = w.stage2(i, w.source_id(i), t, true, t % w.per_round == 0, w.stage1(i, true));
   }
 }
 

@@ -141,7 +141,7 @@ int gosh_matrix_place(int64_t n, int32_t d, uint64_t arena_bytes, float **M_dev,
     if (timed.count(first_row)) return GOSH_OK;
     float *window = reinterpret_cast<float *>(arena->va + static_cast<size_t>(first_row) * row_bytes);
     GOSH_TRY_HIP(hipEventRecord(start, nullptr), "hipEventRecord");
-    if (int rc = gosh::row_probe(window, n, d, 4 * n, 1, nullptr)) return rc;
+    if (int rc = gosh::row_probe(window, n, d, 4 * n, 1, GOSH_PROBE_READ_WRITE, nullptr)) return rc;
     GOSH_TRY_HIP(hipEventRecord(stop, nullptr), "hipEventRecord");
     GOSH_TRY_HIP(hipEventSynchronize(stop), "row probe");
     float ms = 0.f;

@@ -75,19 +75,26 @@ struct EpochWork {
   __device__ __forceinline__ int64_t count() const { return s.n; }
   __device__ __forceinline__ int32_t source_id(int64_t i) const { return static_cast<int32_t>(i); }
   __device__ __forceinline__ float *source_row(int64_t i) const { return M + i * d; }
+  // What sampling needs from memory knowing the source alone: where its neighbour list is.
+  struct Pre {
+    OffT begin;
+    uint32_t deg;
+  };
+  __device__ __forceinline__ Pre stage1(int64_t i, bool) const {  // i is a valid source also when unwanted
+    const OffT *xadj = static_cast<const OffT *>(s.xadj);
+    const OffT begin = xadj[i];
+    return Pre{begin, row_entries(begin, xadj[i + 1], s.nnz)};
+  }
   // Sample t of a source is draw t; the positive reads the neighbour list.  Written
-  // without branches around the reads: lanes that do not want a positive read the
+  // without branches around the read: lanes that do not want a positive read the
   // first offset again instead of a neighbour entry.
-  __device__ __forceinline__ int32_t sample(int64_t, int32_t src, int32_t t, bool want,
-                                            bool positive) const {
+  __device__ __forceinline__ int32_t stage2(int64_t, int32_t src, int32_t t, bool want, bool positive,
+                                            const Pre &pre) const {
     const uint64_t r = philox_draw(static_cast<uint32_t>(src), static_cast<uint32_t>(t), s.epoch,
                                    s.level, s.key0, s.key1);
-    const OffT *xadj = static_cast<const OffT *>(s.xadj);
-    const OffT begin = xadj[src];
-    const uint32_t deg = row_entries(begin, xadj[src + 1], s.nnz);
-    const bool read_adj = want && positive && deg != 0;
-    const int32_t *entry = read_adj ? s.adj + (begin + static_cast<OffT>(scale_draw(r, deg)))
-                                    : reinterpret_cast<const int32_t *>(xadj);
+    const bool read_adj = want && positive && pre.deg != 0;
+    const int32_t *entry = read_adj ? s.adj + (pre.begin + static_cast<OffT>(scale_draw(r, pre.deg)))
+                                    : reinterpret_cast<const int32_t *>(s.xadj);
     const int32_t neighbour = *entry;
     const int32_t uniform = static_cast<int32_t>(scale_draw(r, s.n));
     const bool is_vertex = static_cast<uint32_t>(neighbour) < s.n;
@@ -153,23 +160,60 @@ __global__ __launch_bounds__(256) void project_kernel(const float4 *__restrict__
   }
 }
 
-// Placement probe: `accesses` random rows are read and written back with `nothing` (zero)
-// added, one wavefront per row -- the access pattern of the training kernels without their
-// arithmetic, leaving the matrix as it is.
+// Row probe: the row traffic of the training kernels without their arithmetic.  A lane group
+// of `lpg` lanes (a power of two covering d/4, at most 64) moves one row with 128-bit
+// accesses, so a wavefront carries 64/lpg rows at a time, like the training kernels.
+//   kProbeReadWrite  a random row is read and written back with `nothing` (zero) added
+//   kProbeRead       a random row is read (a store that never happens keeps the loads alive)
+//   kProbeWrite      a random row is overwritten with `nothing`
+//   kProbeEpochMix   what one source of an epoch with three negatives moves: row i (sources
+//                    are consecutive) and four random rows are read, all five requested
+//                    before the first is used, then written back with `nothing` added
+// Draw q of access i is Philox(counter = (i_lo, i_hi, 0xFFFFFFFE, q), key = seed).
+enum ProbeMode : int32_t { kProbeReadWrite = 0, kProbeRead = 1, kProbeWrite = 2, kProbeEpochMix = 3 };
+
+template <int MODE>
 __global__ __launch_bounds__(256) void row_probe_kernel(float4 *__restrict__ M, uint64_t n, int32_t d4,
-                                                        uint64_t accesses, uint32_t key0, uint32_t key1,
-                                                        float nothing) {
+                                                        int32_t lpg, uint64_t accesses, uint32_t key0,
+                                                        uint32_t key1, float nothing) {
+  constexpr int kRows = MODE == kProbeEpochMix ? 5 : 1;
+  const int lane = threadIdx.x & 63, gl = lane & (lpg - 1), gpw = 64 / lpg;
   const uint64_t wave = (blockIdx.x * 256ull + threadIdx.x) >> 6, waves = (gridDim.x * 256ull) >> 6;
-  const int lane = threadIdx.x & 63;
-  for (uint64_t i = wave; i < accesses; i += waves) {
-    const uint64_t draw = philox_draw(static_cast<uint32_t>(i), static_cast<uint32_t>(i >> 32), 0xFFFFFFFEu, 0, key0, key1);
-    const uint64_t row = scale_draw(draw, static_cast<uint32_t>(n));
-    for (int c = lane; c < d4; c += 64) {
-      float4 v = M[row * d4 + c];
-      v.x += nothing;
-      M[row * d4 + c] = v;
+  float sink = 0.f;
+  for (uint64_t base = wave * gpw; base < accesses; base += waves * gpw) {
+    const uint64_t i = base + lane / lpg;
+    if (i >= accesses) continue;
+    uint64_t row[kRows];
+#pragma unroll
+    for (int q = 0; q < kRows; ++q) {
+      const uint64_t draw = philox_draw(static_cast<uint32_t>(i), static_cast<uint32_t>(i >> 32), 0xFFFFFFFEu,
+                                        static_cast<uint32_t>(q), key0, key1);
+      row[q] = (MODE == kProbeEpochMix && q == 0) ? i % n : scale_draw(draw, static_cast<uint32_t>(n));
     }
+    float4 v[kRows][2];
+#pragma unroll
+    for (int q = 0; q < kRows; ++q)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = gl + u * lpg;
+        v[q][u] = float4{0.f, 0.f, 0.f, 0.f};
+        if (MODE != kProbeWrite && c < d4) v[q][u] = M[row[q] * d4 + c];
+      }
+#pragma unroll
+    for (int q = 0; q < kRows; ++q)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = gl + u * lpg;
+        if (MODE == kProbeRead) {
+          sink += v[q][u].x;
+        } else if (c < d4) {
+          float4 x = v[q][u];
+          x.x += nothing;
+          M[row[q] * d4 + c] = x;
+        }
+      }
   }
+  if (MODE == kProbeRead && sink == 1.2345e-30f) M[0].x = sink;  // practically never: keeps the loads
 }
 
 // Largest finite |x| and the number of non-finite entries of `total4` float4s, accumulated
@@ -362,12 +406,32 @@ int matrix_check_read(const CheckResult *result_dev, float *max_abs, int64_t *no
   return GOSH_OK;
 }
 
-int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, hipStream_t st) {
+int row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, int32_t mode, hipStream_t st) {
   if (accesses <= 0) return GOSH_OK;
-  const int blocks = grid_for(accesses, 4, 1 << 13);  // four wavefronts per block
-  hipLaunchKernelGGL(row_probe_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<float4 *>(M_dev),
-                     static_cast<uint64_t>(n), d / 4, static_cast<uint64_t>(accesses), static_cast<uint32_t>(seed),
-                     static_cast<uint32_t>(seed >> 32), 0.0f);
+  const int32_t d4 = d / 4;
+  int32_t lpg = 1;
+  while (lpg < d4 && lpg < 64) lpg *= 2;
+  const int64_t per_block = 4 * (64 / lpg);  // four wavefronts per block
+  const int blocks = grid_for(accesses, static_cast<int>(per_block), 1 << 18);
+  float4 *M4 = reinterpret_cast<float4 *>(M_dev);
+  const uint64_t un = static_cast<uint64_t>(n), ua = static_cast<uint64_t>(accesses);
+  const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+  switch (mode) {
+    case kProbeReadWrite:
+      hipLaunchKernelGGL(row_probe_kernel<kProbeReadWrite>, dim3(blocks), dim3(256), 0, st, M4, un, d4, lpg, ua, k0, k1, 0.0f);
+      break;
+    case kProbeRead:
+      hipLaunchKernelGGL(row_probe_kernel<kProbeRead>, dim3(blocks), dim3(256), 0, st, M4, un, d4, lpg, ua, k0, k1, 0.0f);
+      break;
+    case kProbeWrite:
+      hipLaunchKernelGGL(row_probe_kernel<kProbeWrite>, dim3(blocks), dim3(256), 0, st, M4, un, d4, lpg, ua, k0, k1, 0.0f);
+      break;
+    case kProbeEpochMix:
+      hipLaunchKernelGGL(row_probe_kernel<kProbeEpochMix>, dim3(blocks), dim3(256), 0, st, M4, un, d4, lpg, ua, k0, k1, 0.0f);
+      break;
+    default:
+      return fail(GOSH_EINVAL, "probe mode %d: must be 0 (read-write), 1 (read), 2 (write) or 3 (epoch mix)", mode);
+  }
   return check_launch("row_probe_kernel");
 }
 
@@ -449,12 +513,15 @@ int gosh_matrix_check(const float *M_dev, int64_t n, int32_t d, float *max_abs, 
   return gosh::matrix_check_read(result, max_abs, nonfinite, st);
 }
 
-int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, void *hip_stream) {
+int gosh_row_probe(float *M_dev, int64_t n, int32_t d, int64_t accesses, uint64_t seed, int32_t mode,
+                   void *hip_stream) {
   if (int rc = gosh::check_matrix(M_dev, d, "M")) return rc;
   if (n < 1 || n >= 2147483647LL) return gosh::fail(GOSH_EINVAL, "n = %lld out of range", (long long)n);
   if (accesses < 0) return gosh::fail(GOSH_EINVAL, "accesses = %lld is negative", (long long)accesses);
+  if (mode < 0 || mode > 3)
+    return gosh::fail(GOSH_EINVAL, "probe mode %d: must be 0 (read-write), 1 (read), 2 (write) or 3 (epoch mix)", mode);
   if (int rc = gosh::check_device_span(M_dev, static_cast<size_t>(n) * d * 4, "M")) return rc;
-  return gosh::row_probe(M_dev, n, d, accesses, seed, gosh::as_stream(hip_stream));
+  return gosh::row_probe(M_dev, n, d, accesses, seed, mode, gosh::as_stream(hip_stream));
 }
 
 int gosh_project(const float *M_coarse_dev, int64_t n_coarse, const int32_t *map_dev, int64_t n_fine,

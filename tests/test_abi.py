@@ -103,10 +103,20 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.gosh_matrix_place(10, 6, 0, C.byref(out), None) == -1 and out.value is None
     assert lib.gosh_matrix_place(0, 32, 0, C.byref(out), None) == -1
     assert lib.gosh_matrix_place(10, 32, 0, None, None) == -1
-    assert lib.gosh_row_probe(ok_ptr, 10, 30, 5, 1, None) == -1
-    assert lib.gosh_row_probe(ok_ptr + 4, 10, 32, 5, 1, None) == -1
-    assert lib.gosh_row_probe(ok_ptr, 0, 32, 5, 1, None) == -1
-    assert lib.gosh_row_probe(ok_ptr, 10, 32, -1, 1, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 10, 30, 5, 1, 0, None) == -1
+    assert lib.gosh_row_probe(ok_ptr + 4, 10, 32, 5, 1, 0, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 0, 32, 5, 1, 0, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 10, 32, -1, 1, 0, None) == -1
+    assert lib.gosh_row_probe(ok_ptr, 10, 32, 5, 1, 4, None) == -1 and "mode" in G.gosh_last_error()
+    assert lib.gosh_matrix_check(ok_ptr, 10, 30, None, None, None) == -1
+    assert lib.gosh_matrix_check(0, 10, 32, None, None, None) == -1
+    # the entry point that never allocates checks its own limit first
+    big = G.gosh_csr(G.GOSH_STATIC_MAX_N + 1, 8, 0x1000, 0x2000, 0)
+    assert lib.gosh_train_epoch_static(C.byref(big), ok_ptr, 32, 3, 0.1, 1, 0, 0, 0, None) == -1
+    assert "at most" in G.gosh_last_error()
+    assert lib.gosh_train_epoch_static(C.byref(g), ok_ptr, 30, 3, 0.1, 1, 0, 0, 0, None) == -1
+    assert lib.gosh_set_tuning(None) == 0
+    assert lib.gosh_pair_level_parts(0, 100, 1, 5) == 0 and lib.gosh_pair_level_parts(10, 100, 1, 0) == 0
 
 
 def test_header_is_plain_c():

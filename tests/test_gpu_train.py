@@ -403,11 +403,21 @@ def test_matrix_place_gives_usable_memory_and_takes_it_back():
 
 def test_row_probe_leaves_the_matrix_as_it_is():
     """gosh_row_probe reads random rows and writes them back with zero added: the values stay,
-    for every d (one or two passes of the wavefront over a row) and with rows hit many times."""
-    for n, d in ((1000, 128), (37, 512), (5000, 4), (300, 260)):
+    for every d (a lane group per row, one or two passes over it) and with rows hit many
+    times; the read-only mode and the epoch mix leave them too; the write mode zeroes the
+    rows it visits and nothing else."""
+    for n, d in ((1000, 128), (37, 512), (5000, 4), (300, 260), (4097, 8), (513, 32), (100, 100)):
         M0 = torch.randn(n, d, dtype=torch.float32, device=DEV)
         M = M0.clone()
-        G.gosh_row_probe(M, 8 * n, seed=3)
+        for mode in (G.GOSH_PROBE_READ_WRITE, G.GOSH_PROBE_READ, G.GOSH_PROBE_EPOCH_MIX):
+            G.gosh_row_probe(M, 8 * n, seed=3, mode=mode)
         torch.cuda.synchronize()
-        assert torch.equal(M, M0)
+        assert torch.equal(M, M0), (n, d)
+        G.gosh_row_probe(M, n // 4, seed=4, mode=G.GOSH_PROBE_WRITE)
+        torch.cuda.synchronize()
+        zeroed = (M == 0).all(dim=1)
+        kept = (M == M0).all(dim=1)
+        assert (zeroed | kept).all() and 0 < int(zeroed.sum()) <= max(1, n // 4), (n, d)
     G.gosh_row_probe(M, 0)  # nothing to do
+    with pytest.raises(G.GoshError):
+        G.gosh_row_probe(M, 10, mode=7)
