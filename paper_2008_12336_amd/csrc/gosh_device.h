@@ -89,6 +89,14 @@ template <int F>
 struct Unit {
   float v[F];
 };
+// Four floats live in one 128-bit register tuple: an explicit 128-bit load (RowAgent128)
+// then delivers straight into the unit, with no instruction in between that could touch
+// registers whose data has not arrived yet.
+typedef float Float4 __attribute__((ext_vector_type(4)));
+template <>
+struct Unit<4> {
+  Float4 v;
+};
 
 __device__ __forceinline__ void atomic_step(float *p, float x) {
   // Built with -munsafe-fp-atomics: the matrix is ordinary coarse-grained device
@@ -96,14 +104,20 @@ __device__ __forceinline__ void atomic_step(float *p, float x) {
   __hip_atomic_fetch_add(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-struct RowPlain128 {
+// Policies whose loads the compiler issues itself need no explicit wait.
+struct TrackedLoads {
+  static __device__ __forceinline__ void wait_all() {}
+  template <int F>
+  static __device__ __forceinline__ void settle(Unit<F> &) {}
+};
+
+struct RowPlain128 : TrackedLoads {
   static constexpr int F = 4;
   static __device__ __forceinline__ Unit<4> load(const float *p) {
-    const float4 x = *reinterpret_cast<const float4 *>(p);
-    return Unit<4>{{x.x, x.y, x.z, x.w}};
+    return Unit<4>{*reinterpret_cast<const Float4 *>(p)};
   }
   static __device__ __forceinline__ void store(float *p, const Unit<4> &u) {
-    *reinterpret_cast<float4 *>(p) = float4{u.v[0], u.v[1], u.v[2], u.v[3]};
+    *reinterpret_cast<Float4 *>(p) = u.v;
   }
 };
 
@@ -111,7 +125,7 @@ struct RowPlain128 {
 // d <= 64, where a row is at most two lines: one instruction per row and lane group
 // instead of four keeps the request count per row down (rows that small are bound by
 // the number of memory requests, not by bytes).
-struct RowAgent64 {
+struct RowAgent64 : TrackedLoads {
   static constexpr int F = 2;
   static __device__ __forceinline__ Unit<2> load(const float *p) {
     const uint64_t b = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED,
@@ -127,7 +141,29 @@ struct RowAgent64 {
   }
 };
 
-struct RowAgent32 {
+// RowAgent128: 128-bit accesses at agent scope, four consecutive floats per lane.  The
+// compiler offers device-scope accesses only as atomics of at most 64 bits, so the two
+// instructions are written out (global_load_dwordx4 / global_store_dwordx4 with the sc1
+// bit, which is what an agent-scope access is on this chip).  The compiler does not count
+// these loads in its waits: settle() waits for all outstanding memory operations and ties
+// every loaded unit to that wait, and must be called for a unit before its first use.
+struct RowAgent128 {
+  static constexpr int F = 4;
+  static __device__ __forceinline__ Unit<4> load(const float *p) {
+    Unit<4> u;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(u.v) : "v"(p) : "memory");
+    return u;
+  }
+  static __device__ __forceinline__ void store(float *p, const Unit<4> &u) {
+    // the no-op keeps the next instruction from overwriting the data registers while the
+    // store still reads them
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" : : "v"(p), "v"(u.v) : "memory");
+  }
+  static __device__ __forceinline__ void wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+  static __device__ __forceinline__ void settle(Unit<4> &u) { asm volatile("" : "+v"(u.v)); }
+};
+
+struct RowAgent32 : TrackedLoads {
   static constexpr int F = 1;
   static __device__ __forceinline__ Unit<1> load(const float *p) {
     return Unit<1>{{__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)}};
@@ -303,17 +339,13 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
     if (idx >= n) continue;
     const int32_t src = w.source_id(idx);
     float *const src_row = w.source_row(idx);
-    U s[UPL];
+    // The source row is requested here and first touched after the rows of the first chunk
+    // have been requested too (`fresh`): nothing may read a unit before P::settle.
+    U s[UPL], s_before[UPL];
 #pragma unroll
-    for (int i = 0; i < UPL; ++i) {
-      s[i] = P::load(src_row + col_read[i]);
-#pragma unroll
-      for (int c = 0; c < F; ++c) s[i].v[c] = col_ok[i] ? s[i].v[c] : 0.f;
-    }
+    for (int i = 0; i < UPL; ++i) s[i] = P::load(src_row + col_read[i]);
     const uint32_t src_word = bits[use_bitmap ? (src >> 5) : 0];
-    U s_before[UPL];
-#pragma unroll
-    for (int i = 0; i < UPL; ++i) s_before[i] = s[i];
+    bool fresh = true;
 
     ChunkPos cur{idx, 0, 0};
     for (int32_t t0 = 0; t0 < a.samples; t0 += kChunk) {
@@ -345,12 +377,26 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
       pre_next = offsets_for(ahead1.next(a.samples, per_round, stride));
       cur = ahead1;  // (its idx is this source's again unless this was the last chunk)
 
+      // Everything this chunk needs has been asked for: from here on the rows may be used.
+      P::wait_all();
+#pragma unroll
+      for (int i = 0; i < UPL; ++i) {
+        P::settle(s[i]);
+#pragma unroll
+        for (int c = 0; c < F; ++c) {
+          s[i].v[c] = col_ok[i] ? s[i].v[c] : 0.f;
+          s_before[i].v[c] = fresh ? s[i].v[c] : s_before[i].v[c];
+        }
+      }
+      fresh = false;
 #pragma unroll
       for (int q = 0; q < kChunk; ++q)
 #pragma unroll
-        for (int i = 0; i < UPL; ++i)
+        for (int i = 0; i < UPL; ++i) {
+          P::settle(r[q][i]);
 #pragma unroll
           for (int c = 0; c < F; ++c) r[q][i].v[c] = col_ok[i] ? r[q][i].v[c] : 0.f;
+        }
 
 #pragma unroll
       for (int q = 0; q < kChunk; ++q) {
@@ -416,7 +462,12 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 //   plain_rows             plain 128-bit units, LPG = pow2ceil(d/4) lanes (<= 64): the layout
 //                          of the sequential-order debug mode
 //   otherwise, d <= 64     64-bit agent-scope units, LPG = pow2ceil(d/2) lanes, one unit
-//                          per lane (2..32 sources per wavefront)
+//                          per lane (2..32 sources per wavefront) -- or, when no row of the
+//                          launch takes the atomic-add path, 128-bit agent-scope units on
+//                          pow2ceil(d/4) lanes: rows of one or two lines move 12-23 %
+//                          faster in 128-bit pieces (5.9 against 4.8 TB/s at d = 32), but an
+//                          atomic add of a row then takes four instructions instead of two,
+//                          which on a graph with hubs costs more than the wider rows gain
 //   otherwise, d  > 64     32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
 //                          lanes (<= 64), four or eight units per lane
 // Each of them runs concurrently (seq = false) or as one lane group (seq = true).
@@ -446,7 +497,10 @@ struct SgdLauncher {
   }
 
   // Lane groups per wavefront in concurrent mode (to size the launch and the hot-row rule).
-  static int groups_per_wave(int32_t d) { return 64 / (d <= 64 ? pow2_lanes(d / 2) : pow2_lanes(d / 4)); }
+  // `stores_only`: no row of the launch takes the atomic-add path.
+  static int groups_per_wave(int32_t d, bool stores_only) {
+    return 64 / (d <= 64 && !stores_only ? pow2_lanes(d / 2) : pow2_lanes(d / 4));
+  }
 
   static void launch(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
                      int64_t max_waves, hipStream_t st) {
@@ -461,6 +515,15 @@ struct SgdLauncher {
         case 4: return run<RowPlain128, 4, 1>(w, a, count, seq, max_waves, st);
         case 2: return run<RowPlain128, 2, 1>(w, a, count, seq, max_waves, st);
         default: return run<RowPlain128, 1, 1>(w, a, count, seq, max_waves, st);
+      }
+    }
+    if (d <= 64 && a.hot.mode == kHotNone) {
+      switch (pow2_lanes(d / 4)) {
+        case 16: return run<RowAgent128, 16, 1>(w, a, count, seq, max_waves, st);
+        case 8: return run<RowAgent128, 8, 1>(w, a, count, seq, max_waves, st);
+        case 4: return run<RowAgent128, 4, 1>(w, a, count, seq, max_waves, st);
+        case 2: return run<RowAgent128, 2, 1>(w, a, count, seq, max_waves, st);
+        default: return run<RowAgent128, 1, 1>(w, a, count, seq, max_waves, st);
       }
     }
     if (d <= 64) {

@@ -1,7 +1,8 @@
 """The kernels as they are shipped and benchmarked, held to the sequential-order bar.
 
 GOSH_FLAG_SEQUENTIAL | GOSH_FLAG_CONCURRENT_LAYOUT runs the concurrent template itself --
-its lane-to-column layout (32-bit interleaved units for d > 64, 64-bit units for d <= 64),
+its lane-to-column layout (32-bit interleaved units for d > 64, 64-bit units for d <= 64,
+128-bit units for d <= 64 when every row is written with plain stores),
 its device-scope row accesses, the hot-row bitmap with the atomic-add and the plain-store
 write paths, the source's own atomic delta, the forwarding inside a chunk of four samples --
 on one lane group that walks the sources in ascending id.  Every address is then touched
@@ -74,6 +75,12 @@ CASES = [
     (512, 3, True, 0.3, MIX),
     (32, 3, False, 1.0, ALL_ATOMIC),
     (4, 15, False, 2.0, MIX),
+    # store-only launches at d <= 64 use 128-bit device-scope units on d/4 lanes
+    (32, 3, False, 1.0, ALL_STORES),
+    (64, 5, True, 0.8, ALL_STORES),
+    (8, 3, False, 2.0, ALL_STORES),
+    (4, 9, False, 2.0, ALL_STORES),
+    (36, 2, False, 1.0, ALL_STORES),
 ]
 
 
@@ -147,15 +154,16 @@ def test_layout_flag_alone_changes_nothing_and_the_default_rule_is_used_without_
     assert np.array_equal(M.cpu().numpy(), M0)
 
 
+@pytest.mark.parametrize("stores_only", [False, True])
 @pytest.mark.parametrize("d,K,B,k", [(128, 3, 5, 3), (32, 4, 2, 3), (256, 2, 3, 2), (8, 5, 4, 5), (512, 9, 4, 9)])
-def test_shipped_pair_kernel_in_sequential_order(d, K, B, k, hot_degree):
+def test_shipped_pair_kernel_in_sequential_order(d, K, B, k, stores_only, hot_degree):
     """The same for the pair kernel of Alg. 5 (rotation on a device-resident matrix and on a
     host matrix): concurrent layout and write paths, sequential order, against the oracle's
     rotation."""
     n, epochs = 1200, 2 * B * K
     xadj, adj = hub_graph(n, 9000, 8)
     hot_degree(10)
-    say(f"[layout pair] d={d} K={K} B={B} k={k}")
+    say(f"[layout pair] d={d} K={K} B={B} k={k} stores_only={stores_only}")
     M0 = (O.init_embedding(n, d, 3, 0).astype(np.float64) * d * 0.8).astype(np.float32)
     want = M0.copy()
     O.train_parts(xadj, adj, want, k, epochs, 0.1, 7, 2, K, B)
@@ -163,7 +171,8 @@ def test_shipped_pair_kernel_in_sequential_order(d, K, B, k, hot_degree):
     for where in ("device", "host"):
         M = torch.from_numpy(M0.copy()).to(DEV) if where == "device" else torch.from_numpy(M0.copy()).pin_memory()
         gx, ga = (xt.to(DEV), at.to(DEV)) if where == "device" else (xt, at)
-        st = G.gosh_train_parts(n, gx, ga, M, k, epochs, 0.1, 7, level=2, force_K=K, B=B, flags=SEQ_LAYOUT)
+        st = G.gosh_train_parts(n, gx, ga, M, k, epochs, 0.1, 7, level=2, force_K=K, B=B,
+                                flags=SEQ_LAYOUT | (G.GOSH_FLAG_PLAIN_STORES if stores_only else 0))
         torch.cuda.synchronize()
         err = rel_err(M.cpu().numpy(), want)
         say(f"              {where}: err={err:.2e}")
