@@ -477,6 +477,9 @@ def main() -> int:
                    "finite": finite},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                     f"profiles/train_epoch_{args.workload}_traffic.txt (rocprofv3 counters of an earlier run of "
+                     "this command, calibrated on a copy of known size; quoted, not measured by this run)",
                      "kernel": "sgd_kernel<EpochWork>", "kernel_ms_avg": avg_kernel_s * 1e3,
                      "kernel_ms_min": float(np.min(kernel_ms)),
                      "algorithmic_bytes_per_launch": row_bytes_per_launch},
