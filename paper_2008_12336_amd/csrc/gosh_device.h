@@ -106,6 +106,7 @@ __device__ __forceinline__ void atomic_step(float *p, float x) {
 
 // Policies whose loads the compiler issues itself need no explicit wait.
 struct TrackedLoads {
+  static constexpr bool kWaveAtomics = false;  // a hot row is added to by the lanes that own it
   static __device__ __forceinline__ void wait_all() {}
   template <int F>
   static __device__ __forceinline__ void settle(Unit<F> &) {}
@@ -121,34 +122,17 @@ struct RowPlain128 : TrackedLoads {
   }
 };
 
-// RowAgent64: 64-bit agent-scope accesses, two consecutive floats per lane.  Used for
-// d <= 64, where a row is at most two lines: one instruction per row and lane group
-// instead of four keeps the request count per row down (rows that small are bound by
-// the number of memory requests, not by bytes).
-struct RowAgent64 : TrackedLoads {
-  static constexpr int F = 2;
-  static __device__ __forceinline__ Unit<2> load(const float *p) {
-    const uint64_t b = __hip_atomic_load(reinterpret_cast<const uint64_t *>(p), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-    return Unit<2>{{__uint_as_float(static_cast<uint32_t>(b)),
-                    __uint_as_float(static_cast<uint32_t>(b >> 32))}};
-  }
-  static __device__ __forceinline__ void store(float *p, const Unit<2> &u) {
-    const uint64_t b = static_cast<uint64_t>(__float_as_uint(u.v[0])) |
-                       (static_cast<uint64_t>(__float_as_uint(u.v[1])) << 32);
-    __hip_atomic_store(reinterpret_cast<uint64_t *>(p), b, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-  }
-};
-
-// RowAgent128: 128-bit accesses at agent scope, four consecutive floats per lane.  The
-// compiler offers device-scope accesses only as atomics of at most 64 bits, so the two
-// instructions are written out (global_load_dwordx4 / global_store_dwordx4 with the sc1
+// RowAgent128: 128-bit accesses at agent scope, four consecutive floats per lane, for
+// d <= 64, where a row is at most two lines: rows that short move 12-23 % faster in 128-bit
+// pieces on d/4 lanes than in 64-bit pieces on d/2 lanes (5.9 against 4.8 TB/s at d = 32),
+// plain or device-scope alike.  The compiler offers device-scope accesses only as atomics of
+// at most 64 bits, so the two instructions are written out (global_load_dwordx4 / global_store_dwordx4 with the sc1
 // bit, which is what an agent-scope access is on this chip).  The compiler does not count
 // these loads in its waits: settle() waits for all outstanding memory operations and ties
 // every loaded unit to that wait, and must be called for a unit before its first use.
 struct RowAgent128 {
   static constexpr int F = 4;
+  static constexpr bool kWaveAtomics = true;  // a hot row is added to by the whole wavefront, see add_rows_as_a_wave
   static __device__ __forceinline__ Unit<4> load(const float *p) {
     Unit<4> u;
     asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(u.v) : "v"(p) : "memory");
@@ -204,6 +188,33 @@ struct SgdArgs {
 
 constexpr int kChunk = 4;  // sample rows in flight per source
 
+// Atomic adds of whole rows with 128-bit units, one row at a time by the whole wavefront.
+// A memory-side fp32 atomic costs one operation per instruction and line it touches, full or
+// sparse.  A lane group of d/4 lanes that adds its own four floats per lane needs four
+// instructions per row, each touching every line of the row; here the rows to be added (one
+// per lane group that asks, `mine`) are taken in turn, lane l of the wavefront fetches float l
+// of the row's step from the lane that holds it and adds it at row + l: one instruction per
+// row, each line touched once.  Needs d <= 64 and every lane of the wavefront present (no
+// divergent branch around the call); `mine` and `row` are uniform inside a lane group.
+template <int LPG>
+__device__ __forceinline__ void add_rows_as_a_wave(bool mine, float *row, const Unit<4> &step, int32_t d, int lane) {
+  unsigned long long todo = __ballot(mine && (lane & (LPG - 1)) == 0);
+  const uint64_t address = reinterpret_cast<uint64_t>(row);
+  const int piece = lane & 3;
+  while (todo != 0) {
+    const int leader = __builtin_amdgcn_readfirstlane(__builtin_ctzll(todo));
+    todo &= todo - 1;
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<uint32_t>(address), leader);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<uint32_t>(address >> 32), leader);
+    float *const target = reinterpret_cast<float *>((static_cast<uint64_t>(hi) << 32) | lo);
+    const int owner = leader + (lane >> 2);  // lanes past the row wrap around and are masked below
+    const float x0 = __shfl(step.v[0], owner, 64), x1 = __shfl(step.v[1], owner, 64);
+    const float x2 = __shfl(step.v[2], owner, 64), x3 = __shfl(step.v[3], owner, 64);
+    const float x = piece == 0 ? x0 : piece == 1 ? x1 : piece == 2 ? x2 : x3;
+    if (lane < d) atomic_step(target + lane, x);
+  }
+}
+
 // Position of a chunk of kChunk samples in the work of one lane group: source index, first
 // sample of the chunk, and the index of the next positive sample at or after it.  All lane
 // groups of a wavefront are at the same (t0, np); only idx differs.
@@ -249,9 +260,10 @@ struct ChunkPos {
 //   P: row access policy; LPG lanes per source, UPL units per lane (LPG*UPL*P::F >= d).
 //   SEQ: a single lane group walks all sources in ascending index (the sequential-order
 //   result), with whatever policy, geometry and hot-row mode it is instantiated and called
-//   with: every address is then read and written by one lane in program order, so stores and
-//   atomic adds alike take effect in the order of Alg. 3.  Otherwise lane groups stride over
-//   the sources.
+//   with: all accesses to the matrix then come from one wavefront in program order, and the
+//   memory system keeps the accesses of a wavefront to one address in that order, so stores
+//   and atomic adds alike take effect in the order of Alg. 3.  Otherwise lane groups stride
+//   over the sources.
 //
 // Sampling is independent of the matrix (the draws are counter-based), so it runs ahead of
 // the updates as a three-stage pipeline over chunks of kChunk samples: while the rows of
@@ -275,7 +287,11 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   using Pre = typename W::Pre;
   const int lane = threadIdx.x & 63;
   const int gl = lane & (LPG - 1);
-  if (SEQ && (lane >= LPG || threadIdx.x >= 64 || blockIdx.x != 0)) return;
+  // The sequential walk is done by the first lane group of the first wavefront; the other
+  // groups of that wavefront tag along without a source (the wavefront-wide atomic adds want
+  // all 64 lanes present).
+  if (SEQ && (threadIdx.x >= 64 || blockIdx.x != 0)) return;
+  const bool group_on = !SEQ || lane < LPG;
 
   const int64_t wave = blockIdx.x * static_cast<int64_t>(blockDim.x / 64) + (threadIdx.x >> 6);
   if (!SEQ && wave >= a.active_waves) return;
@@ -303,7 +319,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   // Stage 2 for the chunk at `pos`: lane q of the group evaluates sample pos.t0 + q (in
   // several passes if the group has fewer than kChunk lanes).
   auto draw_ids = [&](const ChunkPos &pos, const Pre &pre, int32_t (&mine)[kPasses]) {
-    const bool live = pos.idx < n;
+    const bool live = group_on && pos.idx < n;
     const int64_t i = live ? pos.idx : 0;
     const int32_t id = w.source_id(i);
     bool is_pos[kChunk];
@@ -319,7 +335,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
     }
   };
   auto offsets_for = [&](const ChunkPos &pos) {
-    const bool live = pos.idx < n;
+    const bool live = group_on && pos.idx < n;
     return w.stage1(live ? pos.idx : 0, live);
   };
 
@@ -332,11 +348,14 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
     pre_next = offsets_for(c0.next(a.samples, per_round, stride));
   }
 
-  // The loop bound is uniform over the wave; groups past the end idle inside.
+  // The loop bound is uniform over the wave.  A group without a source (past the end, or
+  // tagging along in the sequential walk) goes through the motions on source 0 -- it reads,
+  // computes and writes nothing -- so that no lane ever leaves the wavefront's control flow.
   const int64_t first_of_wave = SEQ ? 0 : wave * kGroupsPerWave;
   for (int64_t base = first_of_wave; base < n; base += stride) {
-    const int64_t idx = first + (base - first_of_wave);
-    if (idx >= n) continue;
+    const int64_t idx_raw = first + (base - first_of_wave);
+    const bool live = group_on && idx_raw < n;
+    const int64_t idx = live ? idx_raw : 0;
     const int32_t src = w.source_id(idx);
     float *const src_row = w.source_row(idx);
     // The source row is requested here and first touched after the rows of the first chunk
@@ -347,7 +366,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
     const uint32_t src_word = bits[use_bitmap ? (src >> 5) : 0];
     bool fresh = true;
 
-    ChunkPos cur{idx, 0, 0};
+    ChunkPos cur{idx_raw, 0, 0};
     for (int32_t t0 = 0; t0 < a.samples; t0 += kChunk) {
       bool is_pos[kChunk];
       cur.positives(per_round, is_pos);
@@ -364,7 +383,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
       bool valid[kChunk];
 #pragma unroll
       for (int q = 0; q < kChunk; ++q) {
-        valid[q] = v[q] >= 0 && v[q] != src;  // a sample that hits the source applies no update
+        valid[q] = live && v[q] >= 0 && v[q] != src;  // a sample that hits the source applies no update
         const float *row = valid[q] ? w.sample_row(idx, v[q]) : src_row;
 #pragma unroll
         for (int i = 0; i < UPL; ++i) r[q][i] = P::load(row + col_read[i]);
@@ -416,19 +435,26 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
             s[i].v[c] = fmaf(g, r[q][i].v[c], s[i].v[c]);
             r[q][i].v[c] = fmaf(g, s[i].v[c], r[q][i].v[c]);
           }
-        if (valid[q]) {  // uniform over the group; only writes inside
-          float *const row = w.sample_row(idx, v[q]);
-          const bool hot = all_hot || ((word[q] >> (v[q] & 31)) & 1u);
-          if (hot) {
+        {
+          float *const row = valid[q] ? w.sample_row(idx, v[q]) : src_row;
+          const bool hot = valid[q] && (all_hot || ((word[q] >> (v[q] & 31)) & 1u));
+          if (valid[q] && !hot) {  // uniform over the group; only writes inside
+#pragma unroll
+            for (int i = 0; i < UPL; ++i)
+              if (col_ok[i]) P::store(row + col[i], r[q][i]);
+          }
+          if constexpr (P::kWaveAtomics) {
+            static_assert(!P::kWaveAtomics || (UPL == 1 && F == 4), "one 128-bit unit per lane");
+            U step;
+#pragma unroll
+            for (int c = 0; c < F; ++c) step.v[c] = g * s[0].v[c];
+            add_rows_as_a_wave<LPG>(hot, row, step, d, lane);
+          } else if (hot) {
 #pragma unroll
             for (int i = 0; i < UPL; ++i)
 #pragma unroll
               for (int c = 0; c < F; ++c)
                 if (col_ok[i]) atomic_step(row + col[i] + c, g * s[i].v[c]);
-          } else {
-#pragma unroll
-            for (int i = 0; i < UPL; ++i)
-              if (col_ok[i]) P::store(row + col[i], r[q][i]);
           }
         }
         // A later sample of the same chunk that names the same vertex must see this
@@ -443,17 +469,23 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
         }
       }
     }
-    const bool src_hot = all_hot || ((src_word >> (src & 31)) & 1u);
-    if (src_hot) {
+    const bool src_hot = live && (all_hot || ((src_word >> (src & 31)) & 1u));
+    if (live && !src_hot) {
+#pragma unroll
+      for (int i = 0; i < UPL; ++i)
+        if (col_ok[i]) P::store(src_row + col[i], s[i]);
+    }
+    if constexpr (P::kWaveAtomics) {
+      U step;
+#pragma unroll
+      for (int c = 0; c < F; ++c) step.v[c] = s[0].v[c] - s_before[0].v[c];
+      add_rows_as_a_wave<LPG>(src_hot, src_row, step, d, lane);
+    } else if (src_hot) {
 #pragma unroll
       for (int i = 0; i < UPL; ++i)
 #pragma unroll
         for (int c = 0; c < F; ++c)
           if (col_ok[i]) atomic_step(src_row + col[i] + c, s[i].v[c] - s_before[i].v[c]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < UPL; ++i)
-        if (col_ok[i]) P::store(src_row + col[i], s[i]);
     }
   }
 }
@@ -461,13 +493,9 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 // Launches sgd_kernel for a given dimension.  Geometry:
 //   plain_rows             plain 128-bit units, LPG = pow2ceil(d/4) lanes (<= 64): the layout
 //                          of the sequential-order debug mode
-//   otherwise, d <= 64     64-bit agent-scope units, LPG = pow2ceil(d/2) lanes, one unit
-//                          per lane (2..32 sources per wavefront) -- or, when no row of the
-//                          launch takes the atomic-add path, 128-bit agent-scope units on
-//                          pow2ceil(d/4) lanes: rows of one or two lines move 12-23 %
-//                          faster in 128-bit pieces (5.9 against 4.8 TB/s at d = 32), but an
-//                          atomic add of a row then takes four instructions instead of two,
-//                          which on a graph with hubs costs more than the wider rows gain
+//   otherwise, d <= 64     128-bit agent-scope units, LPG = pow2ceil(d/4) lanes, one unit per
+//                          lane (4..64 sources per wavefront); hot rows are added to by the
+//                          whole wavefront, one row at a time
 //   otherwise, d  > 64     32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
 //                          lanes (<= 64), four or eight units per lane
 // Each of them runs concurrently (seq = false) or as one lane group (seq = true).
@@ -497,10 +525,7 @@ struct SgdLauncher {
   }
 
   // Lane groups per wavefront in concurrent mode (to size the launch and the hot-row rule).
-  // `stores_only`: no row of the launch takes the atomic-add path.
-  static int groups_per_wave(int32_t d, bool stores_only) {
-    return 64 / (d <= 64 && !stores_only ? pow2_lanes(d / 2) : pow2_lanes(d / 4));
-  }
+  static int groups_per_wave(int32_t d) { return 64 / pow2_lanes(d / 4); }
 
   static void launch(const W &w, const SgdArgs &a, int64_t count, bool seq, bool plain_rows,
                      int64_t max_waves, hipStream_t st) {
@@ -517,22 +542,13 @@ struct SgdLauncher {
         default: return run<RowPlain128, 1, 1>(w, a, count, seq, max_waves, st);
       }
     }
-    if (d <= 64 && a.hot.mode == kHotNone) {
+    if (d <= 64) {
       switch (pow2_lanes(d / 4)) {
         case 16: return run<RowAgent128, 16, 1>(w, a, count, seq, max_waves, st);
         case 8: return run<RowAgent128, 8, 1>(w, a, count, seq, max_waves, st);
         case 4: return run<RowAgent128, 4, 1>(w, a, count, seq, max_waves, st);
         case 2: return run<RowAgent128, 2, 1>(w, a, count, seq, max_waves, st);
         default: return run<RowAgent128, 1, 1>(w, a, count, seq, max_waves, st);
-      }
-    }
-    if (d <= 64) {
-      switch (pow2_lanes(d / 2)) {
-        case 32: return run<RowAgent64, 32, 1>(w, a, count, seq, max_waves, st);
-        case 16: return run<RowAgent64, 16, 1>(w, a, count, seq, max_waves, st);
-        case 8: return run<RowAgent64, 8, 1>(w, a, count, seq, max_waves, st);
-        case 4: return run<RowAgent64, 4, 1>(w, a, count, seq, max_waves, st);
-        default: return run<RowAgent64, 2, 1>(w, a, count, seq, max_waves, st);
       }
     }
     if (d > 256) return run<RowAgent32, 64, 8>(w, a, count, seq, max_waves, st);

@@ -470,7 +470,7 @@ class Rotation {
   int build_hot_set() {
     const int64_t n = pl.g->n;
     if (concurrent_paths) {
-      const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(pl.d, (pl.flags & GOSH_FLAG_PLAIN_STORES) != 0);
+      const int gpw = gosh::SgdLauncher<PairWork>::groups_per_wave(pl.d);
       const int64_t pair_sources = 2 * L.part_rows;
       const int64_t waves = std::min<int64_t>((pair_sources + gpw - 1) / gpw, tune.max_waves);
       const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;

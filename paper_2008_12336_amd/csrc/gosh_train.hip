@@ -300,7 +300,7 @@ int launch_epoch(const gosh_csr *g, float *M, int32_t d, int32_t k_neg, float lr
     // are hot.  Both constants come from link-prediction AUCROC against the sequential
     // reference on R-MAT graphs of 2^12..2^20 vertices: with them the concurrent kernel
     // stays within 0.001..0.005 of the reference, without them it drops by up to 0.4.
-    const int gpw = gosh::SgdLauncher<EpochWork<OffT>>::groups_per_wave(d, (flags & GOSH_FLAG_PLAIN_STORES) != 0);
+    const int gpw = gosh::SgdLauncher<EpochWork<OffT>>::groups_per_wave(d);
     int64_t waves = std::min<int64_t>((n + gpw - 1) / gpw, max_waves);
     const int64_t in_flight = std::min<int64_t>(waves, gosh::resident_waves()) * gpw;
     int mode = gosh::kHotBitmap;
