@@ -75,12 +75,15 @@ CASES = [
     (512, 3, True, 0.3, MIX),
     (32, 3, False, 1.0, ALL_ATOMIC),
     (4, 15, False, 2.0, MIX),
-    # store-only launches at d <= 64 use 128-bit device-scope units on d/4 lanes
+    # store-only and all-atomic launches of the 128-bit units of d <= 64
     (32, 3, False, 1.0, ALL_STORES),
     (64, 5, True, 0.8, ALL_STORES),
     (8, 3, False, 2.0, ALL_STORES),
     (4, 9, False, 2.0, ALL_STORES),
     (36, 2, False, 1.0, ALL_STORES),
+    (64, 3, False, 0.8, ALL_ATOMIC),
+    (8, 5, True, 2.0, ALL_ATOMIC),
+    (36, 4, False, 1.0, MIX),
 ]
 
 
