@@ -106,8 +106,9 @@ const char *gosh_last_error(void);
 typedef struct {
   int32_t plain_rows;        /* non-zero: plain 128-bit row accesses also in the concurrent
                                 kernels (coherent inside one XCD only).  Default 0 */
-  int64_t max_waves;         /* cap on the wavefronts that share the sources of one launch.
-                                Default 2^22 */
+  int64_t max_waves;         /* cap on the wavefronts that share the sources of one launch
+                                (each then walks several sources, sampling ahead).
+                                Default 2^18 */
   int64_t hot_inv_eps;       /* a vertex is hot if deg * C / nnz > 1 / hot_inv_eps, C = sources
                                 in flight.  Default 64 */
   int64_t hot_all_inv_eps;   /* every row is hot if (k_neg + 1) * C / n > 1 / hot_all_inv_eps;

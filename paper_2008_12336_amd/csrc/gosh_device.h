@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 
 namespace gosh {
@@ -183,7 +184,9 @@ struct SgdArgs {
   int32_t k_neg;    // sample t of a source is a positive iff t % (k_neg + 1) == 0
   int32_t samples;  // samples per source: k_neg + 1 per round
   float lr;
-  int64_t active_waves;  // wavefronts that take part; the rest of the grid exits at once
+  int64_t active_waves;      // wavefronts that take part; the rest of the grid exits at once
+  int64_t sources_per_wave;  // each of them walks this many consecutive sources (a multiple of
+                             // the lane groups per wavefront)
 };
 
 constexpr int kChunk = 4;  // sample rows in flight per source
@@ -251,8 +254,11 @@ struct ChunkPos {
 //     float  *source_row(int64_t i)
 //     Pre     stage1(int64_t i, bool want)    what sampling for source i needs from memory and
 //                                             can be asked for knowing i alone (row offsets)
-//     int32_t stage2(int64_t i, int32_t id, int32_t t, bool want, bool positive, Pre)
-//                                             vertex id of sample t (-1 = none, or !want)
+//     uint64_t draw(int64_t i, int32_t id, int32_t t)
+//                                             the random draw of sample t: arithmetic only
+//     int32_t stage2(int64_t i, int32_t id, int32_t t, bool want, bool positive, Pre, uint64_t r)
+//                                             vertex id of sample t from its draw r (-1 = none,
+//                                             or !want)
 //     float  *sample_row(int64_t i, int32_t v)
 //     Both stages must be free of branches around their memory reads (read a safe address
 //     when !want).
@@ -295,9 +301,14 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 
   const int64_t wave = blockIdx.x * static_cast<int64_t>(blockDim.x / 64) + (threadIdx.x >> 6);
   if (!SEQ && wave >= a.active_waves) return;
-  const int64_t n = w.count();
-  const int64_t stride = SEQ ? 1 : a.active_waves * kGroupsPerWave;
-  const int64_t first = SEQ ? 0 : wave * kGroupsPerWave + lane / LPG;
+  // A wavefront walks a block of consecutive sources, kGroupsPerWave at a time, so that the
+  // sources of an epoch are taken up in ascending order (wavefronts start in the order of their
+  // index) however many of them one wavefront walks.  `n` is the end of this wavefront's block.
+  const int64_t first_of_wave = SEQ ? 0 : wave * a.sources_per_wave;
+  const int64_t n =
+      SEQ ? w.count() : std::min<int64_t>(w.count(), first_of_wave + a.sources_per_wave);
+  const int64_t stride = SEQ ? 1 : kGroupsPerWave;
+  const int64_t first = first_of_wave + (SEQ ? 0 : lane / LPG);
   const int32_t d = a.d;
   const int32_t per_round = a.k_neg + 1;
   const bool use_bitmap = a.hot.mode == kHotBitmap;
@@ -320,6 +331,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   // several passes if the group has fewer than kChunk lanes).
   auto draw_ids = [&](const ChunkPos &pos, const Pre &pre, int32_t (&mine)[kPasses]) {
     const bool live = group_on && pos.idx < n;
+    const bool any_live = __ballot(live) != 0;  // the same for the whole wavefront: a jump, not a mask
     const int64_t i = live ? pos.idx : 0;
     const int32_t id = w.source_id(i);
     bool is_pos[kChunk];
@@ -331,7 +343,11 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
       bool mine_pos = false;
 #pragma unroll
       for (int q = 0; q < LPG && p * LPG + q < kChunk; ++q) mine_pos = (gl == q) ? is_pos[p * LPG + q] : mine_pos;
-      mine[p] = w.stage2(i, id, want ? t : 0, want, mine_pos, pre);
+      // Past a wavefront's last chunk nobody wants the draw: only the arithmetic is skipped,
+      // the reads of stage 2 stay unconditional.
+      uint64_t r = 0;
+      if (any_live) r = w.draw(i, id, want ? t : 0);
+      mine[p] = w.stage2(i, id, want ? t : 0, want, mine_pos, pre, r);
     }
   };
   auto offsets_for = [&](const ChunkPos &pos) {
@@ -351,7 +367,6 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   // The loop bound is uniform over the wave.  A group without a source (past the end, or
   // tagging along in the sequential walk) goes through the motions on source 0 -- it reads,
   // computes and writes nothing -- so that no lane ever leaves the wavefront's control flow.
-  const int64_t first_of_wave = SEQ ? 0 : wave * kGroupsPerWave;
   for (int64_t base = first_of_wave; base < n; base += stride) {
     const int64_t idx_raw = first + (base - first_of_wave);
     const bool live = group_on && idx_raw < n;
@@ -499,17 +514,18 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 //   otherwise, d  > 64     32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
 //                          lanes (<= 64), four or eight units per lane
 // Each of them runs concurrently (seq = false) or as one lane group (seq = true).
-// `a.active_waves` is filled in here from `count`.
+// `a.active_waves` and `a.sources_per_wave` are filled in here from `count`.
 template <class W>
 struct SgdLauncher {
   template <class P, int LPG, int UPL>
   static void run(const W &w, SgdArgs a, int64_t count, bool seq, int64_t max_waves, hipStream_t st) {
     constexpr int kWavesPerBlock = 4;
     constexpr int kGroupsPerWave = 64 / LPG;
-    int64_t waves = (count + kGroupsPerWave - 1) / kGroupsPerWave;
-    if (waves > max_waves) waves = max_waves;
-    if (waves < 1) waves = 1;
+    const int64_t turns = (count + kGroupsPerWave - 1) / kGroupsPerWave;  // wavefront-loads of sources
+    const int64_t per_wave = std::max<int64_t>((turns + max_waves - 1) / max_waves, 1);
+    const int64_t waves = std::max<int64_t>((turns + per_wave - 1) / per_wave, 1);
     a.active_waves = waves;
+    a.sources_per_wave = per_wave * kGroupsPerWave;
     if (seq) {
       hipLaunchKernelGGL((sgd_kernel<P, LPG, UPL, W, true>), dim3(1), dim3(64), 0, st, w, a);
     } else {

@@ -90,7 +90,7 @@ int check_launch(const char *kernel) {
 
 namespace {
 std::mutex g_tuning_mutex;
-constexpr gosh_tuning kDefaultTuning{0, int64_t{1} << 22, 64, 4, 0, int64_t{1} << 22};
+constexpr gosh_tuning kDefaultTuning{0, int64_t{1} << 18, 64, 4, 0, int64_t{1} << 22};
 gosh_tuning g_tuning = kDefaultTuning;
 }  // namespace
 

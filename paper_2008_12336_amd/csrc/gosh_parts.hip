@@ -61,8 +61,13 @@ struct PairWork {
   struct Pre {};
   __device__ __forceinline__ Pre stage1(int64_t, bool) const { return Pre{}; }
   // Branch-free around the pool read: a lane that does not want a positive reads entry 0.
-  __device__ __forceinline__ int32_t stage2(int64_t i, int32_t src, int32_t t, bool want, bool positive,
-                                            const Pre &) const {
+  __device__ __forceinline__ uint64_t draw(int64_t i, int32_t src, int32_t t) const {
+    const int side = i >= a_n;
+    return philox_draw(static_cast<uint32_t>(src), static_cast<uint32_t>(side * B * per_round + t), rotation,
+                       word3, key0, key1);
+  }
+  __device__ __forceinline__ int32_t stage2(int64_t i, int32_t, int32_t t, bool want, bool positive, const Pre &,
+                                            uint64_t r) const {
     const int side = i >= a_n;
     const int64_t local = side ? i - a_n : i;
     const int32_t *pool = side ? pool_b : pool_a;
@@ -71,9 +76,6 @@ struct PairWork {
     // is no sample: the kernel never leaves the two slots
     int32_t from_pool = pool[(want && positive) ? local * B + t / per_round : 0];
     if (static_cast<uint32_t>(from_pool - other_lo) >= static_cast<uint32_t>(other_n)) from_pool = -1;
-    const uint64_t r = philox_draw(static_cast<uint32_t>(src),
-                                   static_cast<uint32_t>(side * B * per_round + t), rotation, word3,
-                                   key0, key1);
     // an empty partner part (possible for the last parts of a split) offers no negative
     const int32_t uniform =
         other_n > 0 ? other_lo + static_cast<int32_t>(scale_draw(r, static_cast<uint32_t>(other_n))) : -1;
@@ -92,7 +94,8 @@ __global__ __launch_bounds__(256) void pair_stream_kernel(PairWork w, int32_t sa
   for (int64_t x = blockIdx.x * 256LL + threadIdx.x; x < total; x += gridDim.x * 256LL) {
     const int64_t i = x / samples;
     const int32_t t = static_cast<int32_t>(x % samples);
-    out[x] = w.stage2(i, w.source_id(i), t, true, t % w.per_round == 0, w.stage1(i, true));
+    const int32_t src = w.source_id(i);
+    out[x] = w.stage2(i, src, t, true, t % w.per_round == 0, w.stage1(i, true), w.draw(i, src, t));
   }
 }
 

@@ -88,10 +88,12 @@ struct EpochWork {
   // Sample t of a source is draw t; the positive reads the neighbour list.  Written
   // without branches around the read: lanes that do not want a positive read the
   // first offset again instead of a neighbour entry.
-  __device__ __forceinline__ int32_t stage2(int64_t, int32_t src, int32_t t, bool want, bool positive,
-                                            const Pre &pre) const {
-    const uint64_t r = philox_draw(static_cast<uint32_t>(src), static_cast<uint32_t>(t), s.epoch,
-                                   s.level, s.key0, s.key1);
+  // The draw itself is arithmetic only; the kernel skips it where no group of the wavefront wants it.
+  __device__ __forceinline__ uint64_t draw(int64_t, int32_t src, int32_t t) const {
+    return philox_draw(static_cast<uint32_t>(src), static_cast<uint32_t>(t), s.epoch, s.level, s.key0, s.key1);
+  }
+  __device__ __forceinline__ int32_t stage2(int64_t, int32_t, int32_t, bool want, bool positive, const Pre &pre,
+                                            uint64_t r) const {
     const bool read_adj = want && positive && pre.deg != 0;
     const int32_t *entry = read_adj ? s.adj + (pre.begin + static_cast<OffT>(scale_draw(r, pre.deg)))
                                     : reinterpret_cast<const int32_t *>(s.xadj);

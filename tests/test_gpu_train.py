@@ -180,6 +180,43 @@ def test_atomic_epoch_matches_first_order_sum(name, d, k):
     assert ok.all()
 
 
+@pytest.fixture
+def tuning():
+    yield G.gosh_set_tuning
+    G.gosh_set_tuning()
+
+
+@pytest.mark.parametrize("name,d,k,max_waves", [("cl3001", 128, 3, 1), ("cl3001", 128, 3, 7), ("er1024", 32, 3, 5),
+                                                ("rmat4096", 64, 4, 100), ("ring24", 8, 15, 2),
+                                                ("cl3001", 512, 2, 1000), ("er1024", 16, 3, 3)])
+def test_few_wavefronts_walk_every_source_once(name, d, k, max_waves, tuning):
+    """When the launch is capped to fewer wavefronts than there are sources to hand out, each
+    wavefront walks a block of consecutive sources (ragged at the end of the graph).  With
+    atomic adds and a small learning rate the result is the sequential one to first order, so a
+    source that was skipped or taken twice shows as an error of the size of its own step; with
+    lr = 0 nothing may move."""
+    n, xadj, adj = GRAPHS[name]
+    lr = 1e-3
+    say(f"[blocks] graph={name} n={n} d={d} k={k} max_waves={max_waves}")
+    tuning(max_waves=max_waves)
+    g, keep = upload(n, xadj, adj, False)
+    M0 = start_matrix(n, d, 9, 0.5)
+    M = torch.from_numpy(M0).to(DEV)
+    G.gosh_train_epoch(g, M, k, 0.0, 21, 2, 0, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(M.cpu().numpy(), M0)
+    want = M0.copy()
+    O.train_epoch(xadj, adj, want, k, lr, 21, 2, 0)
+    G.gosh_train_epoch(g, M, k, lr, 21, 2, 0, G.GOSH_FLAG_ATOMIC_ADDS)
+    torch.cuda.synchronize()
+    got = M.cpu().numpy().astype(np.float64)
+    step = np.abs(want.astype(np.float64) - M0).max(axis=1)
+    err = np.abs(got - want).max(axis=1)
+    ok = err <= 0.02 * step + 2e-7 * np.abs(M0).max()
+    say(f"      rows agreeing: {ok.mean():.4f}, worst err/step {np.max(err / np.maximum(step, 1e-30)):.3e}")
+    assert ok.all()
+
+
 def test_parallel_epoch_stays_within_the_reach_of_its_updates():
     """A Hogwild epoch on a small graph races on nearly every row (all sources are in
     flight at once), so rows cannot be compared one by one; what must hold is that no

@@ -73,7 +73,7 @@ def test_pair_level_rule():
 def test_tuning_record_round_trip():
     """gosh_set_tuning / gosh_get_tuning: defaults, a change, range checks, back to defaults."""
     defaults = G.gosh_tuning_defaults()
-    assert defaults == dict(plain_rows=0, max_waves=1 << 22, hot_inv_eps=64, hot_all_inv_eps=4,
+    assert defaults == dict(plain_rows=0, max_waves=1 << 18, hot_inv_eps=64, hot_all_inv_eps=4,
                             hot_min_degree=0, pair_level_min_n=1 << 22)
     assert G.gosh_get_tuning() == defaults
     try:
