@@ -184,9 +184,8 @@ struct SgdArgs {
   int32_t k_neg;    // sample t of a source is a positive iff t % (k_neg + 1) == 0
   int32_t samples;  // samples per source: k_neg + 1 per round
   float lr;
-  int64_t active_waves;      // wavefronts that take part; the rest of the grid exits at once
-  int64_t sources_per_wave;  // each of them walks this many consecutive sources (a multiple of
-                             // the lane groups per wavefront)
+  int64_t sources_per_block;  // consecutive sources that one workgroup walks (a multiple of
+                              // the sources that its wavefronts take per turn)
 };
 
 constexpr int kChunk = 4;  // sample rows in flight per source
@@ -299,15 +298,16 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
   if (SEQ && (threadIdx.x >= 64 || blockIdx.x != 0)) return;
   const bool group_on = !SEQ || lane < LPG;
 
-  const int64_t wave = blockIdx.x * static_cast<int64_t>(blockDim.x / 64) + (threadIdx.x >> 6);
-  if (!SEQ && wave >= a.active_waves) return;
-  // A wavefront walks a block of consecutive sources, kGroupsPerWave at a time, so that the
-  // sources of an epoch are taken up in ascending order (wavefronts start in the order of their
-  // index) however many of them one wavefront walks.  `n` is the end of this wavefront's block.
-  const int64_t first_of_wave = SEQ ? 0 : wave * a.sources_per_wave;
-  const int64_t n =
-      SEQ ? w.count() : std::min<int64_t>(w.count(), first_of_wave + a.sources_per_wave);
-  const int64_t stride = SEQ ? 1 : kGroupsPerWave;
+  // A workgroup walks a block of consecutive sources: in each turn its wavefronts take one load
+  // of kGroupsPerWave sources each, next to each other.  Workgroups start in the order of their
+  // index, so the sources of an epoch are taken up in ascending order in time however many of
+  // them one wavefront walks, and neighbouring sources (whose neighbour lists share cache
+  // lines) are handled on one compute unit at one time.  `n` is the end of the block.
+  const int64_t waves_per_block = SEQ ? 1 : blockDim.x / 64;
+  const int64_t block_lo = SEQ ? 0 : blockIdx.x * a.sources_per_block;
+  const int64_t first_of_wave = block_lo + (SEQ ? 0 : (threadIdx.x >> 6) * kGroupsPerWave);
+  const int64_t n = SEQ ? w.count() : std::min<int64_t>(w.count(), block_lo + a.sources_per_block);
+  const int64_t stride = SEQ ? 1 : waves_per_block * kGroupsPerWave;
   const int64_t first = first_of_wave + (SEQ ? 0 : lane / LPG);
   const int32_t d = a.d;
   const int32_t per_round = a.k_neg + 1;
@@ -514,22 +514,23 @@ __global__ __launch_bounds__(256) void sgd_kernel(W w, SgdArgs a) {
 //   otherwise, d  > 64     32-bit agent-scope units interleaved over LPG = pow2ceil(d/4)
 //                          lanes (<= 64), four or eight units per lane
 // Each of them runs concurrently (seq = false) or as one lane group (seq = true).
-// `a.active_waves` and `a.sources_per_wave` are filled in here from `count`.
+// `a.sources_per_block` is filled in here from `count`.
 template <class W>
 struct SgdLauncher {
   template <class P, int LPG, int UPL>
   static void run(const W &w, SgdArgs a, int64_t count, bool seq, int64_t max_waves, hipStream_t st) {
     constexpr int kWavesPerBlock = 4;
     constexpr int kGroupsPerWave = 64 / LPG;
-    const int64_t turns = (count + kGroupsPerWave - 1) / kGroupsPerWave;  // wavefront-loads of sources
-    const int64_t per_wave = std::max<int64_t>((turns + max_waves - 1) / max_waves, 1);
-    const int64_t waves = std::max<int64_t>((turns + per_wave - 1) / per_wave, 1);
-    a.active_waves = waves;
-    a.sources_per_wave = per_wave * kGroupsPerWave;
+    constexpr int64_t kPerTurn = kWavesPerBlock * kGroupsPerWave;  // sources a workgroup takes per turn
+    const int64_t turns = std::max<int64_t>((count + kPerTurn - 1) / kPerTurn, 1);
+    const int64_t max_blocks = std::max<int64_t>(max_waves / kWavesPerBlock, 1);
+    const int64_t per_block = (turns + max_blocks - 1) / max_blocks;  // turns of one workgroup
+    const int64_t blocks64 = (turns + per_block - 1) / per_block;
+    a.sources_per_block = per_block * kPerTurn;
     if (seq) {
       hipLaunchKernelGGL((sgd_kernel<P, LPG, UPL, W, true>), dim3(1), dim3(64), 0, st, w, a);
     } else {
-      const int blocks = static_cast<int>((waves + kWavesPerBlock - 1) / kWavesPerBlock);
+      const int blocks = static_cast<int>(blocks64);
       hipLaunchKernelGGL((sgd_kernel<P, LPG, UPL, W, false>), dim3(blocks), dim3(256), 0, st, w, a);
     }
   }
