@@ -62,10 +62,11 @@ def test_full_size_sample_stream_bit_exact(big):
     assert np.array_equal(out.cpu().numpy(), want)
 
 
-def test_full_size_hogwild_epoch_rows(big):
+@pytest.mark.parametrize("D", [128, 32])  # the benchmark's kernel, and the 128-bit small-dimension one
+def test_full_size_hogwild_epoch_rows(big, D):
     n, csr, xadj, adj = big
     g = G.csr_view(n, csr.xadj, csr.adj)
-    seed, epoch, lr, scale = 1, 3, 1e-3, 48.0
+    seed, epoch, lr, scale = 1, 3, 1e-3, 48.0 * D / 128
     M = torch.empty(n, D, dtype=torch.float32, device=DEV)
     G.gosh_init_embedding(M, seed, 0)
     torch.cuda.synchronize()
@@ -124,7 +125,11 @@ def test_full_size_hogwild_epoch_rows(big):
     frac_bad = bad / len(rows)
     say(f"[full] rows off by more than 2% of their own step: {bad}/{len(rows)} "
         f"(worst agreeing row: {worst_ok:.2e} of its step)")
-    assert frac_bad <= 0.03
+    # Rows that miss are rows that lost an update to a race, which the method tolerates: two
+    # sources in flight at once that touch the same cold row.  Their share follows the rows in
+    # flight -- resident wavefronts x sources per wavefront (2 at d = 128, 8 at d = 32) x K + 2
+    # rows each, out of n: about 0.5 % and 2 % here (observed 0.8 % and 2.2 %).
+    assert frac_bad <= (0.03 if D == 128 else 0.05)
 
 
 def test_full_size_coarsening(big):
