@@ -267,8 +267,8 @@ struct ChunkPos {
 //   result), with whatever policy, geometry and hot-row mode it is instantiated and called
 //   with: all accesses to the matrix then come from one wavefront in program order, and the
 //   memory system keeps the accesses of a wavefront to one address in that order, so stores
-//   and atomic adds alike take effect in the order of Alg. 3.  Otherwise lane groups stride
-//   over the sources.
+//   and atomic adds alike take effect in the order of Alg. 3.  Otherwise every workgroup
+//   walks a block of consecutive sources, its lane groups working side by side.
 //
 // Sampling is independent of the matrix (the draws are counter-based), so it runs ahead of
 // the updates as a three-stage pipeline over chunks of kChunk samples: while the rows of
