@@ -59,9 +59,11 @@ def test_random_cases_match_the_oracle(sweep_seed):
         M = torch.from_numpy(M0.copy()).to(DEV)
         G.gosh_train_epoch(g, M, k, lr, seed, epoch, level, G.GOSH_FLAG_SEQUENTIAL)
         torch.cuda.synchronize()
-        want = M0.copy()
-        O.train_epoch(xadj, adj, want, k, lr, seed, epoch, level)
-        assert rel_err(M.cpu().numpy(), want) <= 1e-5
+        # (rows this long can make the epoch ill-conditioned in the oracle itself, as in the
+        # rotation below: the bar follows the oracle's measured sensitivity there, 1e-5 elsewhere)
+        want, sens = oracle_sensitivity(lambda X: O.train_epoch(xadj, adj, X, k, lr, seed, epoch, level), M0)
+        err, bar = rel_err(M.cpu().numpy(), want), conditioned_bar(sens)
+        assert err <= bar, (err, bar, sens, scale, lr)
         # the concurrent kernels (default mix, plain stores, atomic adds) move nothing at lr = 0
         for flags in (0, G.GOSH_FLAG_PLAIN_STORES, G.GOSH_FLAG_ATOMIC_ADDS):
             M = torch.from_numpy(M0.copy()).to(DEV)
