@@ -140,9 +140,9 @@ struct RowAgent128 {
     return u;
   }
   static __device__ __forceinline__ void store(float *p, const Unit<4> &u) {
-    // the no-op keeps the next instruction from overwriting the data registers while the
-    // store still reads them
-    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" : : "v"(p), "v"(u.v) : "memory");
+    // A store of more than 64 bits still reads its data registers for two wait states after
+    // it issues; the compiler pads its own stores and cannot see into this one.
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(u.v) : "memory");
   }
   static __device__ __forceinline__ void wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
   static __device__ __forceinline__ void settle(Unit<4> &u) { asm volatile("" : "+v"(u.v)); }

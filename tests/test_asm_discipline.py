@@ -1,7 +1,9 @@
 """The explicit 128-bit device-scope loads of RowAgent128 are not counted by the compiler's
 own wait insertion: the kernel waits for them itself (P::wait_all) before the first use
 (P::settle).  That discipline only holds if the compiler puts no instruction that touches a
-load's destination registers between the load and the wait -- no copy, no spill.  This test
+load's destination registers between the load and the wait -- no copy, no spill.  The explicit
+128-bit stores likewise carry their own two wait states (s_nop 1), which the compiler cannot add
+to an instruction it does not see.  This test
 compiles the two translation units that instantiate the SGD kernel to assembly (device pass
 only, no GPU needed) and checks exactly that, for every RowAgent128 instantiation."""
 import os
@@ -29,6 +31,7 @@ def violations(path):
     bad = []
     inside = False
     pending = {}
+    stores = []  # line of the last explicit store while its s_nop has not been seen, else None
     for number, line in enumerate(open(path), 1):
         text = line.strip()
         m = re.match(r"^(_ZN4gosh10sgd_kernel\S*):", text)
@@ -44,6 +47,18 @@ def violations(path):
             pending = {}
             continue
         tokens = re.findall(r"v\[\d+:\d+\]|v\d+", text)
+        if op == "global_store_dwordx4" and " sc1" in text:
+            stores.append(number)
+            continue
+        if stores and stores[-1] is not None and op != "s_nop":
+            bad.append(f"{os.path.basename(path)}:{number}: explicit store not followed by its wait states: {text}")
+            stores[-1] = None
+            continue
+        if op == "s_nop" and stores and stores[-1] is not None:
+            if text.split()[1] != "1":
+                bad.append(f"{os.path.basename(path)}:{number}: {text} after an explicit 128-bit store (two wait states are needed)")
+            stores[-1] = None
+            continue
         if op == "global_load_dwordx4" and " sc1" in text:
             loads += 1
             for reg in registers(tokens[0]):
