@@ -170,8 +170,10 @@ def csr_view(n: int, xadj: torch.Tensor, adj: torch.Tensor) -> gosh_csr:
         raise TypeError("xadj must be int32/int64 and adj int32")
     if xadj.numel() != n + 1 or not xadj.is_contiguous() or not adj.is_contiguous():
         raise ValueError("xadj must hold n+1 contiguous offsets, adj must be contiguous")
-    return gosh_csr(n, adj.numel(), xadj.data_ptr(), adj.data_ptr() if adj.numel() else None,
+    view = gosh_csr(n, adj.numel(), xadj.data_ptr(), adj.data_ptr() if adj.numel() else None,
                     1 if xadj.dtype == torch.int64 else 0)
+    view._tensors = (xadj, adj)  # the view holds raw pointers: keep their memory alive with it
+    return view
 
 
 def _matrix(M: torch.Tensor, name: str):
