@@ -260,7 +260,10 @@ int gosh_sample_epoch(const gosh_csr *g_dev, int32_t k_neg, uint64_t seed, uint3
  * negatives).  No positive update for a vertex without neighbours; a negative equal
  * to the source applies no update.  Sources run concurrently without locks (Sec. 3.1);
  * the launch is the epoch barrier.  With GOSH_FLAG_SEQUENTIAL the sources are taken one
- * by one in ascending id, which is deterministic.  In concurrent mode the default is a
+ * by one in ascending id, which is deterministic.  In concurrent mode the sources are
+ * handed out in ascending id too (workgroups start in the order of their index and each walks
+ * a block of consecutive sources), so an epoch sweeps the graph in the order of the sequential
+ * one, a window of concurrently running sources wide.  The default write path is a
  * mix: rows likely to be held by several wavefronts at once (every row of a small
  * graph, high-degree vertices of a large one) receive atomic adds of the step, the
  * others plain stores; GOSH_FLAG_PLAIN_STORES / GOSH_FLAG_ATOMIC_ADDS force one kind.
