@@ -121,8 +121,12 @@ def _power_law_cdf(n: int, m: int, gamma: float, device) -> torch.Tensor:
             else:
                 hi = mid
     w = (idx + hi) ** (-alpha)
-    cdf = torch.cumsum(w, 0)
-    return cdf / cdf[-1]
+    # The running sum is taken on the host: a device scan adds its partial sums in an order
+    # that depends on timing, so its fp64 result differs in the last bits from run to run, and
+    # among billions of draws a few then land on the other side of a boundary.  The graph must
+    # be a function of the seed alone.
+    cdf = torch.cumsum(w.cpu(), 0)
+    return (cdf / cdf[-1]).to(device)
 
 
 def chung_lu(n: int, m: int, seed: int, gamma=2.1, device="cpu", permute=True,
