@@ -41,16 +41,17 @@ def progress(msg):
         pass
 
 
-@pytest.mark.timeout(600)
-def test_config2_hogwild_aucroc_within_a_hundredth_of_the_oracle():
-    n, d, k, lr0, epochs, seed = 1 << 20, 128, 3, 0.045, 60, 1
+def hogwild_against_the_oracle(tag, d, lr0, epochs):
+    """Both sides on the config's graph; returns (oracle held-out, oracle fit, gpu held-out, gpu fit,
+    oracle max |entry|, gpu max |entry|)."""
+    n, k, seed = 1 << 20, 3, 1
     t0 = time.time()
     edges = graphgen.rmat(20, 1 << 24, seed, device=DEV).cpu()
     train, test = graphgen.holdout_split(edges, 0.1, 1001)
     csr = graphgen.to_csr(n, train)
     xadj, adj = csr.xadj.numpy().astype(np.int64), csr.adj.numpy()
     deg = np.diff(xadj)
-    progress(f"[cfg2] graph: {len(edges)} edges, {len(train)} kept, max degree {deg.max()}, "
+    progress(f"[{tag}] graph: {len(edges)} edges, {len(train)} kept, max degree {deg.max()}, "
              f"{(deg == 0).mean():.2f} isolated, {time.time() - t0:.1f}s")
     # link prediction on a sample of the pairs (the whole edge set is 15 M pairs)
     rng = np.random.default_rng(0)
@@ -67,25 +68,43 @@ def test_config2_hogwild_aucroc_within_a_hundredth_of_the_oracle():
     top_gpu, bad_gpu = G.gosh_matrix_check(M)
     assert bad_gpu == 0
     Mg = M.cpu().numpy()
-    progress(f"[cfg2] gpu: {epochs} epochs done, max |entry| {top_gpu:.3e}")
+    progress(f"[{tag}] gpu: {epochs} epochs done, max |entry| {top_gpu:.3e}")
 
     Mo = O.init_embedding(n, d, seed, 0)
     t1 = time.time()
     for j in range(epochs):
         O.train_epoch(xadj, adj, Mo, k, O.lr(lr0, j, epochs), seed, j, 0)
         if j % 5 == 4:
-            progress(f"[cfg2] oracle: epoch {j + 1}/{epochs}, {time.time() - t1:.0f}s")
+            progress(f"[{tag}] oracle: epoch {j + 1}/{epochs}, {time.time() - t1:.0f}s")
     assert np.isfinite(Mo).all()
     top_or = float(np.abs(Mo).max())
 
     held_o, fit_o = aucroc(Mo, sets)
-    progress(f"[cfg2] oracle AUCROC held-out {held_o:.4f} fit {fit_o:.4f}, max |entry| {top_or:.3e}")
+    progress(f"[{tag}] oracle AUCROC held-out {held_o:.4f} fit {fit_o:.4f}, max |entry| {top_or:.3e}")
     held_g, fit_g = aucroc(Mg, sets)
-    progress(f"[cfg2] gpu    AUCROC held-out {held_g:.4f} fit {fit_g:.4f}, max |entry| {top_gpu:.3e}, "
+    progress(f"[{tag}] gpu    AUCROC held-out {held_g:.4f} fit {fit_g:.4f}, max |entry| {top_gpu:.3e}, "
              f"total {time.time() - t0:.0f}s")
+    return held_o, fit_o, held_g, fit_g, top_or, top_gpu
+
+
+@pytest.mark.timeout(600)
+def test_config2_hogwild_aucroc_within_a_hundredth_of_the_oracle():
+    held_o, fit_o, held_g, fit_g, top_or, top_gpu = hogwild_against_the_oracle("cfg2", 128, 0.045, 60)
     assert held_o > 0.6  # far from chance, even in this unstable regime
     assert abs(held_g - held_o) <= 0.01
     assert abs(fit_g - fit_o) <= 0.01
     # the runaway rows run away alike: the largest entry agrees within a quarter (observed: 0.2 %; it is
     # the end of an exponential growth that differs by the order of the concurrent updates)
     assert 0.8 <= top_gpu / top_or <= 1.25
+
+
+@pytest.mark.timeout(600)
+def test_config2_graph_at_d32_hogwild_aucroc_within_a_hundredth_of_the_oracle():
+    """The same graph at d = 32: the 128-bit small-dimension kernel with its mix of plain stores
+    and wavefront-wide atomic adds (at 2^20 vertices the degree rule, not the all-rows rule,
+    decides which rows are hot), end to end.  lr0 = 0.025 over 100 epochs: a schedule under which
+    the method is stable on this graph and learns it (held-out AUCROC 0.88 on both sides)."""
+    held_o, fit_o, held_g, fit_g, top_or, top_gpu = hogwild_against_the_oracle("cfg2 d32", 32, 0.025, 100)
+    assert held_o > 0.6
+    assert abs(held_g - held_o) <= 0.01
+    assert abs(fit_g - fit_o) <= 0.01
